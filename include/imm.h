@@ -1,0 +1,233 @@
+/* imm.h -- C ABI of the MI355X matmul-sumcheck prover.
+ *
+ * What it proves.  The audit step of the paper (section 5.2, item 2 of the VC
+ * statement; the call F_theta* inside the VC algorithm of the appendix) has to
+ * show that the reference model's continuous transformations -- in practice its
+ * matrix products -- were computed from the committed operands.  The paper
+ * leaves the (Prove, Vrfy) pair abstract (section 2.2) and uses hash commitments
+ * (section 2.1).  This library instantiates Prove for one statement "C = A.B"
+ * as a Fiat-Shamir sumcheck over the Goldilocks field p = 2^64 - 2^32 + 1:
+ *
+ *   C~(rx, ry) = sum_{j in {0,1}^delta} A~(rx, j) * B~(j, ry)
+ *
+ * A is m x d (int16 activations), B is d x n (int8 weights), C is m x n (int64),
+ * all row-major.  mu, delta, nu = ceil(log2) of m, d, n; dimensions are padded
+ * to powers of two by virtual zeros.  T~ is the multilinear extension with the
+ * FIRST variable bound to the MOST significant index bit.  Signed integers are
+ * mapped to x mod p.  Every field element that crosses this interface is the
+ * canonical residue in [0, p), stored as a little-endian uint64_t.
+ *
+ * Transcript (SHA-256): a 32-byte state s.
+ *   init      s = SHA256("IMM-FS-v1")
+ *   absorb    s = SHA256(s || tag[4] || u64le(len) || data)
+ *   challenge for ctr = 0,1,..: h = SHA256(s || "chal" || u32le(ctr));
+ *             v = u64le(h[0..8)); accept when v < p and set s = h.
+ * Proof schedule: absorb "shap" (m,d,n as 3 x u64le), "comA", "comB", "comC"
+ * (the three digests); squeeze rx[mu] then ry[nu]; absorb "clmC" (c0); for each
+ * round k = 1..delta absorb "rnd " (g_k(0), g_k(1), g_k(2)) and squeeze r_k;
+ * absorb "fin " (vA, vB).
+ *
+ * Pointers are marked HOST or DEVICE.  The caller owns every buffer it passes;
+ * inputs are never modified.  The library allocates device memory only inside an
+ * imm_ctx and frees it in imm_ctx_destroy.  `stream` is a hipStream_t passed as
+ * void* (NULL = the default stream).  No exception or abort crosses this ABI:
+ * every call returns an int, 0 for success / ACCEPT, negative for a usage or
+ * runtime error, positive (imm_verify only) for a REJECT reason.
+ */
+#ifndef IMM_H
+#define IMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define IMM_MAX_ROUNDS 32     /* largest supported ceil(log2(dimension)) */
+#define IMM_PROOF_VERSION 1u
+
+/* element types of a table handed to the library */
+typedef enum imm_dtype {
+    IMM_I8 = 1,    /* int8_t  */
+    IMM_I16 = 2,   /* int16_t */
+    IMM_I64 = 3,   /* int64_t */
+    IMM_F64P = 4   /* uint64_t, canonical Goldilocks residue (already encoded) */
+} imm_dtype;
+
+/* error codes (negative) */
+#define IMM_OK 0
+#define IMM_E_NULL (-1)    /* a required pointer is NULL */
+#define IMM_E_SHAPE (-2)   /* zero dimension, dimension > 2^IMM_MAX_ROUNDS, ld < cols, bad count */
+#define IMM_E_DTYPE (-3)   /* dtype not valid for this argument */
+#define IMM_E_NOMEM (-4)   /* device or host allocation failed */
+#define IMM_E_HIP (-5)     /* a HIP runtime call failed; see imm_last_error() */
+#define IMM_E_STATE (-6)   /* nothing to fetch / context not in the required state */
+
+/* reject reasons (positive, imm_verify only) -- the paper's "output bottom" */
+#define IMM_REJ_ROUND_SUM 1  /* g_k(0) + g_k(1) != running claim; round in *fail_round (1-based) */
+#define IMM_REJ_FINAL 2      /* last claim != vA * vB */
+#define IMM_REJ_OPEN_A 3     /* vA != A~(rx || r) recomputed from the supplied A */
+#define IMM_REJ_OPEN_B 4     /* vB != B~(r || ry) */
+#define IMM_REJ_OPEN_C 5     /* c0 != C~(rx || ry) */
+#define IMM_REJ_COMMIT 6     /* a supplied matrix does not hash to its committed digest */
+#define IMM_REJ_FORMAT 7     /* header does not match the shapes, or a word >= p */
+
+/* Hash commitment of one matrix (paper section 2.1: c = Hash(m); no blinding salt).
+ * digest = SHA256("IMM-COMMIT-v1" || u32le(dtype) || u64le(rows) || u64le(cols)
+ *                 || leaf_0 || leaf_1 || ...),
+ * leaf_t = SHA256 of the t-th 1 MiB slice of the raw row-major little-endian bytes. */
+typedef struct imm_commit1 {
+    uint8_t digest[32];
+    uint64_t rows, cols;
+    uint32_t dtype;   /* imm_dtype of the committed raw integers */
+    uint32_t _pad;
+} imm_commit1;
+
+typedef struct imm_commit {
+    imm_commit1 A, B, C;
+} imm_commit;
+
+/* One proof.  g[3*(k-1)+t] = g_k(t) for round k = 1..delta, t = 0,1,2; unused
+ * entries are zero.  c0 = claimed C~(rx, ry); vA = A~(rx, r); vB = B~(r, ry). */
+typedef struct imm_proof {
+    uint32_t version, mu, delta, nu;
+    uint64_t c0;
+    uint64_t vA, vB;
+    uint64_t g[3 * IMM_MAX_ROUNDS];
+} imm_proof;
+
+/* One statement of a batch (see imm_sumcheck_matmul_prove_batch). */
+typedef struct imm_matmul_desc {
+    const void* A_dev;  /* DEVICE, m x d row-major, dtype dtA (IMM_I16 or IMM_F64P) */
+    const void* B_dev;  /* DEVICE, d x n row-major, dtype dtB (IMM_I8 or IMM_F64P) */
+    uint32_t dtA, dtB;
+    uint64_t m, d, n;
+    const imm_commit* com; /* HOST */
+} imm_matmul_desc;
+
+typedef struct imm_ctx imm_ctx; /* opaque; owns device scratch, a pinned staging page, events */
+
+/* Create a context on HIP device `device`.  `scratch_bytes` is a hint: that much
+ * device memory is reserved up front (0 = grow on demand; buffers grow, never
+ * shrink, so a warm-up call with the largest shapes makes later calls
+ * allocation-free).  Errors: IMM_E_NULL, IMM_E_HIP, IMM_E_NOMEM. */
+int imm_ctx_create(imm_ctx** out, int device, size_t scratch_bytes);
+int imm_ctx_destroy(imm_ctx* ctx);
+
+/* Text of the last HIP/runtime error seen by the calling thread ("" if none). */
+const char* imm_last_error(void);
+
+/* Write the initial transcript state SHA256("IMM-FS-v1") into state[32] (HOST). */
+int imm_fs_init(uint8_t state[32]);
+
+/* Hash-commit the three matrices of a statement (paper section 2.1 and the model
+ * commitment of section 5.4 "Setup").  A, B, C are HOST pointers to row-major
+ * int16 / int8 / int64 arrays; any of them may be NULL, in which case that entry
+ * of *out is left untouched.  CPU only; not part of the timed prover.
+ * Errors: IMM_E_NULL (out), IMM_E_SHAPE. */
+int imm_commit_matmul(const int16_t* A, const int8_t* B, const int64_t* C,
+                      uint64_t m, uint64_t d, uint64_t n, imm_commit* out);
+
+/* Field-encoding pass: dst[i] = src[i] mod p for `count` elements.
+ * src: DEVICE, dtype IMM_I8 / IMM_I16 / IMM_I64.  dst: DEVICE, count x uint64_t.
+ * Asynchronous on `stream`.  Used to widen weights once at deployment so that
+ * proofs can take them as IMM_F64P.  Errors: IMM_E_NULL, IMM_E_DTYPE, IMM_E_HIP. */
+int imm_encode(imm_ctx* ctx, void* stream, const void* src_dev, imm_dtype dtype,
+               uint64_t count, uint64_t* dst_dev);
+
+/* Multilinear-extension evaluation T~(pt_rows || pt_cols) of a rows x cols table
+ * with leading dimension ld (elements).  table_dev: DEVICE, any imm_dtype.
+ * pt_rows: HOST, ceil(log2(rows)) canonical field elements (first = row MSB);
+ * pt_cols: HOST, ceil(log2(cols)) elements; either may be NULL when its count is 0.
+ * *out_host (HOST) receives the canonical value; the call synchronises `stream`.
+ * Errors: IMM_E_NULL, IMM_E_SHAPE, IMM_E_DTYPE, IMM_E_NOMEM, IMM_E_HIP. */
+int imm_mle_eval(imm_ctx* ctx, void* stream, const void* table_dev, imm_dtype dt,
+                 uint64_t rows, uint64_t cols, uint64_t ld,
+                 const uint64_t* pt_rows, const uint64_t* pt_cols, uint64_t* out_host);
+
+/* Prove C = A.B for one statement (the schedule at the top of this file).
+ * A_dev: DEVICE m x d, IMM_I16 or IMM_F64P.  B_dev: DEVICE d x n, IMM_I8 or
+ * IMM_F64P.  Raw integer operands are widened into context scratch by the
+ * encoding pass first; IMM_F64P operands are streamed as they are.
+ * com: HOST, the statement's commitments (only the digests are read).
+ * transcript_state: HOST, 32 bytes, in = chained state (imm_fs_init for a fresh
+ * transcript), out = state after this proof.  out_host: HOST.
+ * c0 is computed as sum_j a[j] b[j], which equals C~(rx, ry) iff C = A.B.
+ * Synchronous with respect to out_host; kernels run on `stream`.
+ * Errors: IMM_E_NULL, IMM_E_SHAPE, IMM_E_DTYPE, IMM_E_NOMEM, IMM_E_HIP. */
+int imm_sumcheck_matmul_prove(imm_ctx* ctx, void* stream,
+                              const void* A_dev, imm_dtype dtA,
+                              const void* B_dev, imm_dtype dtB,
+                              uint64_t m, uint64_t d, uint64_t n,
+                              const imm_commit* com,
+                              uint8_t transcript_state[32], imm_proof* out_host);
+
+/* `count` proofs in order.  chained = 1: one transcript threads through all of
+ * them (proof t+1 starts from the state after proof t), as for the layers of one
+ * audited request.  chained = 0: every proof starts from the incoming state, as
+ * for independent experts; on return transcript_state holds the state after the
+ * LAST proof, and states_out (HOST, count x 32 bytes, may be NULL) receives the
+ * state after each proof.  A desc with a zero dimension is IMM_E_SHAPE. */
+int imm_sumcheck_matmul_prove_batch(imm_ctx* ctx, void* stream, int count,
+                                    const imm_matmul_desc* descs, int chained,
+                                    uint8_t transcript_state[32], imm_proof* outs_host,
+                                    uint8_t* states_out);
+
+/* One pass of the per-round kernel on caller-owned tables (also the unit that the
+ * prover runs delta times).  a_dev, b_dev: DEVICE, L canonical field elements each,
+ * L a power of two >= 2, modified in place.  If fold_r is non-NULL (HOST, one field
+ * element) the leading variable is first bound to *fold_r:
+ *   x[i] <- x[i] + r (x[i + L/2] - x[i]),  i < L/2,
+ * and the round polynomial is evaluated on the folded tables of length L/2;
+ * otherwise it is evaluated on the tables of length L.  g_host (HOST, 3 words)
+ * receives g(0), g(1), g(2); when the evaluated length is 1 it receives
+ * (a[0], b[0], 0) instead.  Synchronises `stream`. */
+int imm_round_fold_eval(imm_ctx* ctx, void* stream, uint64_t* a_dev, uint64_t* b_dev,
+                        uint64_t L, const uint64_t* fold_r, uint64_t g_host[3]);
+
+/* Verify one proof -- CPU only (the paper's Vrfy; a REJECT is its "bottom").
+ * com: HOST.  transcript_in: HOST 32 bytes.  A, B, C: HOST raw matrices or NULL.
+ * With matrices the digests are recomputed and the three openings c0, vA, vB are
+ * checked by direct evaluation (this stands in for a polynomial-commitment
+ * opening, which hash commitments do not provide); with NULL only the transcript
+ * consistency is checked.  transcript_out (HOST, nullable) receives the state
+ * after the proof on ACCEPT; *fail_round (nullable) the failing round. */
+int imm_verify(const imm_commit* com, const uint8_t transcript_in[32], const imm_proof* proof,
+               const int16_t* A, const int8_t* B, const int64_t* C,
+               uint8_t transcript_out[32], int* fail_round);
+
+/* Test/diagnostic access to the intermediates of the most recent single proof of
+ * this context: which = 0 eqx (2^mu), 1 eqy (2^nu), 2 a = A~(rx, .) (2^delta),
+ * 3 b = B~(., ry) (2^delta), 4 rx, 5 ry, 6 r (the round challenges).  Copies at
+ * most `capacity` words to out_host and stores the available count in *count.
+ * a and b are snapshots taken before the first fold.  Needs IMM_OPT_DEBUG_SNAPSHOTS
+ * set before the proof; IMM_E_STATE otherwise. */
+int imm_debug_fetch(imm_ctx* ctx, int which, uint64_t* out_host, uint64_t capacity, uint64_t* count);
+
+/* Context options. */
+#define IMM_OPT_DEBUG_SNAPSHOTS 1 /* value != 0: keep the intermediates imm_debug_fetch serves (default 0) */
+#define IMM_OPT_WIDEN 2           /* value != 0 (default): raw int8/int16 operands of a proof go through the
+                                     encoding pass and are streamed as 8-byte field elements; value 0: the
+                                     reductions read the narrow integers directly and encode in registers */
+int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value);
+
+/* Per-kernel timing with HIP events on the launch stream.  Kernel ids: */
+#define IMM_K_ENCODE_A 0
+#define IMM_K_ENCODE_B 1
+#define IMM_K_EQ 2
+#define IMM_K_REDUCE_A 3   /* partial MLE of A over its rows (column-wise reduction) */
+#define IMM_K_REDUCE_B 4   /* partial MLE of B over its columns (row-wise reduction) */
+#define IMM_K_ROUND 5      /* evaluate g_k(0,1,2) + fold */
+#define IMM_K_COMBINE 6    /* sum of per-split partial vectors */
+#define IMM_K_COUNT 7
+/* mask: bit k set = time kernel id k (0 = profiling off). */
+int imm_ctx_set_profiling(imm_ctx* ctx, uint32_t mask);
+/* Sum of durations (ms) and number of launches since the last reset. */
+int imm_ctx_kernel_time(imm_ctx* ctx, int kernel_id, uint64_t* launches, double* total_ms);
+int imm_ctx_reset_profiling(imm_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IMM_H */

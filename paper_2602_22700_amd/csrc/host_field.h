@@ -1,0 +1,50 @@
+// Host-side Goldilocks arithmetic (p = 2^64 - 2^32 + 1) for the verifier, the
+// transcript glue and the first claim.  Values are canonical residues in [0, p).
+#pragma once
+#include <cstdint>
+
+namespace imm {
+namespace hf {
+
+constexpr uint64_t P = 0xFFFFFFFF00000001ull;
+constexpr uint64_t INV2 = 0x7FFFFFFF80000001ull;  // (p + 1) / 2
+
+inline uint64_t add(uint64_t a, uint64_t b) {
+    uint64_t s = a + b;
+    return (s < a || s >= P) ? s - P : s;
+}
+inline uint64_t sub(uint64_t a, uint64_t b) { return a >= b ? a - b : a - b + P; }
+inline uint64_t neg(uint64_t a) { return a ? P - a : 0; }
+
+// Reduce a 128-bit value using 2^64 = 2^32 - 1 and 2^96 = -1 (mod p).
+inline uint64_t reduce128(unsigned __int128 x) {
+    uint64_t lo = (uint64_t)x, hi = (uint64_t)(x >> 64);
+    uint64_t hl = hi & 0xFFFFFFFFull, hh = hi >> 32;
+    uint64_t t = lo - hh;
+    if (lo < hh) t -= 0xFFFFFFFFull;            // borrowed 2^64 = p + (2^32 - 1)
+    uint64_t u = (hl << 32) - hl;               // hl * (2^32 - 1)
+    uint64_t s = t + u;
+    if (s < t) s += 0xFFFFFFFFull;              // carried 2^64 = 2^32 - 1 (mod p); cannot carry again
+    return s >= P ? s - P : s;
+}
+inline uint64_t mul(uint64_t a, uint64_t b) { return reduce128((unsigned __int128)a * b); }
+
+inline uint64_t enc(int64_t x) { return x >= 0 ? (uint64_t)x : P - (uint64_t)(-(x + 1)) - 1; }
+
+// value at r of the quadratic through (0,g0), (1,g1), (2,g2)
+inline uint64_t interpolate3(uint64_t g0, uint64_t g1, uint64_t g2, uint64_t r) {
+    uint64_t rm1 = sub(r, 1), rm2 = sub(r, 2);
+    uint64_t l0 = mul(mul(rm1, rm2), INV2);
+    uint64_t l1 = neg(mul(r, rm2));
+    uint64_t l2 = mul(mul(r, rm1), INV2);
+    return add(add(mul(g0, l0), mul(g1, l1)), mul(g2, l2));
+}
+
+inline int ceil_log2(uint64_t n) {
+    int t = 0;
+    while (t < 64 && (1ull << t) < n) ++t;
+    return t;
+}
+
+}  // namespace hf
+}  // namespace imm

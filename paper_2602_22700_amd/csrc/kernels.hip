@@ -1,0 +1,455 @@
+// gfx950 kernels of the matmul sumcheck prover: field encoding, eq-vector build,
+// the two streaming partial-evaluation reductions, and the per-round
+// "evaluate g(0,1,2) + fold" kernel.  Wave size is 64 throughout.
+//
+// The protocol these serve (paper section 5.2 item 2 instantiated as a sumcheck
+// for C = A.B over Goldilocks) and all conventions are stated in include/imm.h.
+#include "kernels.h"
+
+#include "goldilocks.cuh"
+
+namespace imm {
+namespace k {
+namespace {
+
+constexpr int kBlock = 256;  // 4 waves
+constexpr int kWaves = kBlock / 64;
+
+// ------------------------------------------------------------------ helpers
+template <typename S> struct Pair;
+template <> struct Pair<int8_t> { using type = char2; };
+template <> struct Pair<int16_t> { using type = short2; };
+template <> struct Pair<int64_t> { using type = longlong2; };
+template <> struct Pair<uint64_t> { using type = ulonglong2; };
+
+template <typename S> __device__ __forceinline__ uint64_t to_field(S v) { return gl::enc((int64_t)v); }
+template <> __device__ __forceinline__ uint64_t to_field<uint64_t>(uint64_t v) { return v; }
+
+__device__ __forceinline__ uint64_t wave_sum(uint64_t v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = gl::add(v, __shfl_down(v, off, 64));
+    return v;  // valid in lane 0
+}
+
+// Sum of one field element per thread over a block of kBlock threads; result valid in thread 0.
+// `lds` holds kWaves words and may be reused after the call returns (ends with a barrier).
+__device__ __forceinline__ uint64_t block_sum(uint64_t v, uint64_t* lds) {
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint64_t total = 0;
+    if (threadIdx.x == 0) {
+        total = lds[0];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) total = gl::add(total, lds[w]);
+    }
+    __syncthreads();
+    return total;
+}
+
+// ------------------------------------------------------------------ encode
+template <typename S, bool VEC>
+__global__ __launch_bounds__(kBlock) void encode_kernel(const S* __restrict__ src, uint64_t* __restrict__ dst,
+                                                        uint64_t count) {
+    const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+    const uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (VEC) {
+        using V2 = typename Pair<S>::type;
+        const uint64_t pairs = count >> 1;
+        const V2* s2 = reinterpret_cast<const V2*>(src);
+        ulonglong2* d2 = reinterpret_cast<ulonglong2*>(dst);
+        for (uint64_t p = t; p < pairs; p += stride) {
+            V2 v = s2[p];
+            d2[p] = make_ulonglong2(to_field<S>((S)v.x), to_field<S>((S)v.y));
+        }
+        if ((count & 1) && t == 0) dst[count - 1] = to_field<S>(src[count - 1]);
+    } else {
+        for (uint64_t i = t; i < count; i += stride) dst[i] = to_field<S>(src[i]);
+    }
+}
+
+template <typename S>
+hipError_t launch_encode(hipStream_t stream, const void* src, uint64_t count, uint64_t* dst) {
+    if (count == 0) return hipSuccess;
+    const bool vec = (reinterpret_cast<uintptr_t>(src) % (2 * sizeof(S)) == 0) &&
+                     (reinterpret_cast<uintptr_t>(dst) % 16 == 0);
+    const uint64_t items = vec ? (count + 1) / 2 : count;
+    uint64_t blocks = (items + kBlock - 1) / kBlock;
+    if (blocks > 8192) blocks = 8192;
+    if (vec)
+        hipLaunchKernelGGL((encode_kernel<S, true>), dim3((unsigned)blocks), dim3(kBlock), 0, stream,
+                           static_cast<const S*>(src), dst, count);
+    else
+        hipLaunchKernelGGL((encode_kernel<S, false>), dim3((unsigned)blocks), dim3(kBlock), 0, stream,
+                           static_cast<const S*>(src), dst, count);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ eq vectors
+// out[i] = prod_k (bit_k(i) ? r_k : 1 - r_k), bit_1 = most significant bit of i.
+// Each entry is an independent product of t factors: no synchronisation, and the
+// result is the same canonical value the doubling recurrence gives.
+__global__ __launch_bounds__(kBlock) void eq_build2_kernel(Point ptA, int tA, uint64_t* __restrict__ outA, Point ptB,
+                                                           int tB, uint64_t* __restrict__ outB) {
+    uint64_t idx = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t nA = 1ull << tA, nB = 1ull << tB;
+    const Point* pt;
+    uint64_t* out;
+    int t;
+    if (idx < nA) {
+        pt = &ptA; out = outA; t = tA;
+    } else {
+        idx -= nA;
+        if (idx >= nB) return;
+        pt = &ptB; out = outB; t = tB;
+    }
+    uint64_t w = 1;
+    for (int kk = 0; kk < t; ++kk) {
+        uint64_t r = pt->v[kk];
+        uint64_t f = ((idx >> (t - 1 - kk)) & 1) ? r : gl::sub(1, r);
+        w = gl::mul(w, f);
+    }
+    out[idx] = w;
+}
+
+// ------------------------------------------------------------------ reduction over the columns (row-wise)
+// Block = R consecutive rows x one column split.  A lane owns column pairs
+// (2*tid, 2*tid+1) + 512*u of the split, so one wave load covers 1 KiB of a row
+// and the eq pair is loaded once and reused for the R rows.
+template <typename S, int R, bool VEC>
+__global__ __launch_bounds__(kBlock) void reduce_over_cols_kernel(const S* __restrict__ T, uint64_t ld, uint64_t rows,
+                                                                  uint64_t cols, const uint64_t* __restrict__ eq,
+                                                                  uint64_t* __restrict__ partial,
+                                                                  uint64_t cols_per_split) {
+    __shared__ uint64_t lds[kWaves];
+    const uint64_t row0 = (uint64_t)blockIdx.x * R;
+    const uint64_t c_begin = (uint64_t)blockIdx.y * cols_per_split;
+    uint64_t c_end = c_begin + cols_per_split;
+    if (c_end > cols) c_end = cols;
+    const uint64_t span = c_end - c_begin;
+
+    gl::Acc acc[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) gl::acc_clear(acc[r]);
+
+    const S* base = T + row0 * ld + c_begin;
+    const uint64_t* eqb = eq + c_begin;
+    if (VEC) {
+        using V2 = typename Pair<S>::type;
+        const uint64_t npairs = span >> 1;
+        for (uint64_t p = threadIdx.x; p < npairs; p += kBlock) {
+            ulonglong2 e = *reinterpret_cast<const ulonglong2*>(eqb + 2 * p);
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (row0 + r < rows) {
+                    V2 x = *reinterpret_cast<const V2*>(base + r * ld + 2 * p);
+                    gl::acc_mac(acc[r], to_field<S>((S)x.x), e.x);
+                    gl::acc_mac(acc[r], to_field<S>((S)x.y), e.y);
+                }
+            }
+        }
+        if ((span & 1) && threadIdx.x == 0) {
+            uint64_t e = eqb[span - 1];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (row0 + r < rows) gl::acc_mac(acc[r], to_field<S>(base[r * ld + span - 1]), e);
+        }
+    } else {
+        for (uint64_t c = threadIdx.x; c < span; c += kBlock) {
+            uint64_t e = eqb[c];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (row0 + r < rows) gl::acc_mac(acc[r], to_field<S>(base[r * ld + c]), e);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        uint64_t total = block_sum(gl::acc_reduce(acc[r]), lds);
+        if (threadIdx.x == 0 && row0 + r < rows) partial[(uint64_t)blockIdx.y * rows + row0 + r] = total;
+    }
+}
+
+constexpr int kRowsPerBlock = 4;
+
+template <typename S>
+hipError_t launch_over_cols(hipStream_t stream, const void* T, uint64_t rows, uint64_t cols, uint64_t ld,
+                            const uint64_t* eq, uint64_t* partial, Split sp) {
+    const bool vec = (reinterpret_cast<uintptr_t>(T) % (2 * sizeof(S)) == 0) && (ld % 2 == 0) &&
+                     (sp.per_split % 2 == 0) && (reinterpret_cast<uintptr_t>(eq) % 16 == 0);
+    dim3 grid((unsigned)((rows + kRowsPerBlock - 1) / kRowsPerBlock), sp.nsplit);
+    if (vec)
+        hipLaunchKernelGGL((reduce_over_cols_kernel<S, kRowsPerBlock, true>), grid, dim3(kBlock), 0, stream,
+                           static_cast<const S*>(T), ld, rows, cols, eq, partial, sp.per_split);
+    else
+        hipLaunchKernelGGL((reduce_over_cols_kernel<S, kRowsPerBlock, false>), grid, dim3(kBlock), 0, stream,
+                           static_cast<const S*>(T), ld, rows, cols, eq, partial, sp.per_split);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ reduction over the rows (column-wise)
+// A lane owns two adjacent columns; a block walks the rows of its split.  The eq
+// weight of a row is the same for every lane (a scalar load).
+template <typename S, bool VEC>
+__global__ __launch_bounds__(kBlock) void reduce_over_rows_kernel(const S* __restrict__ T, uint64_t ld, uint64_t rows,
+                                                                  uint64_t cols, const uint64_t* __restrict__ eq,
+                                                                  uint64_t* __restrict__ partial,
+                                                                  uint64_t rows_per_split) {
+    const uint64_t r_begin = (uint64_t)blockIdx.y * rows_per_split;
+    uint64_t r_end = r_begin + rows_per_split;
+    if (r_end > rows) r_end = rows;
+    uint64_t* out = partial + (uint64_t)blockIdx.y * cols;
+    if (VEC) {
+        using V2 = typename Pair<S>::type;
+        const uint64_t col = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 2;
+        if (col >= cols) return;
+        gl::Acc a0, a1;
+        gl::acc_clear(a0);
+        gl::acc_clear(a1);
+        if (col + 1 < cols) {
+            const S* p = T + r_begin * ld + col;
+#pragma unroll 4
+            for (uint64_t i = r_begin; i < r_end; ++i, p += ld) {
+                uint64_t e = eq[i];
+                V2 x = *reinterpret_cast<const V2*>(p);
+                gl::acc_mac(a0, to_field<S>((S)x.x), e);
+                gl::acc_mac(a1, to_field<S>((S)x.y), e);
+            }
+            out[col] = gl::acc_reduce(a0);
+            out[col + 1] = gl::acc_reduce(a1);
+        } else {  // last column of an odd-width table
+            for (uint64_t i = r_begin; i < r_end; ++i) gl::acc_mac(a0, to_field<S>(T[i * ld + col]), eq[i]);
+            out[col] = gl::acc_reduce(a0);
+        }
+    } else {
+        const uint64_t col = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+        if (col >= cols) return;
+        gl::Acc a0;
+        gl::acc_clear(a0);
+        for (uint64_t i = r_begin; i < r_end; ++i) gl::acc_mac(a0, to_field<S>(T[i * ld + col]), eq[i]);
+        out[col] = gl::acc_reduce(a0);
+    }
+}
+
+template <typename S>
+hipError_t launch_over_rows(hipStream_t stream, const void* T, uint64_t rows, uint64_t cols, uint64_t ld,
+                            const uint64_t* eq, uint64_t* partial, Split sp) {
+    const bool vec = (reinterpret_cast<uintptr_t>(T) % (2 * sizeof(S)) == 0) && (ld % 2 == 0);
+    const uint64_t lanes = vec ? (cols + 1) / 2 : cols;
+    dim3 grid((unsigned)((lanes + kBlock - 1) / kBlock), sp.nsplit);
+    if (vec)
+        hipLaunchKernelGGL((reduce_over_rows_kernel<S, true>), grid, dim3(kBlock), 0, stream, static_cast<const S*>(T),
+                           ld, rows, cols, eq, partial, sp.per_split);
+    else
+        hipLaunchKernelGGL((reduce_over_rows_kernel<S, false>), grid, dim3(kBlock), 0, stream,
+                           static_cast<const S*>(T), ld, rows, cols, eq, partial, sp.per_split);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ combine / dot
+__global__ __launch_bounds__(kBlock) void combine_kernel(const uint64_t* __restrict__ partial, uint32_t nsplit,
+                                                         uint64_t len, uint64_t padded, uint64_t* __restrict__ out) {
+    const uint64_t j = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (j >= padded) return;
+    uint64_t v = 0;
+    if (j < len)
+        for (uint32_t s = 0; s < nsplit; ++s) v = gl::add(v, partial[(uint64_t)s * len + j]);
+    out[j] = v;
+}
+
+__global__ __launch_bounds__(kBlock) void dot_kernel(const uint64_t* __restrict__ x, const uint64_t* __restrict__ y,
+                                                     uint64_t len, uint64_t* __restrict__ out) {
+    __shared__ uint64_t lds[kWaves];
+    gl::Acc acc;
+    gl::acc_clear(acc);
+    for (uint64_t i = threadIdx.x; i < len; i += kBlock) gl::acc_mac(acc, x[i], y[i]);
+    uint64_t total = block_sum(gl::acc_reduce(acc), lds);
+    if (threadIdx.x == 0) out[0] = total;
+}
+
+// ------------------------------------------------------------------ sumcheck round
+// FOLD = false: pair (i, i + L/2), i < L/2, of the tables as they are.
+// FOLD = true : item i < L/4 reads entries i, i + L/4, i + L/2, i + 3L/4 of each
+// table, binds the leading variable (entries i and i + L/4 are rewritten in place;
+// no other item touches them) and evaluates the next round's pair (i, i + L/4).
+template <bool FOLD>
+__global__ __launch_bounds__(kBlock) void round_kernel(uint64_t* __restrict__ a, uint64_t* __restrict__ b, uint64_t L,
+                                                       uint64_t r, uint64_t* __restrict__ out /*[gridDim.x][3]*/) {
+    __shared__ uint64_t lds[kWaves];
+    const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+    const uint64_t h = L >> 1;
+    uint64_t g0 = 0, g1 = 0, g2 = 0;
+    const uint64_t items = FOLD ? (L >> 2) : h;
+    const uint64_t q = L >> 2;
+    for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < items; i += stride) {
+        uint64_t a0, a1, b0, b1;
+        if (FOLD) {
+            uint64_t x0 = a[i], x1 = a[i + q], x2 = a[i + h], x3 = a[i + h + q];
+            uint64_t y0 = b[i], y1 = b[i + q], y2 = b[i + h], y3 = b[i + h + q];
+            a0 = gl::add(x0, gl::mul(r, gl::sub(x2, x0)));
+            a1 = gl::add(x1, gl::mul(r, gl::sub(x3, x1)));
+            b0 = gl::add(y0, gl::mul(r, gl::sub(y2, y0)));
+            b1 = gl::add(y1, gl::mul(r, gl::sub(y3, y1)));
+            a[i] = a0; a[i + q] = a1;
+            b[i] = b0; b[i + q] = b1;
+        } else {
+            a0 = a[i]; a1 = a[i + h];
+            b0 = b[i]; b1 = b[i + h];
+        }
+        uint64_t a2 = gl::sub(gl::add(a1, a1), a0);  // table value at t = 2: 2*x1 - x0
+        uint64_t b2 = gl::sub(gl::add(b1, b1), b0);
+        g0 = gl::add(g0, gl::mul(a0, b0));
+        g1 = gl::add(g1, gl::mul(a1, b1));
+        g2 = gl::add(g2, gl::mul(a2, b2));
+    }
+    g0 = block_sum(g0, lds);
+    g1 = block_sum(g1, lds);
+    g2 = block_sum(g2, lds);
+    if (threadIdx.x == 0) {
+        out[3 * blockIdx.x + 0] = g0;
+        out[3 * blockIdx.x + 1] = g1;
+        out[3 * blockIdx.x + 2] = g2;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void round_finish_kernel(const uint64_t* __restrict__ part, uint32_t nblk,
+                                                              uint64_t* __restrict__ out3) {
+    __shared__ uint64_t lds[kWaves];
+    uint64_t g0 = 0, g1 = 0, g2 = 0;
+    for (uint32_t i = threadIdx.x; i < nblk; i += kBlock) {
+        g0 = gl::add(g0, part[3 * i]);
+        g1 = gl::add(g1, part[3 * i + 1]);
+        g2 = gl::add(g2, part[3 * i + 2]);
+    }
+    g0 = block_sum(g0, lds);
+    g1 = block_sum(g1, lds);
+    g2 = block_sum(g2, lds);
+    if (threadIdx.x == 0) {
+        out3[0] = g0; out3[1] = g1; out3[2] = g2;
+    }
+}
+
+// Last fold (L == 2): one entry per table remains.
+__global__ void fold_last_kernel(uint64_t* __restrict__ a, uint64_t* __restrict__ b, uint64_t r,
+                                 uint64_t* __restrict__ out3) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    uint64_t va = gl::add(a[0], gl::mul(r, gl::sub(a[1], a[0])));
+    uint64_t vb = gl::add(b[0], gl::mul(r, gl::sub(b[1], b[0])));
+    a[0] = va;
+    b[0] = vb;
+    out3[0] = va; out3[1] = vb; out3[2] = 0;
+}
+
+constexpr uint32_t kMaxRoundBlocks = 2048;
+
+uint32_t round_blocks(uint64_t items) {
+    uint64_t nb = (items + kBlock - 1) / kBlock;
+    if (nb < 1) nb = 1;
+    if (nb > kMaxRoundBlocks) nb = kMaxRoundBlocks;
+    return (uint32_t)nb;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ wrappers
+hipError_t encode(hipStream_t stream, const void* src, int dtype, uint64_t count, uint64_t* dst) {
+    switch (dtype) {
+    case IMM_I8: return launch_encode<int8_t>(stream, src, count, dst);
+    case IMM_I16: return launch_encode<int16_t>(stream, src, count, dst);
+    case IMM_I64: return launch_encode<int64_t>(stream, src, count, dst);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t eq_build2(hipStream_t stream, const Point& ptA, int tA, uint64_t* outA, const Point& ptB, int tB,
+                     uint64_t* outB) {
+    const uint64_t total = (1ull << tA) + (1ull << tB);
+    hipLaunchKernelGGL(eq_build2_kernel, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, ptA,
+                       tA, outA, ptB, tB, outB);
+    return hipGetLastError();
+}
+
+Split plan_over_rows(uint64_t rows, uint64_t cols) {
+    // aim at >= 2048 blocks of 256 lanes; one lane owns two columns
+    const uint64_t col_blocks = ((cols + 1) / 2 + kBlock - 1) / kBlock;
+    uint64_t want = (2048 + col_blocks - 1) / col_blocks;
+    uint64_t per = (rows + want - 1) / want;
+    if (per < 16) per = 16;
+    if (per > rows) per = rows;
+    Split sp;
+    sp.per_split = per;
+    sp.nsplit = (uint32_t)((rows + per - 1) / per);
+    return sp;
+}
+
+Split plan_over_cols(uint64_t rows, uint64_t cols) {
+    // a block covers kRowsPerBlock rows; split the columns until there are >= 2048 blocks,
+    // but keep at least 2048 columns (4 pairs per lane) per split
+    const uint64_t row_blocks = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
+    uint64_t want = (2048 + row_blocks - 1) / row_blocks;
+    uint64_t per = (cols + want - 1) / want;
+    if (per < 2048) per = 2048;
+    per = (per + 511) / 512 * 512;  // whole block passes, and even
+    if (per > cols) per = (cols + 1) / 2 * 2;
+    Split sp;
+    sp.per_split = per;
+    sp.nsplit = (uint32_t)((cols + per - 1) / per);
+    return sp;
+}
+
+hipError_t reduce_over_rows(hipStream_t stream, const void* T, int dtype, uint64_t rows, uint64_t cols, uint64_t ld,
+                            const uint64_t* eq_rows, uint64_t* partial, Split sp) {
+    switch (dtype) {
+    case IMM_I8: return launch_over_rows<int8_t>(stream, T, rows, cols, ld, eq_rows, partial, sp);
+    case IMM_I16: return launch_over_rows<int16_t>(stream, T, rows, cols, ld, eq_rows, partial, sp);
+    case IMM_I64: return launch_over_rows<int64_t>(stream, T, rows, cols, ld, eq_rows, partial, sp);
+    case IMM_F64P: return launch_over_rows<uint64_t>(stream, T, rows, cols, ld, eq_rows, partial, sp);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t reduce_over_cols(hipStream_t stream, const void* T, int dtype, uint64_t rows, uint64_t cols, uint64_t ld,
+                            const uint64_t* eq_cols, uint64_t* partial, Split sp) {
+    switch (dtype) {
+    case IMM_I8: return launch_over_cols<int8_t>(stream, T, rows, cols, ld, eq_cols, partial, sp);
+    case IMM_I16: return launch_over_cols<int16_t>(stream, T, rows, cols, ld, eq_cols, partial, sp);
+    case IMM_I64: return launch_over_cols<int64_t>(stream, T, rows, cols, ld, eq_cols, partial, sp);
+    case IMM_F64P: return launch_over_cols<uint64_t>(stream, T, rows, cols, ld, eq_cols, partial, sp);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t combine(hipStream_t stream, const uint64_t* partial, uint32_t nsplit, uint64_t len, uint64_t padded,
+                   uint64_t* out) {
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((padded + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream,
+                       partial, nsplit, len, padded, out);
+    return hipGetLastError();
+}
+
+hipError_t dot(hipStream_t stream, const uint64_t* x, const uint64_t* y, uint64_t len, uint64_t* out) {
+    hipLaunchKernelGGL(dot_kernel, dim3(1), dim3(kBlock), 0, stream, x, y, len, out);
+    return hipGetLastError();
+}
+
+uint64_t round_scratch_words(uint64_t L) { return 3ull * round_blocks(L / 2); }
+
+hipError_t round(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, bool fold, uint64_t r, uint64_t* out3,
+                 uint64_t* scratch) {
+    if (fold && L == 2) {
+        hipLaunchKernelGGL(fold_last_kernel, dim3(1), dim3(64), 0, stream, a, b, r, out3);
+        return hipGetLastError();
+    }
+    const uint64_t items = fold ? L / 4 : L / 2;
+    const uint32_t nb = round_blocks(items);
+    uint64_t* dst = nb == 1 ? out3 : scratch;
+    if (fold)
+        hipLaunchKernelGGL((round_kernel<true>), dim3(nb), dim3(kBlock), 0, stream, a, b, L, r, dst);
+    else
+        hipLaunchKernelGGL((round_kernel<false>), dim3(nb), dim3(kBlock), 0, stream, a, b, L, r, dst);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || nb == 1) return e;
+    hipLaunchKernelGGL(round_finish_kernel, dim3(1), dim3(kBlock), 0, stream, scratch, nb, out3);
+    return hipGetLastError();
+}
+
+}  // namespace k
+}  // namespace imm

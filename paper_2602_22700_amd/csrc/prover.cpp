@@ -1,0 +1,513 @@
+// Host orchestration of the prover: context, scratch buffers, launch sequence,
+// transcript glue and proof assembly.  The arithmetic runs in kernels.hip; the
+// host only hashes and moves a few words per round.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/imm.h"
+#include "host_field.h"
+#include "kernels.h"
+#include "transcript.h"
+
+namespace imm {
+
+static thread_local std::string g_last_error;
+
+static int fail_hip(hipError_t e, const char* what) {
+    g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+    return IMM_E_HIP;
+}
+
+#define IMM_HIP(call)                                       \
+    do {                                                    \
+        hipError_t e_ = (call);                             \
+        if (e_ != hipSuccess) return fail_hip(e_, #call);   \
+    } while (0)
+
+// A device buffer that only grows.
+struct DevBuf {
+    void* p = nullptr;
+    size_t bytes = 0;
+    int ensure(size_t need) {
+        if (need <= bytes) return IMM_OK;
+        if (p) {
+            hipError_t e = hipFree(p);
+            p = nullptr;
+            bytes = 0;
+            if (e != hipSuccess) return fail_hip(e, "hipFree");
+        }
+        size_t rounded = (need + 255) & ~size_t(255);
+        hipError_t e = hipMalloc(&p, rounded);
+        if (e != hipSuccess) {
+            p = nullptr;
+            (void)hipGetLastError();
+            g_last_error = "hipMalloc failed";
+            return e == hipErrorOutOfMemory ? IMM_E_NOMEM : fail_hip(e, "hipMalloc");
+        }
+        bytes = rounded;
+        return IMM_OK;
+    }
+    void release() {
+        if (p) (void)hipFree(p);
+        p = nullptr;
+        bytes = 0;
+    }
+    uint64_t* u64() const { return static_cast<uint64_t*>(p); }
+};
+
+struct Profiler {
+    static constexpr size_t kPool = 1024;  // event pairs
+    uint32_t mask = 0;
+    std::vector<hipEvent_t> ev;
+    struct Rec { int id; size_t first; };
+    std::vector<Rec> recs;
+    double total_ms[IMM_K_COUNT] = {};
+    uint64_t launches[IMM_K_COUNT] = {};
+
+    bool wants(int id) const { return (mask >> id) & 1u; }
+    int begin(int id, hipStream_t s) {
+        if (!wants(id)) return IMM_OK;
+        if (ev.empty()) {
+            ev.resize(2 * kPool);
+            for (auto& e : ev) IMM_HIP(hipEventCreate(&e));
+        }
+        if (recs.size() >= kPool) {
+            int rc = flush();
+            if (rc) return rc;
+        }
+        size_t first = 2 * recs.size();
+        recs.push_back({id, first});
+        IMM_HIP(hipEventRecord(ev[first], s));
+        return IMM_OK;
+    }
+    int end(int id, hipStream_t s) {
+        if (!wants(id) || recs.empty()) return IMM_OK;
+        IMM_HIP(hipEventRecord(ev[recs.back().first + 1], s));
+        return IMM_OK;
+    }
+    int flush() {
+        for (const Rec& r : recs) {
+            IMM_HIP(hipEventSynchronize(ev[r.first + 1]));
+            float ms = 0.f;
+            IMM_HIP(hipEventElapsedTime(&ms, ev[r.first], ev[r.first + 1]));
+            total_ms[r.id] += ms;
+            launches[r.id] += 1;
+        }
+        recs.clear();
+        return IMM_OK;
+    }
+    void reset() {
+        recs.clear();
+        for (int i = 0; i < IMM_K_COUNT; ++i) { total_ms[i] = 0; launches[i] = 0; }
+    }
+    void destroy() {
+        for (auto& e : ev) (void)hipEventDestroy(e);
+        ev.clear();
+    }
+};
+
+}  // namespace imm
+
+struct imm_ctx {
+    int device = 0;
+    imm::DevBuf encA, encB, eqx, eqy, a, b, partA, partB, round_scratch, words, snapA, snapB;
+    uint64_t* pinned = nullptr;  // host staging, 4 KiB
+    imm::Profiler prof;
+    bool debug = false;
+    bool widen = true;
+    // intermediates of the last single proof (debug)
+    int dbg_mu = -1, dbg_delta = -1, dbg_nu = -1;
+    uint64_t dbg_rx[IMM_MAX_ROUNDS], dbg_ry[IMM_MAX_ROUNDS], dbg_r[IMM_MAX_ROUNDS];
+};
+
+namespace imm {
+
+constexpr size_t kWordsDev = 3 + 3 * IMM_MAX_ROUNDS + 3;  // c0, vA, vB, g[...], final triple
+
+static bool dim_ok(uint64_t v) { return v >= 1 && v <= (1ull << IMM_MAX_ROUNDS); }
+
+static int fetch_words(imm_ctx* ctx, hipStream_t s, const uint64_t* dev, size_t count, uint64_t* host_out) {
+    IMM_HIP(hipMemcpyAsync(ctx->pinned, dev, count * sizeof(uint64_t), hipMemcpyDeviceToHost, s));
+    IMM_HIP(hipStreamSynchronize(s));
+    std::memcpy(host_out, ctx->pinned, count * sizeof(uint64_t));
+    return IMM_OK;
+}
+
+// eq vectors for the row point (tR coordinates) and the column point (tC).
+static int build_eq(imm_ctx* ctx, hipStream_t s, const uint64_t* pr, int tR, const uint64_t* pc, int tC) {
+    int rc;
+    if ((rc = ctx->eqx.ensure(sizeof(uint64_t) << tR))) return rc;
+    if ((rc = ctx->eqy.ensure(sizeof(uint64_t) << tC))) return rc;
+    k::Point a{}, b{};
+    for (int i = 0; i < tR; ++i) a.v[i] = pr[i];
+    for (int i = 0; i < tC; ++i) b.v[i] = pc[i];
+    if ((rc = ctx->prof.begin(IMM_K_EQ, s))) return rc;
+    IMM_HIP(k::eq_build2(s, a, tR, ctx->eqx.u64(), b, tC, ctx->eqy.u64()));
+    return ctx->prof.end(IMM_K_EQ, s);
+}
+
+// a[j] = sum_i eqx[i] T[i][j] for j < cols, zero up to `padded`.
+static int partial_over_rows(imm_ctx* ctx, hipStream_t s, int kid, const void* T, int dt, uint64_t rows, uint64_t cols,
+                             uint64_t ld, const uint64_t* eq, uint64_t padded, DevBuf& part, uint64_t* out) {
+    int rc;
+    k::Split sp = k::plan_over_rows(rows, cols);
+    if ((rc = part.ensure(sizeof(uint64_t) * sp.nsplit * cols))) return rc;
+    if ((rc = ctx->prof.begin(kid, s))) return rc;
+    IMM_HIP(k::reduce_over_rows(s, T, dt, rows, cols, ld, eq, part.u64(), sp));
+    if ((rc = ctx->prof.end(kid, s))) return rc;
+    if ((rc = ctx->prof.begin(IMM_K_COMBINE, s))) return rc;
+    IMM_HIP(k::combine(s, part.u64(), sp.nsplit, cols, padded, out));
+    return ctx->prof.end(IMM_K_COMBINE, s);
+}
+
+// b[i] = sum_j eqy[j] T[i][j] for i < rows, zero up to `padded`.
+static int partial_over_cols(imm_ctx* ctx, hipStream_t s, int kid, const void* T, int dt, uint64_t rows, uint64_t cols,
+                             uint64_t ld, const uint64_t* eq, uint64_t padded, DevBuf& part, uint64_t* out) {
+    int rc;
+    k::Split sp = k::plan_over_cols(rows, cols);
+    if ((rc = part.ensure(sizeof(uint64_t) * sp.nsplit * rows))) return rc;
+    if ((rc = ctx->prof.begin(kid, s))) return rc;
+    IMM_HIP(k::reduce_over_cols(s, T, dt, rows, cols, ld, eq, part.u64(), sp));
+    if ((rc = ctx->prof.end(kid, s))) return rc;
+    if ((rc = ctx->prof.begin(IMM_K_COMBINE, s))) return rc;
+    IMM_HIP(k::combine(s, part.u64(), sp.nsplit, rows, padded, out));
+    return ctx->prof.end(IMM_K_COMBINE, s);
+}
+
+static int run_round(imm_ctx* ctx, hipStream_t s, uint64_t* a, uint64_t* b, uint64_t L, bool fold, uint64_t r,
+                     uint64_t* out3_dev, uint64_t* host3) {
+    int rc;
+    if ((rc = ctx->round_scratch.ensure(sizeof(uint64_t) * k::round_scratch_words(L)))) return rc;
+    if ((rc = ctx->prof.begin(IMM_K_ROUND, s))) return rc;
+    IMM_HIP(k::round(s, a, b, L, fold, r, out3_dev, ctx->round_scratch.u64()));
+    if ((rc = ctx->prof.end(IMM_K_ROUND, s))) return rc;
+    return fetch_words(ctx, s, out3_dev, 3, host3);
+}
+
+static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uint8_t state[32], imm_proof* out) {
+    if (!ds.A_dev || !ds.B_dev || !ds.com || !state || !out) return IMM_E_NULL;
+    if (!dim_ok(ds.m) || !dim_ok(ds.d) || !dim_ok(ds.n)) return IMM_E_SHAPE;
+    if (ds.dtA != IMM_I16 && ds.dtA != IMM_F64P) return IMM_E_DTYPE;
+    if (ds.dtB != IMM_I8 && ds.dtB != IMM_F64P) return IMM_E_DTYPE;
+    const uint64_t m = ds.m, d = ds.d, n = ds.n;
+    const int mu = hf::ceil_log2(m), delta = hf::ceil_log2(d), nu = hf::ceil_log2(n);
+    const uint64_t D = 1ull << delta;
+    int rc;
+
+    Transcript tr(state);
+    uint64_t rx[IMM_MAX_ROUNDS] = {}, ry[IMM_MAX_ROUNDS] = {}, rr[IMM_MAX_ROUNDS] = {};
+    tr.head(m, d, n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, mu, nu, rx, ry);
+
+    // a1: widen raw operands into scratch (skipped for pre-encoded tables or in narrow-read mode)
+    const void* Ap = ds.A_dev;
+    const void* Bp = ds.B_dev;
+    int dtA = (int)ds.dtA, dtB = (int)ds.dtB;
+    if (ctx->widen && dtA != IMM_F64P) {
+        if ((rc = ctx->encA.ensure(sizeof(uint64_t) * m * d))) return rc;
+        if ((rc = ctx->prof.begin(IMM_K_ENCODE_A, s))) return rc;
+        IMM_HIP(k::encode(s, Ap, dtA, m * d, ctx->encA.u64()));
+        if ((rc = ctx->prof.end(IMM_K_ENCODE_A, s))) return rc;
+        Ap = ctx->encA.p;
+        dtA = IMM_F64P;
+    }
+    if (ctx->widen && dtB != IMM_F64P) {
+        if ((rc = ctx->encB.ensure(sizeof(uint64_t) * d * n))) return rc;
+        if ((rc = ctx->prof.begin(IMM_K_ENCODE_B, s))) return rc;
+        IMM_HIP(k::encode(s, Bp, dtB, d * n, ctx->encB.u64()));
+        if ((rc = ctx->prof.end(IMM_K_ENCODE_B, s))) return rc;
+        Bp = ctx->encB.p;
+        dtB = IMM_F64P;
+    }
+
+    // a2: eq vectors; a3/a4: the two streaming partial evaluations
+    if ((rc = build_eq(ctx, s, rx, mu, ry, nu))) return rc;
+    if ((rc = ctx->a.ensure(sizeof(uint64_t) * D))) return rc;
+    if ((rc = ctx->b.ensure(sizeof(uint64_t) * D))) return rc;
+    if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
+    uint64_t* a = ctx->a.u64();
+    uint64_t* b = ctx->b.u64();
+    uint64_t* words = ctx->words.u64();
+    if ((rc = partial_over_rows(ctx, s, IMM_K_REDUCE_A, Ap, dtA, m, d, d, ctx->eqx.u64(), D, ctx->partA, a))) return rc;
+    if ((rc = partial_over_cols(ctx, s, IMM_K_REDUCE_B, Bp, dtB, d, n, n, ctx->eqy.u64(), D, ctx->partB, b))) return rc;
+
+    if (ctx->debug) {
+        if ((rc = ctx->snapA.ensure(sizeof(uint64_t) * D))) return rc;
+        if ((rc = ctx->snapB.ensure(sizeof(uint64_t) * D))) return rc;
+        IMM_HIP(hipMemcpyAsync(ctx->snapA.p, a, sizeof(uint64_t) * D, hipMemcpyDeviceToDevice, s));
+        IMM_HIP(hipMemcpyAsync(ctx->snapB.p, b, sizeof(uint64_t) * D, hipMemcpyDeviceToDevice, s));
+    }
+
+    std::memset(out, 0, sizeof(*out));
+    out->version = IMM_PROOF_VERSION;
+    out->mu = (uint32_t)mu;
+    out->delta = (uint32_t)delta;
+    out->nu = (uint32_t)nu;
+
+    uint64_t fin[3];
+    if (delta == 0) {
+        // a single shared index: the claim is the product of the two table entries
+        uint64_t av, bv;
+        if ((rc = fetch_words(ctx, s, a, 1, &av))) return rc;
+        if ((rc = fetch_words(ctx, s, b, 1, &bv))) return rc;
+        out->c0 = hf::mul(av, bv);
+        tr.absorb_words("clmC", &out->c0, 1);
+        fin[0] = av;
+        fin[1] = bv;
+    } else {
+        // a5/a6: first evaluation, then delta times (absorb, squeeze, fold + evaluate)
+        uint64_t g[3];
+        if ((rc = run_round(ctx, s, a, b, D, false, 0, words + 3, g))) return rc;
+        out->c0 = hf::add(g[0], g[1]);
+        tr.absorb_words("clmC", &out->c0, 1);
+        uint64_t L = D;
+        for (int kk = 0; kk < delta; ++kk) {
+            out->g[3 * kk] = g[0];
+            out->g[3 * kk + 1] = g[1];
+            out->g[3 * kk + 2] = g[2];
+            tr.absorb_words("rnd ", g, 3);
+            rr[kk] = tr.challenge();
+            uint64_t* dst = words + 3 + 3 * (kk + 1);
+            if ((rc = run_round(ctx, s, a, b, L, true, rr[kk], dst, g))) return rc;
+            L >>= 1;
+        }
+        fin[0] = g[0];  // after the last fold the kernel returns (a[0], b[0], 0)
+        fin[1] = g[1];
+    }
+    out->vA = fin[0];
+    out->vB = fin[1];
+    tr.absorb_words("fin ", fin, 2);
+    std::memcpy(state, tr.s, 32);
+
+    if (ctx->debug) {
+        ctx->dbg_mu = mu; ctx->dbg_delta = delta; ctx->dbg_nu = nu;
+        std::memcpy(ctx->dbg_rx, rx, sizeof(rx));
+        std::memcpy(ctx->dbg_ry, ry, sizeof(ry));
+        std::memcpy(ctx->dbg_r, rr, sizeof(rr));
+    }
+    return ctx->prof.mask ? ctx->prof.flush() : IMM_OK;
+}
+
+}  // namespace imm
+
+using namespace imm;
+
+extern "C" const char* imm_last_error(void) { return g_last_error.c_str(); }
+
+extern "C" int imm_ctx_create(imm_ctx** out, int device, size_t scratch_bytes) {
+    if (!out) return IMM_E_NULL;
+    *out = nullptr;
+    int count = 0;
+    IMM_HIP(hipGetDeviceCount(&count));
+    if (device < 0 || device >= count) {
+        g_last_error = "no such HIP device";
+        return IMM_E_HIP;
+    }
+    IMM_HIP(hipSetDevice(device));
+    imm_ctx* ctx = new (std::nothrow) imm_ctx();
+    if (!ctx) return IMM_E_NOMEM;
+    ctx->device = device;
+    hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), 4096, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        delete ctx;
+        return fail_hip(e, "hipHostMalloc");
+    }
+    if (scratch_bytes) {
+        // the hint goes to the widened weight table, by far the largest scratch buffer
+        int rc = ctx->encB.ensure(scratch_bytes);
+        if (rc) {
+            (void)hipHostFree(ctx->pinned);
+            delete ctx;
+            return rc;
+        }
+    }
+    *out = ctx;
+    return IMM_OK;
+}
+
+extern "C" int imm_ctx_destroy(imm_ctx* ctx) {
+    if (!ctx) return IMM_E_NULL;
+    (void)hipSetDevice(ctx->device);
+    (void)hipDeviceSynchronize();
+    for (DevBuf* bf : {&ctx->encA, &ctx->encB, &ctx->eqx, &ctx->eqy, &ctx->a, &ctx->b, &ctx->partA, &ctx->partB,
+                       &ctx->round_scratch, &ctx->words, &ctx->snapA, &ctx->snapB})
+        bf->release();
+    ctx->prof.destroy();
+    if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+    delete ctx;
+    return IMM_OK;
+}
+
+extern "C" int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value) {
+    if (!ctx) return IMM_E_NULL;
+    switch (option) {
+    case IMM_OPT_DEBUG_SNAPSHOTS: ctx->debug = value != 0; return IMM_OK;
+    case IMM_OPT_WIDEN: ctx->widen = value != 0; return IMM_OK;
+    default: return IMM_E_STATE;
+    }
+}
+
+extern "C" int imm_ctx_set_profiling(imm_ctx* ctx, uint32_t mask) {
+    if (!ctx) return IMM_E_NULL;
+    IMM_HIP(hipSetDevice(ctx->device));
+    if (ctx->prof.mask) {
+        int rc = ctx->prof.flush();
+        if (rc) return rc;
+    }
+    ctx->prof.mask = mask & ((1u << IMM_K_COUNT) - 1);
+    return IMM_OK;
+}
+
+extern "C" int imm_ctx_kernel_time(imm_ctx* ctx, int kernel_id, uint64_t* launches, double* total_ms) {
+    if (!ctx) return IMM_E_NULL;
+    if (kernel_id < 0 || kernel_id >= IMM_K_COUNT) return IMM_E_SHAPE;
+    IMM_HIP(hipSetDevice(ctx->device));
+    int rc = ctx->prof.flush();
+    if (rc) return rc;
+    if (launches) *launches = ctx->prof.launches[kernel_id];
+    if (total_ms) *total_ms = ctx->prof.total_ms[kernel_id];
+    return IMM_OK;
+}
+
+extern "C" int imm_ctx_reset_profiling(imm_ctx* ctx) {
+    if (!ctx) return IMM_E_NULL;
+    IMM_HIP(hipSetDevice(ctx->device));
+    int rc = ctx->prof.flush();
+    ctx->prof.reset();
+    return rc;
+}
+
+extern "C" int imm_encode(imm_ctx* ctx, void* stream, const void* src_dev, imm_dtype dtype, uint64_t count,
+                          uint64_t* dst_dev) {
+    if (!ctx || (count && (!src_dev || !dst_dev))) return IMM_E_NULL;
+    if (dtype != IMM_I8 && dtype != IMM_I16 && dtype != IMM_I64) return IMM_E_DTYPE;
+    IMM_HIP(hipSetDevice(ctx->device));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc;
+    if ((rc = ctx->prof.begin(IMM_K_ENCODE_B, s))) return rc;
+    IMM_HIP(k::encode(s, src_dev, dtype, count, dst_dev));
+    return ctx->prof.end(IMM_K_ENCODE_B, s);
+}
+
+extern "C" int imm_mle_eval(imm_ctx* ctx, void* stream, const void* table_dev, imm_dtype dt, uint64_t rows,
+                            uint64_t cols, uint64_t ld, const uint64_t* pt_rows, const uint64_t* pt_cols,
+                            uint64_t* out_host) {
+    if (!ctx || !table_dev || !out_host) return IMM_E_NULL;
+    if (!dim_ok(rows) || !dim_ok(cols) || ld < cols) return IMM_E_SHAPE;
+    if (dt < IMM_I8 || dt > IMM_F64P) return IMM_E_DTYPE;
+    const int tR = hf::ceil_log2(rows), tC = hf::ceil_log2(cols);
+    if ((tR && !pt_rows) || (tC && !pt_cols)) return IMM_E_NULL;
+    for (int i = 0; i < tR; ++i)
+        if (pt_rows[i] >= hf::P) return IMM_E_SHAPE;
+    for (int i = 0; i < tC; ++i)
+        if (pt_cols[i] >= hf::P) return IMM_E_SHAPE;
+    IMM_HIP(hipSetDevice(ctx->device));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc;
+    if ((rc = build_eq(ctx, s, pt_rows, tR, pt_cols, tC))) return rc;
+    if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
+    if (cols >= 256) {
+        // wide table: reduce along the rows first, then one dot product with the row weights
+        if ((rc = ctx->a.ensure(sizeof(uint64_t) * rows))) return rc;
+        if ((rc = partial_over_cols(ctx, s, IMM_K_REDUCE_B, table_dev, dt, rows, cols, ld, ctx->eqy.u64(), rows,
+                                    ctx->partB, ctx->a.u64())))
+            return rc;
+        IMM_HIP(k::dot(s, ctx->a.u64(), ctx->eqx.u64(), rows, ctx->words.u64()));
+    } else {
+        if ((rc = ctx->a.ensure(sizeof(uint64_t) * cols))) return rc;
+        if ((rc = partial_over_rows(ctx, s, IMM_K_REDUCE_A, table_dev, dt, rows, cols, ld, ctx->eqx.u64(), cols,
+                                    ctx->partA, ctx->a.u64())))
+            return rc;
+        IMM_HIP(k::dot(s, ctx->a.u64(), ctx->eqy.u64(), cols, ctx->words.u64()));
+    }
+    if ((rc = fetch_words(ctx, s, ctx->words.u64(), 1, out_host))) return rc;
+    return ctx->prof.mask ? ctx->prof.flush() : IMM_OK;
+}
+
+extern "C" int imm_sumcheck_matmul_prove(imm_ctx* ctx, void* stream, const void* A_dev, imm_dtype dtA,
+                                         const void* B_dev, imm_dtype dtB, uint64_t m, uint64_t d, uint64_t n,
+                                         const imm_commit* com, uint8_t transcript_state[32], imm_proof* out_host) {
+    if (!ctx) return IMM_E_NULL;
+    IMM_HIP(hipSetDevice(ctx->device));
+    imm_matmul_desc ds;
+    ds.A_dev = A_dev; ds.B_dev = B_dev;
+    ds.dtA = (uint32_t)dtA; ds.dtB = (uint32_t)dtB;
+    ds.m = m; ds.d = d; ds.n = n;
+    ds.com = com;
+    return prove_one(ctx, static_cast<hipStream_t>(stream), ds, transcript_state, out_host);
+}
+
+extern "C" int imm_sumcheck_matmul_prove_batch(imm_ctx* ctx, void* stream, int count, const imm_matmul_desc* descs,
+                                               int chained, uint8_t transcript_state[32], imm_proof* outs_host,
+                                               uint8_t* states_out) {
+    if (!ctx || !transcript_state || (count > 0 && (!descs || !outs_host))) return IMM_E_NULL;
+    if (count < 0) return IMM_E_SHAPE;
+    IMM_HIP(hipSetDevice(ctx->device));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // validate everything before the first launch
+    for (int t = 0; t < count; ++t) {
+        const imm_matmul_desc& ds = descs[t];
+        if (!ds.A_dev || !ds.B_dev || !ds.com) return IMM_E_NULL;
+        if (!dim_ok(ds.m) || !dim_ok(ds.d) || !dim_ok(ds.n)) return IMM_E_SHAPE;
+        if (ds.dtA != IMM_I16 && ds.dtA != IMM_F64P) return IMM_E_DTYPE;
+        if (ds.dtB != IMM_I8 && ds.dtB != IMM_F64P) return IMM_E_DTYPE;
+    }
+    uint8_t start[32], cur[32];
+    std::memcpy(start, transcript_state, 32);
+    std::memcpy(cur, transcript_state, 32);
+    for (int t = 0; t < count; ++t) {
+        if (!chained) std::memcpy(cur, start, 32);
+        int rc = prove_one(ctx, s, descs[t], cur, &outs_host[t]);
+        if (rc) return rc;
+        if (states_out) std::memcpy(states_out + 32 * (size_t)t, cur, 32);
+    }
+    std::memcpy(transcript_state, cur, 32);
+    return IMM_OK;
+}
+
+extern "C" int imm_round_fold_eval(imm_ctx* ctx, void* stream, uint64_t* a_dev, uint64_t* b_dev, uint64_t L,
+                                   const uint64_t* fold_r, uint64_t g_host[3]) {
+    if (!ctx || !a_dev || !b_dev || !g_host) return IMM_E_NULL;
+    if (L < 2 || (L & (L - 1)) || L > (1ull << IMM_MAX_ROUNDS)) return IMM_E_SHAPE;
+    if (fold_r && *fold_r >= hf::P) return IMM_E_SHAPE;
+    IMM_HIP(hipSetDevice(ctx->device));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc;
+    if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
+    if ((rc = run_round(ctx, s, a_dev, b_dev, L, fold_r != nullptr, fold_r ? *fold_r : 0, ctx->words.u64(), g_host)))
+        return rc;
+    return ctx->prof.mask ? ctx->prof.flush() : IMM_OK;
+}
+
+extern "C" int imm_debug_fetch(imm_ctx* ctx, int which, uint64_t* out_host, uint64_t capacity, uint64_t* count) {
+    if (!ctx || !count) return IMM_E_NULL;
+    if (!ctx->debug || ctx->dbg_delta < 0) return IMM_E_STATE;
+    IMM_HIP(hipSetDevice(ctx->device));
+    const uint64_t* host_src = nullptr;
+    const void* dev_src = nullptr;
+    uint64_t avail = 0;
+    switch (which) {
+    case 0: dev_src = ctx->eqx.p; avail = 1ull << ctx->dbg_mu; break;
+    case 1: dev_src = ctx->eqy.p; avail = 1ull << ctx->dbg_nu; break;
+    case 2: dev_src = ctx->snapA.p; avail = 1ull << ctx->dbg_delta; break;
+    case 3: dev_src = ctx->snapB.p; avail = 1ull << ctx->dbg_delta; break;
+    case 4: host_src = ctx->dbg_rx; avail = (uint64_t)ctx->dbg_mu; break;
+    case 5: host_src = ctx->dbg_ry; avail = (uint64_t)ctx->dbg_nu; break;
+    case 6: host_src = ctx->dbg_r; avail = (uint64_t)ctx->dbg_delta; break;
+    default: return IMM_E_SHAPE;
+    }
+    *count = avail;
+    uint64_t ncopy = avail < capacity ? avail : capacity;
+    if (!ncopy) return IMM_OK;
+    if (!out_host) return IMM_E_NULL;
+    if (host_src) {
+        std::memcpy(out_host, host_src, ncopy * sizeof(uint64_t));
+    } else {
+        IMM_HIP(hipDeviceSynchronize());
+        IMM_HIP(hipMemcpy(out_host, dev_src, ncopy * sizeof(uint64_t), hipMemcpyDeviceToHost));
+    }
+    return IMM_OK;
+}

@@ -1,0 +1,189 @@
+"""CPU-side checks of libimm.so: it loads, exports what include/imm.h declares, and its
+host-only entry points (commit, verify, transcript init) agree with the oracle.
+No GPU compute is called here."""
+import ctypes
+import hashlib
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import reference as ref
+from paper_2602_22700_amd import binding as imm
+from paper_2602_22700_amd import build as imm_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = ref.P
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(imm.LIB_PATH):
+        imm_build.build_library(force=True)
+    return imm.load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "imm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(imm_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert "imm_commit_matmul" in names and "imm_mle_eval" in names
+    assert "imm_sumcheck_matmul_prove" in names and "imm_verify" in names
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(imm.EXPORTS) == names
+
+
+def test_struct_layouts_match_the_header():
+    assert ctypes.sizeof(imm.Commit1) == 56 and ctypes.sizeof(imm.Commit) == 168
+    assert ctypes.sizeof(imm.Proof) == 16 + 24 + 8 * 3 * imm.IMM_MAX_ROUNDS
+    assert imm.Proof.g.offset == 40 and imm.Proof.c0.offset == 16
+
+
+def test_fs_init_and_sha256_against_hashlib(lib):
+    assert imm.imm_fs_init() == hashlib.sha256(b"IMM-FS-v1").digest() == ref.FS_INIT
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (64, 64, 64), (2, (1 << 20) + 3, 1), (130, 4100, 257)])
+def test_commit_matches_oracle(lib, oracle_fast, shape):
+    m, d, n = shape
+    rng = np.random.default_rng(m * 1000 + n)
+    A = rng.integers(-2**15, 2**15, size=(m, d), dtype=np.int16)
+    B = rng.integers(-128, 128, size=(d, n), dtype=np.int8)
+    C = rng.integers(-2**40, 2**40, size=(m, n), dtype=np.int64)
+    com = imm.imm_commit_matmul(A, B, C, m, d, n)
+    assert com.digests() == oracle_fast.commit_matmul(A, B, C)
+    assert (com.A.rows, com.A.cols, com.A.dtype) == (m, d, imm.IMM_I16)
+    assert (com.B.rows, com.B.cols, com.B.dtype) == (d, n, imm.IMM_I8)
+    assert (com.C.rows, com.C.cols, com.C.dtype) == (m, n, imm.IMM_I64)
+    # NULL entries are left untouched
+    com2 = imm.imm_commit_matmul(None, B, None, m, d, n)
+    assert bytes(com2.B.digest) == bytes(com.B.digest) and bytes(com2.A.digest) == bytes(32)
+
+
+def test_commit_rejects_bad_shapes(lib):
+    with pytest.raises(imm.ImmError) as e:
+        imm.imm_commit_matmul(None, None, None, 0, 1, 1)
+    assert e.value.code == -2
+    assert lib.imm_commit_matmul(None, None, None, 1, 1, 1, None) == -1
+
+
+def to_proof(p: dict) -> imm.Proof:
+    out = imm.Proof()
+    out.version = 1
+    out.mu, out.delta, out.nu = p["mu"], p["delta"], p["nu"]
+    out.c0, out.vA, out.vB = p["c0"], p["vA"], p["vB"]
+    for i, v in enumerate(p["g"]):
+        out.g[i] = v
+    return out
+
+
+def make_case(oracle_fast, m, d, n, seed):
+    rng = np.random.default_rng(seed)
+    A = rng.integers(-2**15, 2**15, size=(m, d), dtype=np.int16)
+    B = rng.integers(-128, 128, size=(d, n), dtype=np.int8)
+    C = oracle_fast.matmul(A, B)
+    com = imm.imm_commit_matmul(A, B, C, m, d, n)
+    proof, s_out = oracle_fast.prove(A, B, C, com.digests())
+    return A, B, C, com, proof, s_out
+
+
+@pytest.mark.parametrize("shape", [(4, 4, 4), (1, 1, 1), (5, 6, 7), (1, 9, 3), (17, 1, 2), (64, 64, 64)])
+def test_verify_accepts_oracle_proofs(lib, oracle_fast, shape):
+    m, d, n = shape
+    A, B, C, com, proof, s_out = make_case(oracle_fast, m, d, n, 77 + m + d + n)
+    code, st, fr = imm.imm_verify(com, ref.FS_INIT, to_proof(proof))
+    assert (code, st, fr) == (0, s_out, 0)
+    code, st, fr = imm.imm_verify(com, ref.FS_INIT, to_proof(proof), A, B, C)
+    assert (code, st, fr) == (0, s_out, 0)
+
+
+def test_verify_reject_codes_match_oracle_on_every_mutation(lib, oracle_fast):
+    m, d, n = 4, 8, 4
+    A, B, C, com, proof, s_out = make_case(oracle_fast, m, d, n, 5)
+    dg = com.digests()
+    muts = [("c0", None), ("vA", None), ("vB", None)] + [("g", k) for k in range(3 * proof["delta"])]
+    for name, k in muts:
+        bad = dict(proof, g=list(proof["g"]))
+        if k is None:
+            bad[name] = (bad[name] + 1) % P
+        else:
+            bad["g"][k] = (bad["g"][k] + 1) % P
+        want = oracle_fast.verify(bad, m, d, n, dg, A=A, B=B, C=C)
+        got = imm.imm_verify(com, ref.FS_INIT, to_proof(bad), A, B, C)
+        assert got[0] == want[0] != 0 and got[2] == want[2], (name, k)
+        want = oracle_fast.verify(bad, m, d, n, dg)
+        got = imm.imm_verify(com, ref.FS_INIT, to_proof(bad))
+        assert got[0] == want[0] != 0 and got[2] == want[2], (name, k)
+
+
+def test_verify_format_commit_and_opening_rejections(lib, oracle_fast):
+    m, d, n = 4, 4, 4
+    A, B, C, com, proof, s_out = make_case(oracle_fast, m, d, n, 6)
+    pr = to_proof(proof)
+    bad = pr.copy(); bad.c0 = P
+    assert imm.imm_verify(com, ref.FS_INIT, bad)[0] == 7
+    bad = pr.copy(); bad.g[0] = 2**64 - 1
+    assert imm.imm_verify(com, ref.FS_INIT, bad)[0] == 7
+    bad = pr.copy(); bad.mu = 3
+    assert imm.imm_verify(com, ref.FS_INIT, bad)[0] == 7
+    bad = pr.copy(); bad.version = 2
+    assert imm.imm_verify(com, ref.FS_INIT, bad)[0] == 7
+    bad = pr.copy(); bad.g[3 * proof["delta"]] = 1   # junk after the last round
+    assert imm.imm_verify(com, ref.FS_INIT, bad)[0] == 7
+    # wrong starting state: the challenges differ, so a round sum or the final check fails
+    assert imm.imm_verify(com, bytes(32), pr)[0] in (1, 2)
+    # every single-entry perturbation of C: its digest no longer matches
+    for i in range(m):
+        for y in range(n):
+            Cb = C.copy(); Cb[i, y] += 1
+            assert imm.imm_verify(com, ref.FS_INIT, pr, A, B, Cb)[0] == 6
+            # committed wrong C, sumcheck of the true product: opening of C fails
+            comb = imm.imm_commit_matmul(A, B, Cb, m, d, n)
+            pb, _ = oracle_fast.prove(A, B, None, comb.digests())
+            assert imm.imm_verify(comb, ref.FS_INIT, to_proof(pb))[0] == 0
+            assert imm.imm_verify(comb, ref.FS_INIT, to_proof(pb), None, None, Cb)[0] == 5
+    Ab = A.copy(); Ab[0, 0] ^= 1
+    assert imm.imm_verify(com, ref.FS_INIT, pr, Ab, None, None)[0] == 6
+    # openings of A and B: statement committed to (Ab, B, C) but proof built from A
+    comA = imm.imm_commit_matmul(Ab, B, C, m, d, n)
+    pA, _ = oracle_fast.prove(A, B, None, comA.digests())
+    assert imm.imm_verify(comA, ref.FS_INIT, to_proof(pA), Ab, None, None)[0] == 3
+    Bb = B.copy(); Bb[1, 2] ^= 1
+    comB = imm.imm_commit_matmul(A, Bb, C, m, d, n)
+    pB, _ = oracle_fast.prove(A, B, None, comB.digests())
+    assert imm.imm_verify(comB, ref.FS_INIT, to_proof(pB), None, Bb, None)[0] == 4
+
+
+def test_verify_argument_errors(lib, oracle_fast):
+    A, B, C, com, proof, _ = make_case(oracle_fast, 2, 2, 2, 1)
+    pr = to_proof(proof)
+    st = (ctypes.c_uint8 * 32)()
+    assert lib.imm_verify(None, st, ctypes.byref(pr), None, None, None, None, None) == -1
+    bad = imm.Commit()
+    ctypes.memmove(ctypes.byref(bad), ctypes.byref(com), ctypes.sizeof(com))
+    bad.B.rows = 3
+    assert lib.imm_verify(ctypes.byref(bad), st, ctypes.byref(pr), None, None, None, None, None) == -2
+
+
+def test_verify_chained_states(lib, oracle_fast):
+    rng = np.random.default_rng(12)
+    items, coms = [], []
+    for t in range(3):
+        A = rng.integers(-2**15, 2**15, size=(3, 8), dtype=np.int16)
+        B = rng.integers(-128, 128, size=(8, 5), dtype=np.int8)
+        C = oracle_fast.matmul(A, B)
+        com = imm.imm_commit_matmul(A, B, C, 3, 8, 5)
+        items.append((A, B, C, com.digests()))
+        coms.append(com)
+    proofs, states = oracle_fast.prove_chain(items, chained=True)
+    s = ref.FS_INIT
+    for com, pr, st in zip(coms, proofs, states):
+        code, s_next, _ = imm.imm_verify(com, s, to_proof(pr))
+        assert code == 0 and s_next == st
+        s = s_next
