@@ -75,7 +75,7 @@ hipError_t launch_encode(hipStream_t stream, const void* src, uint64_t count, ui
                      (reinterpret_cast<uintptr_t>(dst) % 16 == 0);
     const uint64_t items = vec ? (count + 1) / 2 : count;
     uint64_t blocks = (items + kBlock - 1) / kBlock;
-    if (blocks > 8192) blocks = 8192;
+    if (blocks > 16384) blocks = 16384;
     if (vec)
         hipLaunchKernelGGL((encode_kernel<S, true>), dim3((unsigned)blocks), dim3(kBlock), 0, stream,
                            static_cast<const S*>(src), dst, count);
@@ -113,10 +113,47 @@ __global__ __launch_bounds__(kBlock) void eq_build2_kernel(Point ptA, int tA, ui
 }
 
 // ------------------------------------------------------------------ reduction over the columns (row-wise)
-// Block = R consecutive rows x one column split.  A lane owns column pairs
-// (2*tid, 2*tid+1) + 512*u of the split, so one wave load covers 1 KiB of a row
-// and the eq pair is loaded once and reused for the R rows.
-template <typename S, int R, bool VEC>
+// Block = R consecutive rows x one column split.  A lane owns the column pairs
+// (2*tid, 2*tid+1) + 512*u of the split, so one wave load covers 1 KiB of a row and the
+// eq pair is loaded once and reused for the R rows.  In the full-tile path all R*U
+// 16-byte loads of a trip are issued before the first multiply, which is what keeps
+// enough bytes in flight per CU to stream at HBM rate.
+template <typename S, int R, int U>
+__device__ __forceinline__ void cols_full_tile(const S* __restrict__ base, uint64_t ld, const uint64_t* __restrict__ eqb,
+                                               uint64_t npairs, gl::Acc (&acc)[R]) {
+    using V2 = typename Pair<S>::type;
+    uint64_t p = threadIdx.x;
+    for (; p + (U - 1) * kBlock < npairs; p += U * kBlock) {
+        ulonglong2 e[U];
+        V2 x[U][R];
+#pragma unroll
+        for (int u = 0; u < U; ++u) e[u] = *reinterpret_cast<const ulonglong2*>(eqb + 2 * (p + u * kBlock));
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int r = 0; r < R; ++r) x[u][r] = *reinterpret_cast<const V2*>(base + r * ld + 2 * (p + u * kBlock));
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                gl::acc_mac(acc[r], to_field<S>((S)x[u][r].x), e[u].x);
+                gl::acc_mac(acc[r], to_field<S>((S)x[u][r].y), e[u].y);
+            }
+    }
+    for (; p < npairs; p += kBlock) {
+        ulonglong2 e = *reinterpret_cast<const ulonglong2*>(eqb + 2 * p);
+        V2 x[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) x[r] = *reinterpret_cast<const V2*>(base + r * ld + 2 * p);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            gl::acc_mac(acc[r], to_field<S>((S)x[r].x), e.x);
+            gl::acc_mac(acc[r], to_field<S>((S)x[r].y), e.y);
+        }
+    }
+}
+
+template <typename S, int R, int U, bool VEC>
 __global__ __launch_bounds__(kBlock) void reduce_over_cols_kernel(const S* __restrict__ T, uint64_t ld, uint64_t rows,
                                                                   uint64_t cols, const uint64_t* __restrict__ eq,
                                                                   uint64_t* __restrict__ partial,
@@ -134,33 +171,17 @@ __global__ __launch_bounds__(kBlock) void reduce_over_cols_kernel(const S* __res
 
     const S* base = T + row0 * ld + c_begin;
     const uint64_t* eqb = eq + c_begin;
-    if (VEC) {
-        using V2 = typename Pair<S>::type;
-        const uint64_t npairs = span >> 1;
-        for (uint64_t p = threadIdx.x; p < npairs; p += kBlock) {
-            ulonglong2 e = *reinterpret_cast<const ulonglong2*>(eqb + 2 * p);
+    uint64_t done = 0;  // columns of the split already accumulated
+    if (VEC && row0 + R <= rows) {
+        cols_full_tile<S, R, U>(base, ld, eqb, span >> 1, acc);
+        done = span & ~uint64_t(1);
+    }
+    // whatever is left: a ragged last tile, an odd last column, or an unaligned table
+    for (uint64_t c = done + threadIdx.x; c < span; c += kBlock) {
+        uint64_t e = eqb[c];
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                if (row0 + r < rows) {
-                    V2 x = *reinterpret_cast<const V2*>(base + r * ld + 2 * p);
-                    gl::acc_mac(acc[r], to_field<S>((S)x.x), e.x);
-                    gl::acc_mac(acc[r], to_field<S>((S)x.y), e.y);
-                }
-            }
-        }
-        if ((span & 1) && threadIdx.x == 0) {
-            uint64_t e = eqb[span - 1];
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (row0 + r < rows) gl::acc_mac(acc[r], to_field<S>(base[r * ld + span - 1]), e);
-        }
-    } else {
-        for (uint64_t c = threadIdx.x; c < span; c += kBlock) {
-            uint64_t e = eqb[c];
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (row0 + r < rows) gl::acc_mac(acc[r], to_field<S>(base[r * ld + c]), e);
-        }
+        for (int r = 0; r < R; ++r)
+            if (row0 + r < rows) gl::acc_mac(acc[r], to_field<S>(base[r * ld + c]), e);
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -169,7 +190,8 @@ __global__ __launch_bounds__(kBlock) void reduce_over_cols_kernel(const S* __res
     }
 }
 
-constexpr int kRowsPerBlock = 4;
+constexpr int kRowsPerBlock = 2;
+constexpr int kColsUnroll = 2;
 
 template <typename S>
 hipError_t launch_over_cols(hipStream_t stream, const void* T, uint64_t rows, uint64_t cols, uint64_t ld,
@@ -178,17 +200,20 @@ hipError_t launch_over_cols(hipStream_t stream, const void* T, uint64_t rows, ui
                      (sp.per_split % 2 == 0) && (reinterpret_cast<uintptr_t>(eq) % 16 == 0);
     dim3 grid((unsigned)((rows + kRowsPerBlock - 1) / kRowsPerBlock), sp.nsplit);
     if (vec)
-        hipLaunchKernelGGL((reduce_over_cols_kernel<S, kRowsPerBlock, true>), grid, dim3(kBlock), 0, stream,
-                           static_cast<const S*>(T), ld, rows, cols, eq, partial, sp.per_split);
+        hipLaunchKernelGGL((reduce_over_cols_kernel<S, kRowsPerBlock, kColsUnroll, true>), grid, dim3(kBlock), 0,
+                           stream, static_cast<const S*>(T), ld, rows, cols, eq, partial, sp.per_split);
     else
-        hipLaunchKernelGGL((reduce_over_cols_kernel<S, kRowsPerBlock, false>), grid, dim3(kBlock), 0, stream,
-                           static_cast<const S*>(T), ld, rows, cols, eq, partial, sp.per_split);
+        hipLaunchKernelGGL((reduce_over_cols_kernel<S, kRowsPerBlock, kColsUnroll, false>), grid, dim3(kBlock), 0,
+                           stream, static_cast<const S*>(T), ld, rows, cols, eq, partial, sp.per_split);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ reduction over the rows (column-wise)
-// A lane owns two adjacent columns; a block walks the rows of its split.  The eq
-// weight of a row is the same for every lane (a scalar load).
+// A lane owns two adjacent columns; a block walks the rows of its split, kRowsUnroll rows
+// per trip with all loads issued first.  The eq weight of a row is the same for every lane
+// (a scalar load).
+constexpr int kRowsUnroll = 8;
+
 template <typename S, bool VEC>
 __global__ __launch_bounds__(kBlock) void reduce_over_rows_kernel(const S* __restrict__ T, uint64_t ld, uint64_t rows,
                                                                   uint64_t cols, const uint64_t* __restrict__ eq,
@@ -207,8 +232,19 @@ __global__ __launch_bounds__(kBlock) void reduce_over_rows_kernel(const S* __res
         gl::acc_clear(a1);
         if (col + 1 < cols) {
             const S* p = T + r_begin * ld + col;
-#pragma unroll 4
-            for (uint64_t i = r_begin; i < r_end; ++i, p += ld) {
+            uint64_t i = r_begin;
+            for (; i + kRowsUnroll <= r_end; i += kRowsUnroll, p += kRowsUnroll * ld) {
+                V2 x[kRowsUnroll];
+#pragma unroll
+                for (int u = 0; u < kRowsUnroll; ++u) x[u] = *reinterpret_cast<const V2*>(p + u * ld);
+#pragma unroll
+                for (int u = 0; u < kRowsUnroll; ++u) {
+                    uint64_t e = eq[i + u];
+                    gl::acc_mac(a0, to_field<S>((S)x[u].x), e);
+                    gl::acc_mac(a1, to_field<S>((S)x[u].y), e);
+                }
+            }
+            for (; i < r_end; ++i, p += ld) {
                 uint64_t e = eq[i];
                 V2 x = *reinterpret_cast<const V2*>(p);
                 gl::acc_mac(a0, to_field<S>((S)x.x), e);
@@ -246,14 +282,22 @@ hipError_t launch_over_rows(hipStream_t stream, const void* T, uint64_t rows, ui
 }
 
 // ------------------------------------------------------------------ combine / dot
+// 64 outputs per block; the four waves take the splits s = w, w + 4, ... and meet in LDS.
 __global__ __launch_bounds__(kBlock) void combine_kernel(const uint64_t* __restrict__ partial, uint32_t nsplit,
                                                          uint64_t len, uint64_t padded, uint64_t* __restrict__ out) {
-    const uint64_t j = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (j >= padded) return;
+    __shared__ uint64_t lds[kWaves][64];
+    const uint32_t lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const uint64_t j = (uint64_t)blockIdx.x * 64 + lane;
     uint64_t v = 0;
     if (j < len)
-        for (uint32_t s = 0; s < nsplit; ++s) v = gl::add(v, partial[(uint64_t)s * len + j]);
-    out[j] = v;
+        for (uint32_t s = w; s < nsplit; s += kWaves) v = gl::add(v, partial[(uint64_t)s * len + j]);
+    lds[w][lane] = v;
+    __syncthreads();
+    if (w == 0 && j < padded) {
+#pragma unroll
+        for (int k = 1; k < kWaves; ++k) v = gl::add(v, lds[k][lane]);
+        out[j] = v;
+    }
 }
 
 __global__ __launch_bounds__(kBlock) void dot_kernel(const uint64_t* __restrict__ x, const uint64_t* __restrict__ y,
@@ -342,6 +386,7 @@ __global__ void fold_last_kernel(uint64_t* __restrict__ a, uint64_t* __restrict_
 constexpr uint32_t kMaxRoundBlocks = 2048;
 
 uint32_t round_blocks(uint64_t items) {
+    if (items <= 8192) return 1;  // small tables: one block writes the result itself, no second launch
     uint64_t nb = (items + kBlock - 1) / kBlock;
     if (nb < 1) nb = 1;
     if (nb > kMaxRoundBlocks) nb = kMaxRoundBlocks;
@@ -369,11 +414,12 @@ hipError_t eq_build2(hipStream_t stream, const Point& ptA, int tA, uint64_t* out
 }
 
 Split plan_over_rows(uint64_t rows, uint64_t cols) {
-    // aim at >= 2048 blocks of 256 lanes; one lane owns two columns
+    // aim at >= 1024 blocks of 256 lanes (one lane owns two columns), at least 32 rows per block
     const uint64_t col_blocks = ((cols + 1) / 2 + kBlock - 1) / kBlock;
-    uint64_t want = (2048 + col_blocks - 1) / col_blocks;
+    uint64_t want = (1024 + col_blocks - 1) / col_blocks;
     uint64_t per = (rows + want - 1) / want;
-    if (per < 16) per = 16;
+    if (per < 32) per = 32;
+    per = (per + kRowsUnroll - 1) / kRowsUnroll * kRowsUnroll;
     if (per > rows) per = rows;
     Split sp;
     sp.per_split = per;
@@ -389,7 +435,7 @@ Split plan_over_cols(uint64_t rows, uint64_t cols) {
     uint64_t per = (cols + want - 1) / want;
     if (per < 2048) per = 2048;
     per = (per + 511) / 512 * 512;  // whole block passes, and even
-    if (per > cols) per = (cols + 1) / 2 * 2;
+    if (per >= cols) per = (cols + 1) / 2 * 2;
     Split sp;
     sp.per_split = per;
     sp.nsplit = (uint32_t)((cols + per - 1) / per);
@@ -420,8 +466,8 @@ hipError_t reduce_over_cols(hipStream_t stream, const void* T, int dtype, uint64
 
 hipError_t combine(hipStream_t stream, const uint64_t* partial, uint32_t nsplit, uint64_t len, uint64_t padded,
                    uint64_t* out) {
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((padded + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream,
-                       partial, nsplit, len, padded, out);
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((padded + 63) / 64)), dim3(kBlock), 0, stream, partial, nsplit,
+                       len, padded, out);
     return hipGetLastError();
 }
 

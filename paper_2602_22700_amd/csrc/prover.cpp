@@ -150,18 +150,31 @@ static int build_eq(imm_ctx* ctx, hipStream_t s, const uint64_t* pr, int tR, con
     return ctx->prof.end(IMM_K_EQ, s);
 }
 
+// Sum the per-split partial vectors into out[0..len) and zero out[len..padded).  When the
+// reduction ran as a single split it already wrote out[0..len) and only the padding is left.
+static int finish_partial(imm_ctx* ctx, hipStream_t s, bool direct, DevBuf& part, uint32_t nsplit, uint64_t len,
+                          uint64_t padded, uint64_t* out) {
+    int rc;
+    if (direct && len == padded) return IMM_OK;
+    if ((rc = ctx->prof.begin(IMM_K_COMBINE, s))) return rc;
+    if (direct)
+        IMM_HIP(k::combine(s, nullptr, 0, 0, padded - len, out + len));
+    else
+        IMM_HIP(k::combine(s, part.u64(), nsplit, len, padded, out));
+    return ctx->prof.end(IMM_K_COMBINE, s);
+}
+
 // a[j] = sum_i eqx[i] T[i][j] for j < cols, zero up to `padded`.
 static int partial_over_rows(imm_ctx* ctx, hipStream_t s, int kid, const void* T, int dt, uint64_t rows, uint64_t cols,
                              uint64_t ld, const uint64_t* eq, uint64_t padded, DevBuf& part, uint64_t* out) {
     int rc;
     k::Split sp = k::plan_over_rows(rows, cols);
-    if ((rc = part.ensure(sizeof(uint64_t) * sp.nsplit * cols))) return rc;
+    const bool direct = sp.nsplit == 1;  // a single split writes the result vector itself
+    if (!direct && (rc = part.ensure(sizeof(uint64_t) * sp.nsplit * cols))) return rc;
     if ((rc = ctx->prof.begin(kid, s))) return rc;
-    IMM_HIP(k::reduce_over_rows(s, T, dt, rows, cols, ld, eq, part.u64(), sp));
+    IMM_HIP(k::reduce_over_rows(s, T, dt, rows, cols, ld, eq, direct ? out : part.u64(), sp));
     if ((rc = ctx->prof.end(kid, s))) return rc;
-    if ((rc = ctx->prof.begin(IMM_K_COMBINE, s))) return rc;
-    IMM_HIP(k::combine(s, part.u64(), sp.nsplit, cols, padded, out));
-    return ctx->prof.end(IMM_K_COMBINE, s);
+    return finish_partial(ctx, s, direct, part, sp.nsplit, cols, padded, out);
 }
 
 // b[i] = sum_j eqy[j] T[i][j] for i < rows, zero up to `padded`.
@@ -169,13 +182,12 @@ static int partial_over_cols(imm_ctx* ctx, hipStream_t s, int kid, const void* T
                              uint64_t ld, const uint64_t* eq, uint64_t padded, DevBuf& part, uint64_t* out) {
     int rc;
     k::Split sp = k::plan_over_cols(rows, cols);
-    if ((rc = part.ensure(sizeof(uint64_t) * sp.nsplit * rows))) return rc;
+    const bool direct = sp.nsplit == 1;
+    if (!direct && (rc = part.ensure(sizeof(uint64_t) * sp.nsplit * rows))) return rc;
     if ((rc = ctx->prof.begin(kid, s))) return rc;
-    IMM_HIP(k::reduce_over_cols(s, T, dt, rows, cols, ld, eq, part.u64(), sp));
+    IMM_HIP(k::reduce_over_cols(s, T, dt, rows, cols, ld, eq, direct ? out : part.u64(), sp));
     if ((rc = ctx->prof.end(kid, s))) return rc;
-    if ((rc = ctx->prof.begin(IMM_K_COMBINE, s))) return rc;
-    IMM_HIP(k::combine(s, part.u64(), sp.nsplit, rows, padded, out));
-    return ctx->prof.end(IMM_K_COMBINE, s);
+    return finish_partial(ctx, s, direct, part, sp.nsplit, rows, padded, out);
 }
 
 static int run_round(imm_ctx* ctx, hipStream_t s, uint64_t* a, uint64_t* b, uint64_t L, bool fold, uint64_t r,

