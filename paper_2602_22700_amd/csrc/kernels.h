@@ -56,5 +56,19 @@ uint64_t round_scratch_words(uint64_t L);
 hipError_t round(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, bool fold, uint64_t r, uint64_t* out3,
                  uint64_t* scratch);
 
+// Layout of the device-side proof word buffer written by rounds().
+constexpr int kWordC0 = 0, kWordVA = 1, kWordVB = 2, kWordG = 3, kWordR = 3 + 3 * IMM_MAX_ROUNDS;
+constexpr int kWordCount = kWordR + IMM_MAX_ROUNDS;
+constexpr uint64_t kRoundsMaxL = 1ull << 15;  // longest table the single-workgroup round loop takes
+
+// Run `nrounds` sumcheck rounds (numbered first_k .. first_k + nrounds - 1, 0-based) in one launch
+// on tables of length L = 2^nrounds <= kRoundsMaxL, hashing the transcript on the device.
+//   state_in : transcript state before the first absorbed message, as the eight big-endian words
+//   absorb_claim: the launch also derives c0 = g(0) + g(1), stores it and absorbs it ("clmC")
+//   words    : device buffer of kWordCount words (c0, vA, vB, g[], r[])
+//   state_out: device buffer of 8 words, the state after the "fin " message
+hipError_t rounds(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, int nrounds, int first_k, bool absorb_claim,
+                  const uint32_t state_in[8], uint64_t* words, uint32_t* state_out);
+
 }  // namespace k
 }  // namespace imm

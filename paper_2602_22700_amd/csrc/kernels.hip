@@ -7,6 +7,7 @@
 #include "kernels.h"
 
 #include "goldilocks.cuh"
+#include "sha256_device.cuh"
 
 namespace imm {
 namespace k {
@@ -16,14 +17,43 @@ constexpr int kBlock = 256;  // 4 waves
 constexpr int kWaves = kBlock / 64;
 
 // ------------------------------------------------------------------ helpers
-template <typename S> struct Pair;
-template <> struct Pair<int8_t> { using type = char2; };
-template <> struct Pair<int16_t> { using type = short2; };
-template <> struct Pair<int64_t> { using type = longlong2; };
-template <> struct Pair<uint64_t> { using type = ulonglong2; };
+// Two adjacent table entries are fetched with one load.  Tables are streamed exactly once,
+// so their loads and the encoder's stores are non-temporal: they do not displace the eq
+// vectors and the partial results from the caches, and on this part they reach a markedly
+// higher share of the HBM rate than plain accesses.
+typedef unsigned long long v2u64 __attribute__((ext_vector_type(2)));
+
+template <typename S> struct RawPair;
+template <> struct RawPair<int8_t> { using type = uint16_t; };
+template <> struct RawPair<int16_t> { using type = uint32_t; };
+template <> struct RawPair<int64_t> { using type = v2u64; };
+template <> struct RawPair<uint64_t> { using type = v2u64; };
 
 template <typename S> __device__ __forceinline__ uint64_t to_field(S v) { return gl::enc((int64_t)v); }
 template <> __device__ __forceinline__ uint64_t to_field<uint64_t>(uint64_t v) { return v; }
+
+template <typename S> __device__ __forceinline__ typename RawPair<S>::type load_pair(const S* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const typename RawPair<S>::type*>(p));
+}
+template <typename S> __device__ __forceinline__ S load_one(const S* p) { return __builtin_nontemporal_load(p); }
+
+template <typename S> __device__ __forceinline__ void unpack(typename RawPair<S>::type raw, uint64_t& f0, uint64_t& f1);
+template <> __device__ __forceinline__ void unpack<int8_t>(uint16_t raw, uint64_t& f0, uint64_t& f1) {
+    f0 = gl::enc((int64_t)(int8_t)(raw & 0xFF));
+    f1 = gl::enc((int64_t)(int8_t)(raw >> 8));
+}
+template <> __device__ __forceinline__ void unpack<int16_t>(uint32_t raw, uint64_t& f0, uint64_t& f1) {
+    f0 = gl::enc((int64_t)(int16_t)(raw & 0xFFFF));
+    f1 = gl::enc((int64_t)(int16_t)(raw >> 16));
+}
+template <> __device__ __forceinline__ void unpack<int64_t>(v2u64 raw, uint64_t& f0, uint64_t& f1) {
+    f0 = gl::enc((int64_t)raw.x);
+    f1 = gl::enc((int64_t)raw.y);
+}
+template <> __device__ __forceinline__ void unpack<uint64_t>(v2u64 raw, uint64_t& f0, uint64_t& f1) {
+    f0 = raw.x;
+    f1 = raw.y;
+}
 
 __device__ __forceinline__ uint64_t wave_sum(uint64_t v) {
 #pragma unroll
@@ -54,13 +84,16 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(const S* __restrict__ sr
     const uint64_t stride = (uint64_t)gridDim.x * kBlock;
     const uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
     if (VEC) {
-        using V2 = typename Pair<S>::type;
+        // one wave reads 64 adjacent pairs and writes 1 KiB of contiguous field elements
         const uint64_t pairs = count >> 1;
-        const V2* s2 = reinterpret_cast<const V2*>(src);
-        ulonglong2* d2 = reinterpret_cast<ulonglong2*>(dst);
         for (uint64_t p = t; p < pairs; p += stride) {
-            V2 v = s2[p];
-            d2[p] = make_ulonglong2(to_field<S>((S)v.x), to_field<S>((S)v.y));
+            v2u64 o;
+            uint64_t f0, f1;
+            // the narrow source is read with ordinary loads; only the 8x larger output streams
+            unpack<S>(*reinterpret_cast<const typename RawPair<S>::type*>(src + 2 * p), f0, f1);
+            o.x = f0;
+            o.y = f1;
+            __builtin_nontemporal_store(o, reinterpret_cast<v2u64*>(dst + 2 * p));
         }
         if ((count & 1) && t == 0) dst[count - 1] = to_field<S>(src[count - 1]);
     } else {
@@ -74,8 +107,8 @@ hipError_t launch_encode(hipStream_t stream, const void* src, uint64_t count, ui
     const bool vec = (reinterpret_cast<uintptr_t>(src) % (2 * sizeof(S)) == 0) &&
                      (reinterpret_cast<uintptr_t>(dst) % 16 == 0);
     const uint64_t items = vec ? (count + 1) / 2 : count;
-    uint64_t blocks = (items + kBlock - 1) / kBlock;
-    if (blocks > 16384) blocks = 16384;
+    uint64_t blocks = (items + kBlock - 1) / kBlock;  // one item per thread: many small blocks stream best
+    if (blocks > (1u << 22)) blocks = 1u << 22;
     if (vec)
         hipLaunchKernelGGL((encode_kernel<S, true>), dim3((unsigned)blocks), dim3(kBlock), 0, stream,
                            static_cast<const S*>(src), dst, count);
@@ -121,34 +154,38 @@ __global__ __launch_bounds__(kBlock) void eq_build2_kernel(Point ptA, int tA, ui
 template <typename S, int R, int U>
 __device__ __forceinline__ void cols_full_tile(const S* __restrict__ base, uint64_t ld, const uint64_t* __restrict__ eqb,
                                                uint64_t npairs, gl::Acc (&acc)[R]) {
-    using V2 = typename Pair<S>::type;
+    using Raw = typename RawPair<S>::type;
     uint64_t p = threadIdx.x;
     for (; p + (U - 1) * kBlock < npairs; p += U * kBlock) {
         ulonglong2 e[U];
-        V2 x[U][R];
+        Raw x[U][R];
 #pragma unroll
         for (int u = 0; u < U; ++u) e[u] = *reinterpret_cast<const ulonglong2*>(eqb + 2 * (p + u * kBlock));
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int r = 0; r < R; ++r) x[u][r] = *reinterpret_cast<const V2*>(base + r * ld + 2 * (p + u * kBlock));
+            for (int r = 0; r < R; ++r) x[u][r] = load_pair<S>(base + r * ld + 2 * (p + u * kBlock));
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                gl::acc_mac(acc[r], to_field<S>((S)x[u][r].x), e[u].x);
-                gl::acc_mac(acc[r], to_field<S>((S)x[u][r].y), e[u].y);
+                uint64_t f0, f1;
+                unpack<S>(x[u][r], f0, f1);
+                gl::acc_mac(acc[r], f0, e[u].x);
+                gl::acc_mac(acc[r], f1, e[u].y);
             }
     }
     for (; p < npairs; p += kBlock) {
         ulonglong2 e = *reinterpret_cast<const ulonglong2*>(eqb + 2 * p);
-        V2 x[R];
+        Raw x[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) x[r] = *reinterpret_cast<const V2*>(base + r * ld + 2 * p);
+        for (int r = 0; r < R; ++r) x[r] = load_pair<S>(base + r * ld + 2 * p);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            gl::acc_mac(acc[r], to_field<S>((S)x[r].x), e.x);
-            gl::acc_mac(acc[r], to_field<S>((S)x[r].y), e.y);
+            uint64_t f0, f1;
+            unpack<S>(x[r], f0, f1);
+            gl::acc_mac(acc[r], f0, e.x);
+            gl::acc_mac(acc[r], f1, e.y);
         }
     }
 }
@@ -181,7 +218,7 @@ __global__ __launch_bounds__(kBlock) void reduce_over_cols_kernel(const S* __res
         uint64_t e = eqb[c];
 #pragma unroll
         for (int r = 0; r < R; ++r)
-            if (row0 + r < rows) gl::acc_mac(acc[r], to_field<S>(base[r * ld + c]), e);
+            if (row0 + r < rows) gl::acc_mac(acc[r], to_field<S>(load_one<S>(base + r * ld + c)), e);
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -224,7 +261,7 @@ __global__ __launch_bounds__(kBlock) void reduce_over_rows_kernel(const S* __res
     if (r_end > rows) r_end = rows;
     uint64_t* out = partial + (uint64_t)blockIdx.y * cols;
     if (VEC) {
-        using V2 = typename Pair<S>::type;
+        using Raw = typename RawPair<S>::type;
         const uint64_t col = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 2;
         if (col >= cols) return;
         gl::Acc a0, a1;
@@ -234,21 +271,22 @@ __global__ __launch_bounds__(kBlock) void reduce_over_rows_kernel(const S* __res
             const S* p = T + r_begin * ld + col;
             uint64_t i = r_begin;
             for (; i + kRowsUnroll <= r_end; i += kRowsUnroll, p += kRowsUnroll * ld) {
-                V2 x[kRowsUnroll];
+                Raw x[kRowsUnroll];
 #pragma unroll
-                for (int u = 0; u < kRowsUnroll; ++u) x[u] = *reinterpret_cast<const V2*>(p + u * ld);
+                for (int u = 0; u < kRowsUnroll; ++u) x[u] = load_pair<S>(p + u * ld);
 #pragma unroll
                 for (int u = 0; u < kRowsUnroll; ++u) {
-                    uint64_t e = eq[i + u];
-                    gl::acc_mac(a0, to_field<S>((S)x[u].x), e);
-                    gl::acc_mac(a1, to_field<S>((S)x[u].y), e);
+                    uint64_t e = eq[i + u], f0, f1;
+                    unpack<S>(x[u], f0, f1);
+                    gl::acc_mac(a0, f0, e);
+                    gl::acc_mac(a1, f1, e);
                 }
             }
             for (; i < r_end; ++i, p += ld) {
-                uint64_t e = eq[i];
-                V2 x = *reinterpret_cast<const V2*>(p);
-                gl::acc_mac(a0, to_field<S>((S)x.x), e);
-                gl::acc_mac(a1, to_field<S>((S)x.y), e);
+                uint64_t e = eq[i], f0, f1;
+                unpack<S>(load_pair<S>(p), f0, f1);
+                gl::acc_mac(a0, f0, e);
+                gl::acc_mac(a1, f1, e);
             }
             out[col] = gl::acc_reduce(a0);
             out[col + 1] = gl::acc_reduce(a1);
@@ -383,6 +421,121 @@ __global__ void fold_last_kernel(uint64_t* __restrict__ a, uint64_t* __restrict_
     out3[0] = va; out3[1] = vb; out3[2] = 0;
 }
 
+// ------------------------------------------------------------------ all rounds in one launch
+// One workgroup runs every remaining round of a proof: evaluate g_k(0,1,2), hash it into the
+// transcript on the device, squeeze r_k, fold, repeat.  The tables have at most kRoundsMaxL
+// entries (they stay L2-resident), so the loop is bound by the three SHA-256 compressions per
+// round that lane 0 performs, not by memory; the host is not involved until the final copy.
+constexpr int kRoundsBlock = 1024;
+constexpr int kRoundsWaves = kRoundsBlock / 64;
+
+struct Triple {
+    uint64_t g0, g1, g2;
+};
+
+__device__ __forceinline__ Triple rounds_block_sum(Triple v, uint64_t (*lds)[3]) {
+    v.g0 = wave_sum(v.g0);
+    v.g1 = wave_sum(v.g1);
+    v.g2 = wave_sum(v.g2);
+    if ((threadIdx.x & 63) == 0) {
+        lds[threadIdx.x >> 6][0] = v.g0;
+        lds[threadIdx.x >> 6][1] = v.g1;
+        lds[threadIdx.x >> 6][2] = v.g2;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kRoundsWaves; ++w) {
+            v.g0 = gl::add(v.g0, lds[w][0]);
+            v.g1 = gl::add(v.g1, lds[w][1]);
+            v.g2 = gl::add(v.g2, lds[w][2]);
+        }
+    }
+    return v;  // valid in thread 0
+}
+
+__device__ __forceinline__ void pair_eval(Triple& acc, uint64_t a0, uint64_t a1, uint64_t b0, uint64_t b1) {
+    uint64_t a2 = gl::sub(gl::add(a1, a1), a0);
+    uint64_t b2 = gl::sub(gl::add(b1, b1), b0);
+    acc.g0 = gl::add(acc.g0, gl::mul(a0, b0));
+    acc.g1 = gl::add(acc.g1, gl::mul(a1, b1));
+    acc.g2 = gl::add(acc.g2, gl::mul(a2, b2));
+}
+
+__global__ __launch_bounds__(kRoundsBlock) void rounds_kernel(uint64_t* __restrict__ a, uint64_t* __restrict__ b,
+                                                             uint64_t L, int rounds, int first_k, int absorb_claim,
+                                                             sha::State st_in, uint64_t* __restrict__ words,
+                                                             uint32_t* __restrict__ state_out) {
+    __shared__ uint64_t lds[kRoundsWaves][3];
+    __shared__ uint64_t r_shared;
+    const uint32_t tid = threadIdx.x;
+    uint32_t s[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s[i] = st_in.h[i];
+
+    // evaluation of the current tables (no fold yet)
+    Triple g = {0, 0, 0};
+    {
+        const uint64_t h = L >> 1;
+        for (uint64_t i = tid; i < h; i += kRoundsBlock) pair_eval(g, a[i], a[i + h], b[i], b[i + h]);
+    }
+    g = rounds_block_sum(g, lds);
+    if (tid == 0 && absorb_claim) {
+        uint64_t c0 = gl::add(g.g0, g.g1);
+        words[kWordC0] = c0;
+        sha::absorb_words(s, sha::TAG_CLMC, &c0, 1);
+    }
+
+    for (int kk = 0; kk < rounds; ++kk) {
+        if (tid == 0) {
+            const uint64_t gw[3] = {g.g0, g.g1, g.g2};
+            words[kWordG + 3 * (first_k + kk) + 0] = gw[0];
+            words[kWordG + 3 * (first_k + kk) + 1] = gw[1];
+            words[kWordG + 3 * (first_k + kk) + 2] = gw[2];
+            sha::absorb_words(s, sha::TAG_RND, gw, 3);
+            const uint64_t r = sha::challenge(s);
+            words[kWordR + first_k + kk] = r;
+            r_shared = r;
+        }
+        __syncthreads();
+        const uint64_t r = r_shared;
+        g = {0, 0, 0};
+        const uint64_t h = L >> 1, q = L >> 2;
+        if (L == 2) {
+            if (tid == 0) {
+                g.g0 = gl::add(a[0], gl::mul(r, gl::sub(a[1], a[0])));
+                g.g1 = gl::add(b[0], gl::mul(r, gl::sub(b[1], b[0])));
+                a[0] = g.g0;
+                b[0] = g.g1;
+            }
+        } else {
+            for (uint64_t i = tid; i < q; i += kRoundsBlock) {
+                uint64_t x0 = a[i], x1 = a[i + q], x2 = a[i + h], x3 = a[i + h + q];
+                uint64_t y0 = b[i], y1 = b[i + q], y2 = b[i + h], y3 = b[i + h + q];
+                uint64_t a0 = gl::add(x0, gl::mul(r, gl::sub(x2, x0)));
+                uint64_t a1 = gl::add(x1, gl::mul(r, gl::sub(x3, x1)));
+                uint64_t b0 = gl::add(y0, gl::mul(r, gl::sub(y2, y0)));
+                uint64_t b1 = gl::add(y1, gl::mul(r, gl::sub(y3, y1)));
+                a[i] = a0; a[i + q] = a1;
+                b[i] = b0; b[i + q] = b1;
+                pair_eval(g, a0, a1, b0, b1);
+            }
+            g = rounds_block_sum(g, lds);  // contains a barrier: the folded entries are visible to the block
+        }
+        L = h;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        // after the last fold g holds (a[0], b[0], -)
+        const uint64_t fin[2] = {g.g0, g.g1};
+        words[kWordVA] = fin[0];
+        words[kWordVB] = fin[1];
+        sha::absorb_words(s, sha::TAG_FIN, fin, 2);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) state_out[i] = s[i];
+    }
+}
+
 constexpr uint32_t kMaxRoundBlocks = 2048;
 
 uint32_t round_blocks(uint64_t items) {
@@ -494,6 +647,15 @@ hipError_t round(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, bool 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || nb == 1) return e;
     hipLaunchKernelGGL(round_finish_kernel, dim3(1), dim3(kBlock), 0, stream, scratch, nb, out3);
+    return hipGetLastError();
+}
+
+hipError_t rounds(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, int nrounds, int first_k, bool absorb_claim,
+                  const uint32_t state_in[8], uint64_t* words, uint32_t* state_out) {
+    sha::State st;
+    for (int i = 0; i < 8; ++i) st.h[i] = state_in[i];
+    hipLaunchKernelGGL(rounds_kernel, dim3(1), dim3(kRoundsBlock), 0, stream, a, b, L, nrounds, first_k,
+                       absorb_claim ? 1 : 0, st, words, state_out);
     return hipGetLastError();
 }
 

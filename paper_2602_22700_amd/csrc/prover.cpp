@@ -126,7 +126,7 @@ struct imm_ctx {
 
 namespace imm {
 
-constexpr size_t kWordsDev = 3 + 3 * IMM_MAX_ROUNDS + 3;  // c0, vA, vB, g[...], final triple
+constexpr size_t kWordsDev = k::kWordCount + 4;  // proof words and challenges, then the 32-byte state
 
 static bool dim_ok(uint64_t v) { return v >= 1 && v <= (1ull << IMM_MAX_ROUNDS); }
 
@@ -259,7 +259,6 @@ static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uin
     out->delta = (uint32_t)delta;
     out->nu = (uint32_t)nu;
 
-    uint64_t fin[3];
     if (delta == 0) {
         // a single shared index: the claim is the product of the two table entries
         uint64_t av, bv;
@@ -267,33 +266,61 @@ static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uin
         if ((rc = fetch_words(ctx, s, b, 1, &bv))) return rc;
         out->c0 = hf::mul(av, bv);
         tr.absorb_words("clmC", &out->c0, 1);
-        fin[0] = av;
-        fin[1] = bv;
+        out->vA = av;
+        out->vB = bv;
+        const uint64_t fin[2] = {av, bv};
+        tr.absorb_words("fin ", fin, 2);
+        std::memcpy(state, tr.s, 32);
     } else {
-        // a5/a6: first evaluation, then delta times (absorb, squeeze, fold + evaluate)
-        uint64_t g[3];
-        if ((rc = run_round(ctx, s, a, b, D, false, 0, words + 3, g))) return rc;
-        out->c0 = hf::add(g[0], g[1]);
-        tr.absorb_words("clmC", &out->c0, 1);
+        // a5..a8.  Tables longer than the single-workgroup limit are first shortened with one
+        // launch and one host round-trip per round; the remaining rounds run in one launch that
+        // hashes the transcript on the device.
         uint64_t L = D;
-        for (int kk = 0; kk < delta; ++kk) {
-            out->g[3 * kk] = g[0];
-            out->g[3 * kk + 1] = g[1];
-            out->g[3 * kk + 2] = g[2];
-            tr.absorb_words("rnd ", g, 3);
-            rr[kk] = tr.challenge();
-            uint64_t* dst = words + 3 + 3 * (kk + 1);
-            if ((rc = run_round(ctx, s, a, b, L, true, rr[kk], dst, g))) return rc;
-            L >>= 1;
+        int kk = 0;
+        bool claim_absorbed = false;
+        if (L > k::kRoundsMaxL) {
+            uint64_t g[3];
+            if ((rc = run_round(ctx, s, a, b, L, false, 0, words + k::kWordG, g))) return rc;
+            out->c0 = hf::add(g[0], g[1]);
+            tr.absorb_words("clmC", &out->c0, 1);
+            claim_absorbed = true;
+            for (; L > k::kRoundsMaxL; ++kk) {
+                out->g[3 * kk] = g[0];
+                out->g[3 * kk + 1] = g[1];
+                out->g[3 * kk + 2] = g[2];
+                tr.absorb_words("rnd ", g, 3);
+                rr[kk] = tr.challenge();
+                if ((rc = run_round(ctx, s, a, b, L, true, rr[kk], words + k::kWordG, g))) return rc;
+                L >>= 1;
+            }
         }
-        fin[0] = g[0];  // after the last fold the kernel returns (a[0], b[0], 0)
-        fin[1] = g[1];
+        uint32_t st_in[8];
+        for (int i = 0; i < 8; ++i)
+            st_in[i] = (uint32_t)tr.s[4 * i] << 24 | (uint32_t)tr.s[4 * i + 1] << 16 | (uint32_t)tr.s[4 * i + 2] << 8 |
+                       (uint32_t)tr.s[4 * i + 3];
+        uint32_t* st_dev = reinterpret_cast<uint32_t*>(words + k::kWordCount);
+        if ((rc = ctx->prof.begin(IMM_K_ROUND, s))) return rc;
+        IMM_HIP(k::rounds(s, a, b, L, delta - kk, kk, !claim_absorbed, st_in, words, st_dev));
+        if ((rc = ctx->prof.end(IMM_K_ROUND, s))) return rc;
+        uint64_t hw[kWordsDev];
+        if ((rc = fetch_words(ctx, s, words, kWordsDev, hw))) return rc;
+        if (!claim_absorbed) out->c0 = hw[k::kWordC0];
+        for (int t = kk; t < delta; ++t) {
+            out->g[3 * t] = hw[k::kWordG + 3 * t];
+            out->g[3 * t + 1] = hw[k::kWordG + 3 * t + 1];
+            out->g[3 * t + 2] = hw[k::kWordG + 3 * t + 2];
+            rr[t] = hw[k::kWordR + t];
+        }
+        out->vA = hw[k::kWordVA];
+        out->vB = hw[k::kWordVB];
+        const uint32_t* st_out = reinterpret_cast<const uint32_t*>(hw + k::kWordCount);
+        for (int i = 0; i < 8; ++i) {
+            state[4 * i] = (uint8_t)(st_out[i] >> 24);
+            state[4 * i + 1] = (uint8_t)(st_out[i] >> 16);
+            state[4 * i + 2] = (uint8_t)(st_out[i] >> 8);
+            state[4 * i + 3] = (uint8_t)st_out[i];
+        }
     }
-    out->vA = fin[0];
-    out->vB = fin[1];
-    tr.absorb_words("fin ", fin, 2);
-    std::memcpy(state, tr.s, 32);
-
     if (ctx->debug) {
         ctx->dbg_mu = mu; ctx->dbg_delta = delta; ctx->dbg_nu = nu;
         std::memcpy(ctx->dbg_rx, rx, sizeof(rx));
