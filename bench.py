@@ -48,6 +48,8 @@ def main():
     ap.add_argument("--workload", default="ffn_up", choices=["ffn_up", "attn", "tiny", "dense_layer"])
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="time budget of the CPU-oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--transcript", default="host", choices=["device", "host"],
+                    help="who hashes the round messages: lane 0 of the round kernel, or the host via the mailbox")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU only: the prover path has no multi-GPU part in this build "
@@ -63,24 +65,27 @@ def main():
     imm.load()
     stmts = make_workload(args.workload, torch, imm, workloads)
     ctx = imm.Context(0)
+    ctx.imm_ctx_set_option(imm.IMM_OPT_TRANSCRIPT,
+                           imm.IMM_TRANSCRIPT_HOST if args.transcript == "host" else imm.IMM_TRANSCRIPT_DEVICE)
     items = [(Ad, Bd, com) for (_, _, Ad, Bd, com) in stmts]
     chained = len(items) > 1
     s0 = imm.imm_fs_init()
 
-    def step():
-        return ctx.imm_sumcheck_matmul_prove_batch(items, chained, s0)
+    batch = ctx.prepare_batch(items, chained, s0)   # arguments marshalled once; a step is one C call
+    step = batch.run
 
     for _ in range(args.warmup):
-        proofs, _, _ = step()
+        step()
     dominant = imm.IMM_K_REDUCE_B
     ctx.imm_ctx_reset_profiling()
     ctx.imm_ctx_set_profiling(1 << dominant)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        proofs, _, _ = step()
+        step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    proofs = batch.proofs
     ctx.imm_ctx_set_profiling(0)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     n_dom, ms_dom = ctx.imm_ctx_kernel_time(dominant)
@@ -112,15 +117,17 @@ def main():
 
     # the same step with the weights widened beforehand (deployment-time encoding)
     items_pre = [(Ad, ctx.imm_encode(Bd), com) for (Ad, Bd, com) in items]
+    batch_pre = ctx.prepare_batch(items_pre, chained, s0)
     for _ in range(2):
-        ctx.imm_sumcheck_matmul_prove_batch(items_pre, chained, s0)
+        batch_pre.run()
     torch.cuda.synchronize()
     t2 = time.perf_counter()
     for _ in range(args.steps):
-        pre_proofs, _, _ = ctx.imm_sumcheck_matmul_prove_batch(items_pre, chained, s0)
+        batch_pre.run()
     torch.cuda.synchronize()
     ms_pre = (time.perf_counter() - t2) * 1e3 / args.steps
-    del items_pre
+    pre_proofs = batch_pre.proofs
+    del items_pre, batch_pre
 
     result = {
         "metric": "matmul_sumcheck_prove_time_per_layer", "value": round(ms_per_step, 4), "unit": "ms",
@@ -129,7 +136,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload,
                    "statements": [{"m": A.shape[0], "d": A.shape[1], "n": B.shape[1]} for (A, B, _, _, _) in stmts],
-                   "A": "int16 Gaussian sigma=2^10", "B": "int8 uniform", "transcript": "SHA-256 Fiat-Shamir",
+                   "A": "int16 Gaussian sigma=2^10", "B": "int8 uniform", "transcript": "SHA-256 Fiat-Shamir, hashed on the " + args.transcript,
                    "includes": "encode A+B, eq, reduce A+B, rounds, hashing"},
         "prove_ms_weights_preencoded": round(ms_pre, 4),
         "kernels": kernels,

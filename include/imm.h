@@ -210,6 +210,17 @@ int imm_debug_fetch(imm_ctx* ctx, int which, uint64_t* out_host, uint64_t capaci
 #define IMM_OPT_WIDEN 2           /* value != 0 (default): raw int8/int16 operands of a proof go through the
                                      encoding pass and are streamed as 8-byte field elements; value 0: the
                                      reductions read the narrow integers directly and encode in registers */
+#define IMM_OPT_TRANSCRIPT 3      /* who hashes the round messages while the round kernel runs (default
+                                     IMM_TRANSCRIPT_HOST).  IMM_TRANSCRIPT_DEVICE: lane 0 of the round kernel (no host involvement
+                                     until the final copy); IMM_TRANSCRIPT_HOST: the calling thread, which
+                                     exchanges g_k / r_k with the running kernel through a mailbox in pinned
+                                     host memory (lower latency per round; both sides wait with a bound) */
+#define IMM_TRANSCRIPT_DEVICE 0
+#define IMM_TRANSCRIPT_HOST 1
+#define IMM_OPT_SPIN_LIMIT 4      /* host-transcript mode: polls the kernel spends per round waiting for r_k
+                                     before it gives up and exits (default 2^21, about four seconds) */
+#define IMM_OPT_HOST_WAIT_MS 5    /* host-transcript mode: milliseconds the host waits for a mailbox slot
+                                     before it aborts the kernel and returns IMM_E_HIP (default 30000) */
 int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value);
 
 /* Per-kernel timing with HIP events on the launch stream.  Kernel ids: */

@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libimm.so")
 
 IMM_MAX_ROUNDS = 32
 IMM_I8, IMM_I16, IMM_I64, IMM_F64P = 1, 2, 3, 4
-IMM_OPT_DEBUG_SNAPSHOTS, IMM_OPT_WIDEN = 1, 2
+IMM_OPT_DEBUG_SNAPSHOTS, IMM_OPT_WIDEN, IMM_OPT_TRANSCRIPT, IMM_OPT_SPIN_LIMIT, IMM_OPT_HOST_WAIT_MS = 1, 2, 3, 4, 5
+IMM_TRANSCRIPT_DEVICE, IMM_TRANSCRIPT_HOST = 0, 1
 (IMM_K_ENCODE_A, IMM_K_ENCODE_B, IMM_K_EQ, IMM_K_REDUCE_A, IMM_K_REDUCE_B, IMM_K_ROUND,
  IMM_K_COMBINE, IMM_K_COUNT) = range(8)
 KERNEL_NAMES = ["encode_A", "encode_B", "eq_build", "reduce_A", "reduce_B", "round", "combine"]
@@ -270,6 +271,10 @@ class Context:
         sb = bytes(states)
         return ([proofs[t].copy() for t in range(count)], [sb[32 * t:32 * t + 32] for t in range(count)], bytes(st))
 
+    def prepare_batch(self, items, chained: bool, state: bytes, stream=None) -> "PreparedBatch":
+        """Marshal a batch once; PreparedBatch.run() then only performs the C call."""
+        return PreparedBatch(self, items, chained, state, stream)
+
     def imm_round_fold_eval(self, a, b, L: int, fold_r: Optional[int] = None, stream=None) -> List[int]:
         import torch
         assert a.is_cuda and b.is_cuda and a.dtype == torch.uint64 and b.dtype == torch.uint64
@@ -289,3 +294,53 @@ class Context:
             _check(load().imm_debug_fetch(self._h, which, out.ctypes.data, cnt.value, ctypes.byref(cnt)),
                    "imm_debug_fetch")
         return out
+
+
+class PreparedBatch:
+    """Pre-marshalled arguments of imm_sumcheck_matmul_prove_batch for repeated calls on the same
+    device buffers (what a serving loop or a benchmark does).  run() resets the starting state and
+    forwards to the C entry point; the results are read from .proofs / .states / .final_state."""
+
+    def __init__(self, ctx: Context, items, chained: bool, state: bytes, stream=None):
+        self._ctx = ctx
+        self._count = len(items)
+        n = max(self._count, 1)
+        self._descs = (MatmulDesc * n)()
+        self._keep = []
+        for t, (A, B, com) in enumerate(items):
+            assert A.is_cuda and B.is_cuda and A.is_contiguous() and B.is_contiguous()
+            m, d = A.shape
+            d2, nn = B.shape
+            assert d == d2
+            self._descs[t].A_dev, self._descs[t].B_dev = A.data_ptr(), B.data_ptr()
+            self._descs[t].dtA, self._descs[t].dtB = _tensor_dtype(A), _tensor_dtype(B)
+            self._descs[t].m, self._descs[t].d, self._descs[t].n = m, d, nn
+            self._descs[t].com = ctypes.pointer(com)
+            self._keep.append((A, B, com))
+        self._proofs = (Proof * n)()
+        self._states = (ctypes.c_uint8 * (32 * n))()
+        self._state0 = bytes(state)
+        self._st = (ctypes.c_uint8 * 32)()
+        self._chained = 1 if chained else 0
+        self._stream = _stream_handle(stream)
+        self._fn = load().imm_sumcheck_matmul_prove_batch
+
+    def run(self) -> None:
+        ctypes.memmove(self._st, self._state0, 32)
+        rc = self._fn(self._ctx._h, self._stream, self._count, self._descs, self._chained, self._st, self._proofs,
+                      self._states)
+        if rc:
+            _check(rc, "imm_sumcheck_matmul_prove_batch")
+
+    @property
+    def proofs(self) -> List[Proof]:
+        return [self._proofs[t].copy() for t in range(self._count)]
+
+    @property
+    def states(self) -> List[bytes]:
+        sb = bytes(self._states)
+        return [sb[32 * t:32 * t + 32] for t in range(self._count)]
+
+    @property
+    def final_state(self) -> bytes:
+        return bytes(self._st)

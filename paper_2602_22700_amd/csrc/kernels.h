@@ -70,5 +70,22 @@ constexpr uint64_t kRoundsMaxL = 1ull << 15;  // longest table the single-workgr
 hipError_t rounds(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, int nrounds, int first_k, bool absorb_claim,
                   const uint32_t state_in[8], uint64_t* words, uint32_t* state_out);
 
+// Mailbox in pinned, coherent host memory shared by rounds_mailbox() and the host thread that
+// hashes the transcript.  Every slot holds kMailEmpty until its owner writes it.
+constexpr uint64_t kMailEmpty = 0xFFFFFFFFFFFFFFFFull;  // not a canonical field element
+constexpr uint64_t kMailAbort = 0xFFFFFFFFFFFFFFFEull;  // host -> device: stop waiting
+struct Mailbox {
+    uint64_t g[IMM_MAX_ROUNDS][4];  // device -> host: g_k(0), g_k(1), g_k(2), unused
+    uint64_t r[IMM_MAX_ROUNDS];     // host -> device: r_k
+    uint64_t fin[4];                // device -> host: a[0], b[0] after the last fold
+};
+
+// The same `nrounds` rounds as rounds(), with the host supplying the challenges through
+// `mailbox` (a device-visible pointer to pinned host memory, slots preset to kMailEmpty).
+// Lane 0 waits at most `spin_limit` polls per round; status[0] (device memory) becomes 0 on
+// completion and 1 if a wait ran out or the host posted kMailAbort.
+hipError_t rounds_mailbox(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, int nrounds, Mailbox* mailbox,
+                          uint64_t spin_limit, uint64_t* status);
+
 }  // namespace k
 }  // namespace imm

@@ -272,11 +272,17 @@ __global__ __launch_bounds__(kBlock) void reduce_over_rows_kernel(const S* __res
             uint64_t i = r_begin;
             for (; i + kRowsUnroll <= r_end; i += kRowsUnroll, p += kRowsUnroll * ld) {
                 Raw x[kRowsUnroll];
+                uint64_t ew[kRowsUnroll];
 #pragma unroll
                 for (int u = 0; u < kRowsUnroll; ++u) x[u] = load_pair<S>(p + u * ld);
 #pragma unroll
+                for (int u = 0; u < kRowsUnroll; ++u) ew[u] = eq[i + u];
+                // keep the loads of a trip together: without this the scheduler sinks each load
+                // next to its use and the wave has a single request in flight
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
                 for (int u = 0; u < kRowsUnroll; ++u) {
-                    uint64_t e = eq[i + u], f0, f1;
+                    uint64_t e = ew[u], f0, f1;
                     unpack<S>(x[u], f0, f1);
                     gl::acc_mac(a0, f0, e);
                     gl::acc_mac(a1, f1, e);
@@ -536,6 +542,84 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_kernel(uint64_t* __restri
     }
 }
 
+// ------------------------------------------------------------------ all rounds in one launch, host hashes
+// Same loop as rounds_kernel, but the transcript stays on the host: lane 0 posts g_k into a
+// mailbox in pinned host memory and polls the slot where the host thread (spinning on the same
+// mailbox inside the prove call) deposits r_k.  Slots start as kMailEmpty, a value no canonical
+// field element can take, so one 8-byte access both signals and carries the value.  The wait is
+// bounded: after `spin_limit` polls, or when the host posts kMailAbort, every wave leaves the
+// kernel and status[0] is set.
+__device__ __forceinline__ void mail_post(uint64_t* slot, uint64_t v) {
+    __hip_atomic_store(slot, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+__device__ __forceinline__ uint64_t mail_peek(const uint64_t* slot) {
+    return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+__global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(uint64_t* __restrict__ a,
+                                                                     uint64_t* __restrict__ b, uint64_t L,
+                                                                     int rounds, Mailbox* mb, uint64_t spin_limit,
+                                                                     uint64_t* __restrict__ status) {
+    __shared__ uint64_t lds[kRoundsWaves][3];
+    __shared__ uint64_t r_shared;
+    const uint32_t tid = threadIdx.x;
+    Triple g = {0, 0, 0};
+    {
+        const uint64_t h = L >> 1;
+        for (uint64_t i = tid; i < h; i += kRoundsBlock) pair_eval(g, a[i], a[i + h], b[i], b[i + h]);
+    }
+    g = rounds_block_sum(g, lds);
+    for (int kk = 0; kk < rounds; ++kk) {
+        if (tid == 0) {
+            mail_post(&mb->g[kk][0], g.g0);
+            mail_post(&mb->g[kk][1], g.g1);
+            mail_post(&mb->g[kk][2], g.g2);
+            uint64_t r = kMailEmpty;
+            for (uint64_t spin = 0; spin < spin_limit; ++spin) {
+                r = mail_peek(&mb->r[kk]);
+                if (r != kMailEmpty) break;
+            }
+            r_shared = r;
+        }
+        __syncthreads();
+        const uint64_t r = r_shared;
+        if (r >= gl::P) {  // no answer within the limit, or the host gave up: uniform exit
+            if (tid == 0) status[0] = 1;
+            return;
+        }
+        g = {0, 0, 0};
+        const uint64_t h = L >> 1, q = L >> 2;
+        if (L == 2) {
+            if (tid == 0) {
+                g.g0 = gl::add(a[0], gl::mul(r, gl::sub(a[1], a[0])));
+                g.g1 = gl::add(b[0], gl::mul(r, gl::sub(b[1], b[0])));
+                a[0] = g.g0;
+                b[0] = g.g1;
+            }
+        } else {
+            for (uint64_t i = tid; i < q; i += kRoundsBlock) {
+                uint64_t x0 = a[i], x1 = a[i + q], x2 = a[i + h], x3 = a[i + h + q];
+                uint64_t y0 = b[i], y1 = b[i + q], y2 = b[i + h], y3 = b[i + h + q];
+                uint64_t a0 = gl::add(x0, gl::mul(r, gl::sub(x2, x0)));
+                uint64_t a1 = gl::add(x1, gl::mul(r, gl::sub(x3, x1)));
+                uint64_t b0 = gl::add(y0, gl::mul(r, gl::sub(y2, y0)));
+                uint64_t b1 = gl::add(y1, gl::mul(r, gl::sub(y3, y1)));
+                a[i] = a0; a[i + q] = a1;
+                b[i] = b0; b[i + q] = b1;
+                pair_eval(g, a0, a1, b0, b1);
+            }
+            g = rounds_block_sum(g, lds);
+        }
+        L = h;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        mail_post(&mb->fin[0], g.g0);
+        mail_post(&mb->fin[1], g.g1);
+        status[0] = 0;
+    }
+}
+
 constexpr uint32_t kMaxRoundBlocks = 2048;
 
 uint32_t round_blocks(uint64_t items) {
@@ -656,6 +740,13 @@ hipError_t rounds(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, int 
     for (int i = 0; i < 8; ++i) st.h[i] = state_in[i];
     hipLaunchKernelGGL(rounds_kernel, dim3(1), dim3(kRoundsBlock), 0, stream, a, b, L, nrounds, first_k,
                        absorb_claim ? 1 : 0, st, words, state_out);
+    return hipGetLastError();
+}
+
+hipError_t rounds_mailbox(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, int nrounds, Mailbox* mailbox,
+                          uint64_t spin_limit, uint64_t* status) {
+    hipLaunchKernelGGL(rounds_mailbox_kernel, dim3(1), dim3(kRoundsBlock), 0, stream, a, b, L, nrounds, mailbox,
+                       spin_limit, status);
     return hipGetLastError();
 }
 

@@ -3,6 +3,8 @@
 // host only hashes and moves a few words per round.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+#include <chrono>
 #include <cstdio>
 #include <cstring>
 #include <string>
@@ -116,6 +118,10 @@ struct imm_ctx {
     int device = 0;
     imm::DevBuf encA, encB, eqx, eqy, a, b, partA, partB, round_scratch, words, snapA, snapB;
     uint64_t* pinned = nullptr;  // host staging, 4 KiB
+    imm::k::Mailbox* mailbox = nullptr;  // pinned + coherent: g_k out, r_k in (host-transcript mode)
+    int transcript_mode = IMM_TRANSCRIPT_HOST;
+    uint64_t spin_limit = 1ull << 21;    // device polls per round before giving up (about 2 us each)
+    int64_t host_wait_ms = 30000;        // host patience per mailbox slot
     imm::Profiler prof;
     bool debug = false;
     bool widen = true;
@@ -126,7 +132,7 @@ struct imm_ctx {
 
 namespace imm {
 
-constexpr size_t kWordsDev = k::kWordCount + 4;  // proof words and challenges, then the 32-byte state
+constexpr size_t kWordsDev = k::kWordCount + 5;  // proof words and challenges, the 32-byte state, one status word
 
 static bool dim_ok(uint64_t v) { return v >= 1 && v <= (1ull << IMM_MAX_ROUNDS); }
 
@@ -200,6 +206,106 @@ static int run_round(imm_ctx* ctx, hipStream_t s, uint64_t* a, uint64_t* b, uint
     return fetch_words(ctx, s, out3_dev, 3, host3);
 }
 
+// Wait until a mailbox slot written by the device leaves the empty state.
+static bool mail_wait(const uint64_t* slot, int64_t patience_ms, uint64_t* value) {
+    const volatile uint64_t* p = slot;
+    auto t0 = std::chrono::steady_clock::now();
+    for (uint64_t spin = 0;; ++spin) {
+        uint64_t v = *p;
+        if (v != k::kMailEmpty) {
+            std::atomic_thread_fence(std::memory_order_acquire);
+            *value = v;
+            return true;
+        }
+        if ((spin & 0xFFF) == 0xFFF) {
+            auto dt = std::chrono::steady_clock::now() - t0;
+            if (std::chrono::duration_cast<std::chrono::milliseconds>(dt).count() > patience_ms) return false;
+        }
+        __builtin_ia32_pause();
+    }
+}
+
+// Rounds kk0 .. delta-1 with the round kernel running on the device and this thread hashing:
+// the kernel posts g_k, the host absorbs it, squeezes r_k and posts it back.
+static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, uint64_t* a, uint64_t* b, uint64_t L, int delta,
+                                       int kk0, bool claim_absorbed, Transcript& tr, imm_proof* out, uint64_t* rr,
+                                       uint64_t* status_dev) {
+    k::Mailbox* mb = ctx->mailbox;
+    std::memset(mb, 0xFF, sizeof(*mb));
+    std::atomic_thread_fence(std::memory_order_seq_cst);
+    int rc;
+    if ((rc = ctx->prof.begin(IMM_K_ROUND, s))) return rc;
+    IMM_HIP(k::rounds_mailbox(s, a, b, L, delta - kk0, mb, ctx->spin_limit, status_dev));
+    if ((rc = ctx->prof.end(IMM_K_ROUND, s))) return rc;
+    bool ok = true;
+    int slot = 0;
+    for (int kk = kk0; kk < delta && ok; ++kk, ++slot) {
+        uint64_t g[3];
+        for (int t = 0; t < 3 && ok; ++t) ok = mail_wait(&mb->g[slot][t], ctx->host_wait_ms, &g[t]);
+        if (!ok) break;
+        if (!claim_absorbed) {
+            out->c0 = hf::add(g[0], g[1]);
+            tr.absorb_words("clmC", &out->c0, 1);
+            claim_absorbed = true;
+        }
+        out->g[3 * kk] = g[0];
+        out->g[3 * kk + 1] = g[1];
+        out->g[3 * kk + 2] = g[2];
+        tr.absorb_words("rnd ", g, 3);
+        rr[kk] = tr.challenge();
+        __atomic_store_n(&mb->r[slot], rr[kk], __ATOMIC_RELEASE);
+    }
+    uint64_t fin[2] = {0, 0};
+    if (ok) ok = mail_wait(&mb->fin[0], ctx->host_wait_ms, &fin[0]) && mail_wait(&mb->fin[1], ctx->host_wait_ms, &fin[1]);
+    if (!ok) {
+        // release the kernel from whatever wait it is in, then let it drain
+        for (int t = 0; t < IMM_MAX_ROUNDS; ++t) __atomic_store_n(&mb->r[t], k::kMailAbort, __ATOMIC_RELEASE);
+        IMM_HIP(hipStreamSynchronize(s));
+        g_last_error = "round kernel and host transcript lost contact (mailbox wait ran out)";
+        return IMM_E_HIP;
+    }
+    out->vA = fin[0];
+    out->vB = fin[1];
+    tr.absorb_words("fin ", fin, 2);
+    IMM_HIP(hipStreamSynchronize(s));
+    return IMM_OK;
+}
+
+// Rounds kk0 .. delta-1 in one launch that also hashes the transcript on the device; one copy
+// at the end brings back the proof words, the challenges and the new state.
+static int rounds_with_device_transcript(imm_ctx* ctx, hipStream_t s, uint64_t* a, uint64_t* b, uint64_t L, int delta,
+                                         int kk0, bool claim_absorbed, const Transcript& tr, imm_proof* out,
+                                         uint64_t* rr, uint64_t* words, uint8_t state[32]) {
+    int rc;
+    uint32_t st_in[8];
+    for (int i = 0; i < 8; ++i)
+        st_in[i] = (uint32_t)tr.s[4 * i] << 24 | (uint32_t)tr.s[4 * i + 1] << 16 | (uint32_t)tr.s[4 * i + 2] << 8 |
+                   (uint32_t)tr.s[4 * i + 3];
+    uint32_t* st_dev = reinterpret_cast<uint32_t*>(words + k::kWordCount);
+    if ((rc = ctx->prof.begin(IMM_K_ROUND, s))) return rc;
+    IMM_HIP(k::rounds(s, a, b, L, delta - kk0, kk0, !claim_absorbed, st_in, words, st_dev));
+    if ((rc = ctx->prof.end(IMM_K_ROUND, s))) return rc;
+    uint64_t hw[kWordsDev];
+    if ((rc = fetch_words(ctx, s, words, kWordsDev, hw))) return rc;
+    if (!claim_absorbed) out->c0 = hw[k::kWordC0];
+    for (int t = kk0; t < delta; ++t) {
+        out->g[3 * t] = hw[k::kWordG + 3 * t];
+        out->g[3 * t + 1] = hw[k::kWordG + 3 * t + 1];
+        out->g[3 * t + 2] = hw[k::kWordG + 3 * t + 2];
+        rr[t] = hw[k::kWordR + t];
+    }
+    out->vA = hw[k::kWordVA];
+    out->vB = hw[k::kWordVB];
+    const uint32_t* st_out = reinterpret_cast<const uint32_t*>(hw + k::kWordCount);
+    for (int i = 0; i < 8; ++i) {
+        state[4 * i] = (uint8_t)(st_out[i] >> 24);
+        state[4 * i + 1] = (uint8_t)(st_out[i] >> 16);
+        state[4 * i + 2] = (uint8_t)(st_out[i] >> 8);
+        state[4 * i + 3] = (uint8_t)st_out[i];
+    }
+    return IMM_OK;
+}
+
 static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uint8_t state[32], imm_proof* out) {
     if (!ds.A_dev || !ds.B_dev || !ds.com || !state || !out) return IMM_E_NULL;
     if (!dim_ok(ds.m) || !dim_ok(ds.d) || !dim_ok(ds.n)) return IMM_E_SHAPE;
@@ -214,7 +320,18 @@ static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uin
     uint64_t rx[IMM_MAX_ROUNDS] = {}, ry[IMM_MAX_ROUNDS] = {}, rr[IMM_MAX_ROUNDS] = {};
     tr.head(m, d, n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, mu, nu, rx, ry);
 
-    // a1: widen raw operands into scratch (skipped for pre-encoded tables or in narrow-read mode)
+    // a2: eq vectors for both points
+    if ((rc = build_eq(ctx, s, rx, mu, ry, nu))) return rc;
+    if ((rc = ctx->a.ensure(sizeof(uint64_t) * D))) return rc;
+    if ((rc = ctx->b.ensure(sizeof(uint64_t) * D))) return rc;
+    if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
+    uint64_t* a = ctx->a.u64();
+    uint64_t* b = ctx->b.u64();
+    uint64_t* words = ctx->words.u64();
+
+    // a1 + a3 for A, then a1 + a4 for B: each operand is widened into scratch (skipped for
+    // pre-encoded tables or in narrow-read mode) and reduced right away, so the reduction of A
+    // does not compete with the write stream of the much larger B.
     const void* Ap = ds.A_dev;
     const void* Bp = ds.B_dev;
     int dtA = (int)ds.dtA, dtB = (int)ds.dtB;
@@ -226,6 +343,7 @@ static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uin
         Ap = ctx->encA.p;
         dtA = IMM_F64P;
     }
+    if ((rc = partial_over_rows(ctx, s, IMM_K_REDUCE_A, Ap, dtA, m, d, d, ctx->eqx.u64(), D, ctx->partA, a))) return rc;
     if (ctx->widen && dtB != IMM_F64P) {
         if ((rc = ctx->encB.ensure(sizeof(uint64_t) * d * n))) return rc;
         if ((rc = ctx->prof.begin(IMM_K_ENCODE_B, s))) return rc;
@@ -234,16 +352,6 @@ static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uin
         Bp = ctx->encB.p;
         dtB = IMM_F64P;
     }
-
-    // a2: eq vectors; a3/a4: the two streaming partial evaluations
-    if ((rc = build_eq(ctx, s, rx, mu, ry, nu))) return rc;
-    if ((rc = ctx->a.ensure(sizeof(uint64_t) * D))) return rc;
-    if ((rc = ctx->b.ensure(sizeof(uint64_t) * D))) return rc;
-    if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
-    uint64_t* a = ctx->a.u64();
-    uint64_t* b = ctx->b.u64();
-    uint64_t* words = ctx->words.u64();
-    if ((rc = partial_over_rows(ctx, s, IMM_K_REDUCE_A, Ap, dtA, m, d, d, ctx->eqx.u64(), D, ctx->partA, a))) return rc;
     if ((rc = partial_over_cols(ctx, s, IMM_K_REDUCE_B, Bp, dtB, d, n, n, ctx->eqy.u64(), D, ctx->partB, b))) return rc;
 
     if (ctx->debug) {
@@ -294,31 +402,15 @@ static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uin
                 L >>= 1;
             }
         }
-        uint32_t st_in[8];
-        for (int i = 0; i < 8; ++i)
-            st_in[i] = (uint32_t)tr.s[4 * i] << 24 | (uint32_t)tr.s[4 * i + 1] << 16 | (uint32_t)tr.s[4 * i + 2] << 8 |
-                       (uint32_t)tr.s[4 * i + 3];
-        uint32_t* st_dev = reinterpret_cast<uint32_t*>(words + k::kWordCount);
-        if ((rc = ctx->prof.begin(IMM_K_ROUND, s))) return rc;
-        IMM_HIP(k::rounds(s, a, b, L, delta - kk, kk, !claim_absorbed, st_in, words, st_dev));
-        if ((rc = ctx->prof.end(IMM_K_ROUND, s))) return rc;
-        uint64_t hw[kWordsDev];
-        if ((rc = fetch_words(ctx, s, words, kWordsDev, hw))) return rc;
-        if (!claim_absorbed) out->c0 = hw[k::kWordC0];
-        for (int t = kk; t < delta; ++t) {
-            out->g[3 * t] = hw[k::kWordG + 3 * t];
-            out->g[3 * t + 1] = hw[k::kWordG + 3 * t + 1];
-            out->g[3 * t + 2] = hw[k::kWordG + 3 * t + 2];
-            rr[t] = hw[k::kWordR + t];
-        }
-        out->vA = hw[k::kWordVA];
-        out->vB = hw[k::kWordVB];
-        const uint32_t* st_out = reinterpret_cast<const uint32_t*>(hw + k::kWordCount);
-        for (int i = 0; i < 8; ++i) {
-            state[4 * i] = (uint8_t)(st_out[i] >> 24);
-            state[4 * i + 1] = (uint8_t)(st_out[i] >> 16);
-            state[4 * i + 2] = (uint8_t)(st_out[i] >> 8);
-            state[4 * i + 3] = (uint8_t)st_out[i];
+        if (ctx->transcript_mode == IMM_TRANSCRIPT_HOST) {
+            if ((rc = rounds_with_host_transcript(ctx, s, a, b, L, delta, kk, claim_absorbed, tr, out, rr,
+                                                  words + k::kWordCount + 4)))
+                return rc;
+            std::memcpy(state, tr.s, 32);
+        } else {
+            if ((rc = rounds_with_device_transcript(ctx, s, a, b, L, delta, kk, claim_absorbed, tr, out, rr, words,
+                                                    state)))
+                return rc;
         }
     }
     if (ctx->debug) {
@@ -354,11 +446,19 @@ extern "C" int imm_ctx_create(imm_ctx** out, int device, size_t scratch_bytes) {
         delete ctx;
         return fail_hip(e, "hipHostMalloc");
     }
+    e = hipHostMalloc(reinterpret_cast<void**>(&ctx->mailbox), sizeof(k::Mailbox),
+                      hipHostMallocMapped | hipHostMallocCoherent);
+    if (e != hipSuccess) {
+        (void)hipHostFree(ctx->pinned);
+        delete ctx;
+        return fail_hip(e, "hipHostMalloc(mailbox)");
+    }
     if (scratch_bytes) {
         // the hint goes to the widened weight table, by far the largest scratch buffer
         int rc = ctx->encB.ensure(scratch_bytes);
         if (rc) {
             (void)hipHostFree(ctx->pinned);
+            (void)hipHostFree(ctx->mailbox);
             delete ctx;
             return rc;
         }
@@ -376,6 +476,7 @@ extern "C" int imm_ctx_destroy(imm_ctx* ctx) {
         bf->release();
     ctx->prof.destroy();
     if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+    if (ctx->mailbox) (void)hipHostFree(ctx->mailbox);
     delete ctx;
     return IMM_OK;
 }
@@ -385,6 +486,18 @@ extern "C" int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value) {
     switch (option) {
     case IMM_OPT_DEBUG_SNAPSHOTS: ctx->debug = value != 0; return IMM_OK;
     case IMM_OPT_WIDEN: ctx->widen = value != 0; return IMM_OK;
+    case IMM_OPT_TRANSCRIPT:
+        if (value != IMM_TRANSCRIPT_DEVICE && value != IMM_TRANSCRIPT_HOST) return IMM_E_SHAPE;
+        ctx->transcript_mode = (int)value;
+        return IMM_OK;
+    case IMM_OPT_SPIN_LIMIT:
+        if (value < 0) return IMM_E_SHAPE;
+        ctx->spin_limit = (uint64_t)value;
+        return IMM_OK;
+    case IMM_OPT_HOST_WAIT_MS:
+        if (value < 1) return IMM_E_SHAPE;
+        ctx->host_wait_ms = value;
+        return IMM_OK;
     default: return IMM_E_STATE;
     }
 }

@@ -183,6 +183,12 @@ def check_proof(torch, ctx, oracle_fast, A, B, C=None, state=ref.FS_INIT, interm
     got2, s2 = ctx.imm_sumcheck_matmul_prove(Ad, Bd, com, state)
     ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
     assert got2.words() == got.words() and s2 == s_got
+    # the default hashes on the host through the mailbox while the round kernel runs;
+    # the same proof with the transcript hashed by the round kernel itself
+    ctx.imm_ctx_set_option(imm.IMM_OPT_TRANSCRIPT, imm.IMM_TRANSCRIPT_DEVICE)
+    got4, s4 = ctx.imm_sumcheck_matmul_prove(Ad, Bd, com, state)
+    ctx.imm_ctx_set_option(imm.IMM_OPT_TRANSCRIPT, imm.IMM_TRANSCRIPT_HOST)
+    assert got4.words() == got.words() and s4 == s_got
     Af, Bf = ctx.imm_encode(Ad), ctx.imm_encode(Bd)
     got3, s3 = ctx.imm_sumcheck_matmul_prove(Af, Bf, com, state)
     assert got3.words() == got.words() and s3 == s_got
@@ -338,6 +344,30 @@ def test_proofs_are_deterministic_and_survive_other_streams(torch, ctx, oracle_f
         p, s = ctx.imm_sumcheck_matmul_prove(Ad, Bd, com, ref.FS_INIT, stream=side)
     side.synchronize()
     assert p.words() == first.words() and s == s_first
+
+
+def test_host_transcript_bounded_waits(torch, oracle_fast):
+    """The round kernel's wait for a challenge is bounded.  With a spin limit of zero it gives up at
+    once, every wave leaves the kernel, the call reports an error after the host's own (shortened)
+    patience, and the context keeps working afterwards."""
+    A, B = workloads.tiny()
+    C = oracle_fast.matmul(A, B)
+    com = imm.imm_commit_matmul(A, B, C, 64, 64, 64)
+    Ad, Bd = dev(torch, A), dev(torch, B)
+    c = imm.Context(0)
+    want, s_want = c.imm_sumcheck_matmul_prove(Ad, Bd, com, ref.FS_INIT)
+    c.imm_ctx_set_option(imm.IMM_OPT_TRANSCRIPT, imm.IMM_TRANSCRIPT_HOST)
+    c.imm_ctx_set_option(imm.IMM_OPT_SPIN_LIMIT, 0)
+    c.imm_ctx_set_option(imm.IMM_OPT_HOST_WAIT_MS, 50)
+    with pytest.raises(imm.ImmError) as e:
+        c.imm_sumcheck_matmul_prove(Ad, Bd, com, ref.FS_INIT)
+    assert e.value.code == -5 and "mailbox" in str(e.value)
+    torch.cuda.synchronize()
+    c.imm_ctx_set_option(imm.IMM_OPT_SPIN_LIMIT, 1 << 21)
+    c.imm_ctx_set_option(imm.IMM_OPT_HOST_WAIT_MS, 30000)
+    got, s_got = c.imm_sumcheck_matmul_prove(Ad, Bd, com, ref.FS_INIT)
+    assert got.words() == want.words() and s_got == s_want
+    c.close()
 
 
 def test_argument_errors(torch, ctx):
