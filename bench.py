@@ -18,6 +18,23 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
 
 
+def recorded_traffic():
+    """HBM bytes per launch of the dominant kernel as measured with hardware counters (see
+    profiles/reduce_B_ffn_up_hbm_counters.txt); None once the kernel sources have changed since."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "reduce_B_ffn_up_hbm_counters.txt")
+    try:
+        kv = dict(line.split(" = ", 1) for line in open(path).read().splitlines() if " = " in line and not line.startswith(" "))
+        h = hashlib.sha256()
+        for fn in ("kernels.hip", "goldilocks.cuh"):
+            h.update(open(os.path.join(ROOT, "paper_2602_22700_amd", "csrc", fn), "rb").read())
+        if h.hexdigest() != kv["kernel_sources_sha256"].strip():
+            return None
+        return int(kv["traffic_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def make_workload(name, torch, imm, workloads):
     """Returns a list of (A_np, B_np, A_dev, B_dev, Commit): the statements of one step."""
     import numpy as np
@@ -48,6 +65,9 @@ def main():
     ap.add_argument("--workload", default="ffn_up", choices=["ffn_up", "attn", "tiny", "dense_layer"])
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="time budget of the CPU-oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 512 MiB device copy three times (reference dispatches for scaling "
+                         "hardware byte counters collected with rocprofv3 --pmc)")
     ap.add_argument("--transcript", default="host", choices=["device", "host"],
                     help="who hashes the round messages: lane 0 of the round kernel, or the host via the mailbox")
     args = ap.parse_args()
@@ -142,9 +162,19 @@ def main():
         "kernels": kernels,
         "roofline": {"bound": "hbm", "kernel": "reduce_B (partial MLE of B over its columns)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": recorded_traffic() if args.workload == "ffn_up" else None,
                      "avg_launch_us": round(avg_ms * 1e3, 2), "algorithmic_bytes_per_launch": 8.0 * b_entries / max(launches_per_step, 1)},
     }
+
+    if args.calibrate_copy:
+        src = torch.arange(64 << 20, dtype=torch.int64, device="cuda")   # 512 MiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        result["calibration_copy_bytes_each_way"] = src.numel() * 8
+        del src, dst
 
     if not args.no_cpu_baseline:
         from oracle import fast as oracle_fast
