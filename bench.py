@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--workload", default="ffn_up", choices=["ffn_up", "attn", "tiny", "dense_layer"])
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="time budget of the CPU-oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fold-log2", type=int, default=26,
+                    help="log2 of the table length of the stand-alone fold-kernel measurement (0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy three times (reference dispatches for scaling "
                          "hardware byte counters collected with rocprofv3 --pmc)")
@@ -166,6 +168,28 @@ def main():
                      "traffic": recorded_traffic() if args.workload == "ffn_up" else None,
                      "avg_launch_us": round(avg_ms * 1e3, 2), "algorithmic_bytes_per_launch": 8.0 * b_entries / max(launches_per_step, 1)},
     }
+
+    # The per-round kernel on tables large enough to be bandwidth-bound (the proof's own tables are
+    # 2 x 32 KB, i.e. latency-bound): fold + evaluate on two tables of 2^26 elements, in place.
+    # Algorithmic bytes per launch: 16 B read + 8 B written per table entry pair = 24 * L.
+    if args.fold_log2 > 0:
+        Lf = 1 << args.fold_log2
+        ta = torch.randint(0, 1 << 62, (Lf,), dtype=torch.int64, device="cuda").view(torch.uint64)
+        tb = torch.randint(0, 1 << 62, (Lf,), dtype=torch.int64, device="cuda").view(torch.uint64)
+        for _ in range(2):
+            ctx.imm_round_fold_eval(ta, tb, Lf, fold_r=0x123456789ABCDEF)
+        ctx.imm_ctx_reset_profiling()
+        ctx.imm_ctx_set_profiling(1 << imm.IMM_K_ROUND)
+        for _ in range(10):
+            ctx.imm_round_fold_eval(ta, tb, Lf, fold_r=0x123456789ABCDEF)
+        ctx.imm_ctx_set_profiling(0)
+        nf, msf = ctx.imm_ctx_kernel_time(imm.IMM_K_ROUND)
+        us = msf * 1e3 / nf
+        result["fold_kernel_large_tables"] = {"L": Lf, "us_per_launch": round(us, 1), "algorithmic_MB": 24 * Lf / 1e6,
+                                              "GBps": round(24 * Lf / (us * 1e-6) / 1e9, 1),
+                                              "frac_of_8TBps": round(24 * Lf / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 3)}
+        ctx.imm_ctx_reset_profiling()
+        del ta, tb
 
     if args.calibrate_copy:
         src = torch.arange(64 << 20, dtype=torch.int64, device="cuda")   # 512 MiB

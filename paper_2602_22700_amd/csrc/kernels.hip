@@ -399,6 +399,83 @@ __global__ __launch_bounds__(kBlock) void round_kernel(uint64_t* __restrict__ a,
     }
 }
 
+// Large tables: the same round with two adjacent items per thread, so that every access is a
+// 16-byte one and all eight (four without fold) loads of a trip are in flight together.  The
+// upper halves are dead after the fold and are read non-temporally; the lower halves are
+// rewritten in place and read again by the next round, so they use ordinary accesses unless
+// the tables are far larger than the last-level cache (STREAM), where everything streams.
+// The three sums are accumulated lazily and reduced once per thread.
+__device__ __forceinline__ v2u64 ld2(const uint64_t* p) { return *reinterpret_cast<const v2u64*>(p); }
+__device__ __forceinline__ v2u64 ld2_nt(const uint64_t* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const v2u64*>(p));
+}
+template <bool STREAM> __device__ __forceinline__ void st2(uint64_t* p, uint64_t x, uint64_t y) {
+    v2u64 v;
+    v.x = x;
+    v.y = y;
+    if (STREAM)
+        __builtin_nontemporal_store(v, reinterpret_cast<v2u64*>(p));
+    else
+        *reinterpret_cast<v2u64*>(p) = v;
+}
+__device__ __forceinline__ uint64_t fold1(uint64_t lo, uint64_t hi, uint64_t r) {
+    return gl::add(lo, gl::mul(r, gl::sub(hi, lo)));
+}
+__device__ __forceinline__ void pair_eval_lazy(gl::Acc& s0, gl::Acc& s1, gl::Acc& s2, uint64_t a0, uint64_t a1,
+                                               uint64_t b0, uint64_t b1) {
+    gl::acc_mac(s0, a0, b0);
+    gl::acc_mac(s1, a1, b1);
+    gl::acc_mac(s2, gl::sub(gl::add(a1, a1), a0), gl::sub(gl::add(b1, b1), b0));
+}
+
+template <bool FOLD, bool STREAM>
+__global__ __launch_bounds__(kBlock) void round_wide_kernel(uint64_t* __restrict__ a, uint64_t* __restrict__ b,
+                                                            uint64_t L, uint64_t r,
+                                                            uint64_t* __restrict__ out /*[gridDim.x][3]*/) {
+    __shared__ uint64_t lds[kWaves];
+    const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+    const uint64_t h = L >> 1, q = L >> 2;
+    const uint64_t pairs = (FOLD ? q : h) >> 1;  // the item count is even here
+    gl::Acc s0, s1, s2;
+    gl::acc_clear(s0);
+    gl::acc_clear(s1);
+    gl::acc_clear(s2);
+    for (uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x; t < pairs; t += stride) {
+        const uint64_t i = 2 * t;
+        if (FOLD) {
+            v2u64 x0 = STREAM ? ld2_nt(a + i) : ld2(a + i), x1 = STREAM ? ld2_nt(a + i + q) : ld2(a + i + q);
+            v2u64 y0 = STREAM ? ld2_nt(b + i) : ld2(b + i), y1 = STREAM ? ld2_nt(b + i + q) : ld2(b + i + q);
+            v2u64 x2 = ld2_nt(a + i + h), x3 = ld2_nt(a + i + h + q);
+            v2u64 y2 = ld2_nt(b + i + h), y3 = ld2_nt(b + i + h + q);
+            __builtin_amdgcn_sched_barrier(0);
+            uint64_t a0x = fold1(x0.x, x2.x, r), a0y = fold1(x0.y, x2.y, r);
+            uint64_t a1x = fold1(x1.x, x3.x, r), a1y = fold1(x1.y, x3.y, r);
+            uint64_t b0x = fold1(y0.x, y2.x, r), b0y = fold1(y0.y, y2.y, r);
+            uint64_t b1x = fold1(y1.x, y3.x, r), b1y = fold1(y1.y, y3.y, r);
+            st2<STREAM>(a + i, a0x, a0y);
+            st2<STREAM>(a + i + q, a1x, a1y);
+            st2<STREAM>(b + i, b0x, b0y);
+            st2<STREAM>(b + i + q, b1x, b1y);
+            pair_eval_lazy(s0, s1, s2, a0x, a1x, b0x, b1x);
+            pair_eval_lazy(s0, s1, s2, a0y, a1y, b0y, b1y);
+        } else {
+            v2u64 x0 = STREAM ? ld2_nt(a + i) : ld2(a + i), x1 = STREAM ? ld2_nt(a + i + h) : ld2(a + i + h);
+            v2u64 y0 = STREAM ? ld2_nt(b + i) : ld2(b + i), y1 = STREAM ? ld2_nt(b + i + h) : ld2(b + i + h);
+            __builtin_amdgcn_sched_barrier(0);
+            pair_eval_lazy(s0, s1, s2, x0.x, x1.x, y0.x, y1.x);
+            pair_eval_lazy(s0, s1, s2, x0.y, x1.y, y0.y, y1.y);
+        }
+    }
+    uint64_t g0 = block_sum(gl::acc_reduce(s0), lds);
+    uint64_t g1 = block_sum(gl::acc_reduce(s1), lds);
+    uint64_t g2 = block_sum(gl::acc_reduce(s2), lds);
+    if (threadIdx.x == 0) {
+        out[3 * blockIdx.x + 0] = g0;
+        out[3 * blockIdx.x + 1] = g1;
+        out[3 * blockIdx.x + 2] = g2;
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void round_finish_kernel(const uint64_t* __restrict__ part, uint32_t nblk,
                                                               uint64_t* __restrict__ out3) {
     __shared__ uint64_t lds[kWaves];
@@ -620,11 +697,17 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(uint64_t* 
     }
 }
 
-constexpr uint32_t kMaxRoundBlocks = 2048;
+#ifndef IMM_MAX_ROUND_BLOCKS
+#define IMM_MAX_ROUND_BLOCKS 512  // two blocks per CU: mixed read/write streams run best with few, long-lived blocks
+#endif
+constexpr uint32_t kMaxRoundBlocks = IMM_MAX_ROUND_BLOCKS;
+constexpr uint64_t kRoundStreamMinL = 1ull << 24;  // two tables of 128 MiB each: beyond the 256 MB cache
+constexpr uint64_t kRoundWideMin = 1ull << 14;  // items from which the two-items-per-thread kernel is used
 
 uint32_t round_blocks(uint64_t items) {
     if (items <= 8192) return 1;  // small tables: one block writes the result itself, no second launch
-    uint64_t nb = (items + kBlock - 1) / kBlock;
+    const uint64_t threads = items >= kRoundWideMin ? items / 2 : items;
+    uint64_t nb = (threads + kBlock - 1) / kBlock;
     if (nb < 1) nb = 1;
     if (nb > kMaxRoundBlocks) nb = kMaxRoundBlocks;
     return (uint32_t)nb;
@@ -713,7 +796,7 @@ hipError_t dot(hipStream_t stream, const uint64_t* x, const uint64_t* y, uint64_
     return hipGetLastError();
 }
 
-uint64_t round_scratch_words(uint64_t L) { return 3ull * round_blocks(L / 2); }
+uint64_t round_scratch_words(uint64_t) { return 3ull * kMaxRoundBlocks; }
 
 hipError_t round(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, bool fold, uint64_t r, uint64_t* out3,
                  uint64_t* scratch) {
@@ -724,7 +807,18 @@ hipError_t round(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, bool 
     const uint64_t items = fold ? L / 4 : L / 2;
     const uint32_t nb = round_blocks(items);
     uint64_t* dst = nb == 1 ? out3 : scratch;
-    if (fold)
+    const bool wide = items >= kRoundWideMin && reinterpret_cast<uintptr_t>(a) % 16 == 0 &&
+                      reinterpret_cast<uintptr_t>(b) % 16 == 0;
+    const bool streaming = L >= kRoundStreamMinL;
+    if (wide && fold && streaming)
+        hipLaunchKernelGGL((round_wide_kernel<true, true>), dim3(nb), dim3(kBlock), 0, stream, a, b, L, r, dst);
+    else if (wide && fold)
+        hipLaunchKernelGGL((round_wide_kernel<true, false>), dim3(nb), dim3(kBlock), 0, stream, a, b, L, r, dst);
+    else if (wide && streaming)
+        hipLaunchKernelGGL((round_wide_kernel<false, true>), dim3(nb), dim3(kBlock), 0, stream, a, b, L, r, dst);
+    else if (wide)
+        hipLaunchKernelGGL((round_wide_kernel<false, false>), dim3(nb), dim3(kBlock), 0, stream, a, b, L, r, dst);
+    else if (fold)
         hipLaunchKernelGGL((round_kernel<true>), dim3(nb), dim3(kBlock), 0, stream, a, b, L, r, dst);
     else
         hipLaunchKernelGGL((round_kernel<false>), dim3(nb), dim3(kBlock), 0, stream, a, b, L, r, dst);

@@ -130,7 +130,7 @@ def test_mle_eval_boolean_point_and_leading_dimension(torch, ctx, oracle_fast):
 
 
 # ------------------------------------------------------------------ K4 round kernel on caller tables
-@pytest.mark.parametrize("logL", [1, 2, 3, 8, 12, 14, 20])
+@pytest.mark.parametrize("logL", [1, 2, 3, 8, 12, 14, 15, 16, 17, 20, 22])
 def test_round_fold_eval_matches_oracle(torch, ctx, oracle_fast, logL):
     L = 1 << logL
     rng = np.random.default_rng(logL)
@@ -279,9 +279,9 @@ def test_config4_moe_expert_batch(torch, ctx, oracle_fast):
 @pytest.mark.timeout(1200)
 def test_config5_dense_layers_chained(torch, ctx, oracle_fast):
     """Chained transcript over the 7 statements of each decoder layer.  IMM_TEST_LAYERS picks how many
-    of the 32 layers run (default 2); the chain is proven layer by layer, resuming from the stored
+    of the 32 layers run (default: all 32, 224 proofs); the chain is proven layer by layer, resuming from the stored
     state, which is also the checkpoint/resume property of the transcript."""
-    layers = int(os.environ.get("IMM_TEST_LAYERS", "2"))
+    layers = int(os.environ.get("IMM_TEST_LAYERS", "32"))
     s_gpu = s_cpu = ref.FS_INIT
     total = 0
     for layer in range(layers):
