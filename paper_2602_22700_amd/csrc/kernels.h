@@ -28,7 +28,7 @@ struct Split {
     uint64_t per_split;   // rows (or columns) covered by one partial vector
 };
 Split plan_over_rows(uint64_t rows, uint64_t cols);
-Split plan_over_cols(uint64_t rows, uint64_t cols);
+Split plan_over_cols(uint64_t rows, uint64_t cols, int dtype);
 
 // partial[s][j] = sum over the rows i of split s of eq[i] * T[i][j]   (j < cols)
 hipError_t reduce_over_rows(hipStream_t stream, const void* T, int dtype, uint64_t rows, uint64_t cols, uint64_t ld,

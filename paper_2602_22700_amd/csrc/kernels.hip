@@ -245,6 +245,120 @@ hipError_t launch_over_cols(hipStream_t stream, const void* T, uint64_t rows, ui
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ row-wise reduction of an int8 table
+// Reads the weights as they are stored (1 byte per entry instead of 8).  With x' = x + 128 in
+// [0, 255] (a sign-bit flip of the byte) the sum over a row is
+//     sum_y eq[y] x[y] = sum_y eq[y] x'[y]  -  128 * sum_y eq[y],
+// and every product eq_limb * x' is below 2^40, so a lane adds thousands of them into a plain
+// 64-bit register: two v_mad_u64_u32 per entry, no carries, one modular reduction per row per
+// block.  A lane owns 16 adjacent columns (one 16-byte load per row) and keeps their 32 eq limbs
+// in registers while it walks the R rows of the block, so the eq vector costs 128/(16 R) bytes of
+// L2 traffic per byte of table.  The correction term is accumulated from the same registers.
+#ifndef IMM_I8_ROWS
+#define IMM_I8_ROWS 8
+#endif
+#ifndef IMM_I8_MIN_BLOCKS
+#define IMM_I8_MIN_BLOCKS 512
+#endif
+constexpr int kI8Rows = IMM_I8_ROWS;              // rows per block
+constexpr uint64_t kI8ColsPerPass = 16 * kBlock;  // columns one block pass covers
+constexpr uint64_t kI8MaxSplit = 1ull << 20;      // columns per split: keeps the 64-bit sums below 2^61
+
+typedef unsigned int v4u32 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint64_t wave_sum_plain(uint64_t v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;
+}
+
+// value = lo + hi * 2^32 with lo, hi < 2^62, as a canonical residue
+__device__ __forceinline__ uint64_t combine_limb_sums(uint64_t lo, uint64_t hi) {
+    uint64_t low = lo + (hi << 32);
+    uint64_t high = (hi >> 32) + (low < lo ? 1 : 0);
+    return gl::reduce128(low, high);
+}
+
+__global__ __launch_bounds__(kBlock) void reduce_over_cols_i8_kernel(const int8_t* __restrict__ T, uint64_t ld,
+                                                                     uint64_t rows, uint64_t cols,
+                                                                     const uint64_t* __restrict__ eq,
+                                                                     uint64_t* __restrict__ partial,
+                                                                     uint64_t cols_per_split) {
+    constexpr int R = kI8Rows;
+    __shared__ uint64_t lds[kWaves][2 * R + 2];
+    const uint64_t row0 = (uint64_t)blockIdx.x * R;
+    const uint64_t c_begin = (uint64_t)blockIdx.y * cols_per_split;
+    uint64_t c_end = c_begin + cols_per_split;
+    if (c_end > cols) c_end = cols;
+
+    uint64_t lo[R], hi[R], ks_lo = 0, ks_hi = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) lo[r] = hi[r] = 0;
+    // rows past the end of the table are read from the last valid row and dropped at the end
+    const int8_t* rowp[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) rowp[r] = T + (row0 + r < rows ? row0 + r : rows - 1) * ld;
+
+    for (uint64_t c = c_begin + 16 * (uint64_t)threadIdx.x; c < c_end; c += kI8ColsPerPass) {
+        v4u32 x[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) x[r] = __builtin_nontemporal_load(reinterpret_cast<const v4u32*>(rowp[r] + c));
+        uint32_t e0[16], e1[16];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            v2u64 e = *reinterpret_cast<const v2u64*>(eq + c + 2 * j);
+            e0[2 * j] = (uint32_t)e.x; e1[2 * j] = (uint32_t)(e.x >> 32);
+            e0[2 * j + 1] = (uint32_t)e.y; e1[2 * j + 1] = (uint32_t)(e.y >> 32);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            ks_lo += e0[j];
+            ks_hi += e1[j];
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t w = x[r][q] ^ 0x80808080u;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t byte = (w >> (8 * k)) & 0xFFu;
+                    lo[r] += (uint64_t)e0[4 * q + k] * byte;
+                    hi[r] += (uint64_t)e1[4 * q + k] * byte;
+                }
+            }
+        }
+    }
+    // block sums of the raw 64-bit accumulators (no wrap: see kI8MaxSplit), then one reduction
+    const uint32_t lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        uint64_t a = wave_sum_plain(lo[r]), b = wave_sum_plain(hi[r]);
+        if (lane == 0) { lds[w][2 * r] = a; lds[w][2 * r + 1] = b; }
+    }
+    {
+        uint64_t a = wave_sum_plain(ks_lo), b = wave_sum_plain(ks_hi);
+        if (lane == 0) { lds[w][2 * R] = a; lds[w][2 * R + 1] = b; }
+    }
+    __syncthreads();
+    if (threadIdx.x < R && row0 + threadIdx.x < rows) {
+        const int r = threadIdx.x;
+        uint64_t a = 0, b = 0, ka = 0, kb = 0;
+#pragma unroll
+        for (int k = 0; k < kWaves; ++k) {
+            a += lds[k][2 * r]; b += lds[k][2 * r + 1];
+            ka += lds[k][2 * R]; kb += lds[k][2 * R + 1];
+        }
+        const uint64_t sum = combine_limb_sums(a, b);
+        const uint64_t corr = gl::mul(128, combine_limb_sums(ka, kb));
+        partial[(uint64_t)blockIdx.y * rows + row0 + r] = gl::sub(sum, corr);
+    }
+}
+
+// The fast int8 kernel needs 16-byte rows and whole 16-column groups.
+bool i8_fast_shape(uint64_t cols) { return cols % 16 == 0; }
+
 // ------------------------------------------------------------------ reduction over the rows (column-wise)
 // A lane owns two adjacent columns; a block walks the rows of its split, kRowsUnroll rows
 // per trip with all loads issued first.  The eq weight of a row is the same for every lane
@@ -747,7 +861,19 @@ Split plan_over_rows(uint64_t rows, uint64_t cols) {
     return sp;
 }
 
-Split plan_over_cols(uint64_t rows, uint64_t cols) {
+Split plan_over_cols(uint64_t rows, uint64_t cols, int dtype) {
+    Split sp;
+    if (dtype == IMM_I8 && i8_fast_shape(cols)) {
+        // blocks of kI8Rows rows; split the columns (whole block passes) until there are >= 1024 blocks
+        const uint64_t row_blocks = (rows + kI8Rows - 1) / kI8Rows;
+        uint64_t want = (IMM_I8_MIN_BLOCKS + row_blocks - 1) / row_blocks;
+        uint64_t per = (cols + want - 1) / want;
+        per = (per + kI8ColsPerPass - 1) / kI8ColsPerPass * kI8ColsPerPass;
+        if (per > kI8MaxSplit) per = kI8MaxSplit;
+        sp.per_split = per;
+        sp.nsplit = (uint32_t)((cols + per - 1) / per);
+        return sp;
+    }
     // a block covers kRowsPerBlock rows; split the columns until there are >= 2048 blocks,
     // but keep at least 2048 columns (4 pairs per lane) per split
     const uint64_t row_blocks = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
@@ -756,7 +882,6 @@ Split plan_over_cols(uint64_t rows, uint64_t cols) {
     if (per < 2048) per = 2048;
     per = (per + 511) / 512 * 512;  // whole block passes, and even
     if (per >= cols) per = (cols + 1) / 2 * 2;
-    Split sp;
     sp.per_split = per;
     sp.nsplit = (uint32_t)((cols + per - 1) / per);
     return sp;
@@ -776,7 +901,15 @@ hipError_t reduce_over_rows(hipStream_t stream, const void* T, int dtype, uint64
 hipError_t reduce_over_cols(hipStream_t stream, const void* T, int dtype, uint64_t rows, uint64_t cols, uint64_t ld,
                             const uint64_t* eq_cols, uint64_t* partial, Split sp) {
     switch (dtype) {
-    case IMM_I8: return launch_over_cols<int8_t>(stream, T, rows, cols, ld, eq_cols, partial, sp);
+    case IMM_I8:
+        if (i8_fast_shape(cols) && sp.per_split % kI8ColsPerPass == 0 && sp.per_split <= kI8MaxSplit &&
+            reinterpret_cast<uintptr_t>(T) % 16 == 0 && ld % 16 == 0 && reinterpret_cast<uintptr_t>(eq_cols) % 16 == 0) {
+            dim3 grid((unsigned)((rows + kI8Rows - 1) / kI8Rows), sp.nsplit);
+            hipLaunchKernelGGL(reduce_over_cols_i8_kernel, grid, dim3(kBlock), 0, stream,
+                               static_cast<const int8_t*>(T), ld, rows, cols, eq_cols, partial, sp.per_split);
+            return hipGetLastError();
+        }
+        return launch_over_cols<int8_t>(stream, T, rows, cols, ld, eq_cols, partial, sp);
     case IMM_I16: return launch_over_cols<int16_t>(stream, T, rows, cols, ld, eq_cols, partial, sp);
     case IMM_I64: return launch_over_cols<int64_t>(stream, T, rows, cols, ld, eq_cols, partial, sp);
     case IMM_F64P: return launch_over_cols<uint64_t>(stream, T, rows, cols, ld, eq_cols, partial, sp);

@@ -187,7 +187,7 @@ static int partial_over_rows(imm_ctx* ctx, hipStream_t s, int kid, const void* T
 static int partial_over_cols(imm_ctx* ctx, hipStream_t s, int kid, const void* T, int dt, uint64_t rows, uint64_t cols,
                              uint64_t ld, const uint64_t* eq, uint64_t padded, DevBuf& part, uint64_t* out) {
     int rc;
-    k::Split sp = k::plan_over_cols(rows, cols);
+    k::Split sp = k::plan_over_cols(rows, cols, dt);
     const bool direct = sp.nsplit == 1;
     if (!direct && (rc = part.ensure(sizeof(uint64_t) * sp.nsplit * rows))) return rc;
     if ((rc = ctx->prof.begin(kid, s))) return rc;

@@ -90,7 +90,7 @@ def test_encode_ragged_counts_and_misaligned_views(torch, ctx, oracle_fast, coun
 
 # ------------------------------------------------------------------ MLE evaluation (K2 + K3 + dot)
 @pytest.mark.parametrize("shape", [(1, 1), (1, 7), (9, 1), (5, 6), (64, 64), (3, 1025), (130, 517), (257, 300),
-                                   (1000, 4096), (37, 14336)])
+                                   (1000, 4096), (37, 14336), (9, 8208), (3, 16)])
 @pytest.mark.parametrize("dt", [np.int8, np.int16, np.int64, np.uint64])
 def test_mle_eval_matches_oracle(torch, ctx, oracle_fast, shape, dt):
     rows, cols = shape
@@ -202,7 +202,7 @@ def check_proof(torch, ctx, oracle_fast, A, B, C=None, state=ref.FS_INIT, interm
 
 @pytest.mark.parametrize("shape", [(1, 1, 1), (1, 5, 3), (3, 1, 2), (2, 2, 2), (4, 4, 4), (5, 6, 7), (2, 9, 1),
                                    (33, 70, 129), (17, 300, 1030), (129, 1025, 515), (7, 2048, 2049),
-                                   (2, 32768, 5), (2, 65539, 3), (1, 131072, 2)])
+                                   (2, 32768, 5), (2, 65539, 3), (1, 131072, 2), (5, 67, 8208), (19, 40, 4096), (8, 8, 16)])
 def test_prove_small_and_ragged_shapes(torch, ctx, oracle_fast, shape):
     m, d, n = shape
     rng = np.random.default_rng(m * 10007 + d * 101 + n)
