@@ -747,28 +747,107 @@ __device__ __forceinline__ uint64_t mail_peek(const uint64_t* slot) {
     return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
+// While the host hashes g_k, the device already prepares round k+1: after the fold with r_k the
+// entries are x + r_k dx, so each value g_{k+1}(t) is a quadratic c0 + c1 r_k + c2 r_k^2 whose
+// coefficients depend only on the tables as they are now.  The block computes the nine
+// coefficients before r_k arrives; when it does, lane 0 evaluates the three quadratics and posts
+// g_{k+1} at once, and the in-place fold runs while the host is busy with g_{k+1}.  The critical
+// path of a round is then one host hash and one PCIe round trip.
+struct Quad3 {
+    uint64_t c[3][3];  // c[t][e]: coefficient of r^e in g(t)
+};
+
+__device__ __forceinline__ void quad_accumulate(uint64_t (&c)[3], uint64_t A, uint64_t dA, uint64_t B, uint64_t dB) {
+    const uint64_t p0 = gl::mul(A, B), p2 = gl::mul(dA, dB);
+    const uint64_t pm = gl::mul(gl::add(A, dA), gl::add(B, dB));  // = p0 + (A dB + dA B) + p2
+    c[0] = gl::add(c[0], p0);
+    c[1] = gl::add(c[1], gl::sub(gl::sub(pm, p0), p2));
+    c[2] = gl::add(c[2], p2);
+}
+
+// Sum the nine coefficients over the block; the result is valid in thread 0.  A single wave
+// issues an instruction every few nanoseconds, so the reduction is spread out: every thread of
+// an active wave drops its nine values into LDS, then wave v adds up column v (one value per
+// lane and active wave, then a wave64 shuffle tree), so the nine sums proceed side by side.
+__device__ __forceinline__ void quad_block_sum(Quad3& qd, uint32_t active_waves, uint64_t (*red)[kRoundsBlock],
+                                               uint64_t* fin9) {
+    const uint32_t tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    if (w < active_waves) {
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+            for (int e = 0; e < 3; ++e) red[3 * t + e][tid] = qd.c[t][e];
+    }
+    __syncthreads();
+    if (w < 9) {
+        uint64_t v = red[w][lane];
+        for (uint32_t j = 1; j < active_waves; ++j) v = gl::add(v, red[w][lane + 64 * j]);
+        v = wave_sum(v);
+        if (lane == 0) fin9[w] = v;
+    }
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+            for (int e = 0; e < 3; ++e) qd.c[t][e] = fin9[3 * t + e];
+    }
+}
+
 __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(uint64_t* __restrict__ a,
                                                                      uint64_t* __restrict__ b, uint64_t L,
                                                                      int rounds, Mailbox* mb, uint64_t spin_limit,
                                                                      uint64_t* __restrict__ status) {
-    __shared__ uint64_t lds[kRoundsWaves][3];
+    __shared__ uint64_t lds3[kRoundsWaves][3];
+    __shared__ uint64_t red[9][kRoundsBlock];  // 72 KiB of the CU's 160 KiB
+    __shared__ uint64_t fin9[9];
     __shared__ uint64_t r_shared;
     const uint32_t tid = threadIdx.x;
+
+    // round 1: plain evaluation of the tables as they are
     Triple g = {0, 0, 0};
     {
         const uint64_t h = L >> 1;
         for (uint64_t i = tid; i < h; i += kRoundsBlock) pair_eval(g, a[i], a[i + h], b[i], b[i + h]);
     }
-    g = rounds_block_sum(g, lds);
+    g = rounds_block_sum(g, lds3);
+    if (tid == 0) {
+        mail_post(&mb->g[0][0], g.g0);
+        mail_post(&mb->g[0][1], g.g1);
+        mail_post(&mb->g[0][2], g.g2);
+    }
+
     for (int kk = 0; kk < rounds; ++kk) {
+        const uint64_t h = L >> 1, q = L >> 2;
+        // coefficients of g_{kk+2}(t) as polynomials in the challenge that is still on its way
+        Quad3 qd;
+#pragma unroll
+        for (int t = 0; t < 3; ++t) qd.c[t][0] = qd.c[t][1] = qd.c[t][2] = 0;
+        if (L >= 4) {
+            for (uint64_t i = tid; i < q; i += kRoundsBlock) {
+                const uint64_t x0 = a[i], x1 = a[i + q], y0 = b[i], y1 = b[i + q];
+                const uint64_t dx0 = gl::sub(a[i + h], x0), dx1 = gl::sub(a[i + h + q], x1);
+                const uint64_t dy0 = gl::sub(b[i + h], y0), dy1 = gl::sub(b[i + h + q], y1);
+                quad_accumulate(qd.c[0], x0, dx0, y0, dy0);
+                quad_accumulate(qd.c[1], x1, dx1, y1, dy1);
+                quad_accumulate(qd.c[2], gl::sub(gl::add(x1, x1), x0), gl::sub(gl::add(dx1, dx1), dx0),
+                                gl::sub(gl::add(y1, y1), y0), gl::sub(gl::add(dy1, dy1), dy0));
+            }
+            const uint32_t active = (uint32_t)((q + 63) / 64 < kRoundsWaves ? (q + 63) / 64 : kRoundsWaves);
+            quad_block_sum(qd, active, red, fin9);
+        }
         if (tid == 0) {
-            mail_post(&mb->g[kk][0], g.g0);
-            mail_post(&mb->g[kk][1], g.g1);
-            mail_post(&mb->g[kk][2], g.g2);
             uint64_t r = kMailEmpty;
             for (uint64_t spin = 0; spin < spin_limit; ++spin) {
                 r = mail_peek(&mb->r[kk]);
                 if (r != kMailEmpty) break;
+            }
+            if (r < gl::P && L >= 4) {
+                // g_{kk+2}(t) = c0 + r (c1 + r c2): out to the host before the tables are touched
+#pragma unroll
+                for (int t = 0; t < 3; ++t)
+                    mail_post(&mb->g[kk + 1][t],
+                              gl::add(qd.c[t][0], gl::mul(r, gl::add(qd.c[t][1], gl::mul(r, qd.c[t][2])))));
             }
             r_shared = r;
         }
@@ -778,35 +857,18 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(uint64_t* 
             if (tid == 0) status[0] = 1;
             return;
         }
-        g = {0, 0, 0};
-        const uint64_t h = L >> 1, q = L >> 2;
-        if (L == 2) {
-            if (tid == 0) {
-                g.g0 = gl::add(a[0], gl::mul(r, gl::sub(a[1], a[0])));
-                g.g1 = gl::add(b[0], gl::mul(r, gl::sub(b[1], b[0])));
-                a[0] = g.g0;
-                b[0] = g.g1;
-            }
-        } else {
-            for (uint64_t i = tid; i < q; i += kRoundsBlock) {
-                uint64_t x0 = a[i], x1 = a[i + q], x2 = a[i + h], x3 = a[i + h + q];
-                uint64_t y0 = b[i], y1 = b[i + q], y2 = b[i + h], y3 = b[i + h + q];
-                uint64_t a0 = gl::add(x0, gl::mul(r, gl::sub(x2, x0)));
-                uint64_t a1 = gl::add(x1, gl::mul(r, gl::sub(x3, x1)));
-                uint64_t b0 = gl::add(y0, gl::mul(r, gl::sub(y2, y0)));
-                uint64_t b1 = gl::add(y1, gl::mul(r, gl::sub(y3, y1)));
-                a[i] = a0; a[i + q] = a1;
-                b[i] = b0; b[i + q] = b1;
-                pair_eval(g, a0, a1, b0, b1);
-            }
-            g = rounds_block_sum(g, lds);
+        // bind the leading variable: x[i] <- x[i] + r (x[i + h] - x[i]), in place
+        for (uint64_t i = tid; i < h; i += kRoundsBlock) {
+            const uint64_t x = a[i], y = b[i];
+            a[i] = gl::add(x, gl::mul(r, gl::sub(a[i + h], x)));
+            b[i] = gl::add(y, gl::mul(r, gl::sub(b[i + h], y)));
         }
         L = h;
         __syncthreads();
     }
     if (tid == 0) {
-        mail_post(&mb->fin[0], g.g0);
-        mail_post(&mb->fin[1], g.g1);
+        mail_post(&mb->fin[0], a[0]);
+        mail_post(&mb->fin[1], b[0]);
         status[0] = 0;
     }
 }
