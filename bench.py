@@ -46,6 +46,9 @@ def make_workload(name, torch, imm, workloads):
         pairs = [workloads.tiny()]
     elif name == "dense_layer":
         pairs = [(A, B) for (_, A, B) in workloads.dense_layer(0)]
+    elif name == "moe":
+        X, routes = workloads.moe_activations()
+        pairs = [(np.ascontiguousarray(X[routes[e]]), workloads.moe_expert_weight(e)) for e in range(8)]
     else:
         raise SystemExit("unknown workload %r" % name)
     out = []
@@ -62,7 +65,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="ffn_up", choices=["ffn_up", "attn", "tiny", "dense_layer"])
+    ap.add_argument("--workload", default="ffn_up", choices=["ffn_up", "attn", "tiny", "dense_layer", "moe"])
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="time budget of the CPU-oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fold-log2", type=int, default=26,
@@ -95,7 +98,7 @@ def main():
     if args.narrow:
         ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 0)
     items = [(Ad, Bd, com) for (_, _, Ad, Bd, com) in stmts]
-    chained = len(items) > 1
+    chained = len(items) > 1 and args.workload != "moe"   # experts are independent statements
     s0 = imm.imm_fs_init()
 
     batch = ctx.prepare_batch(items, chained, s0)   # arguments marshalled once; a step is one C call

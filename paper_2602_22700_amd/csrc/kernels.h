@@ -80,11 +80,24 @@ struct Mailbox {
     uint64_t fin[4];                // device -> host: a[0], b[0] after the last fold
 };
 
-// The same `nrounds` rounds as rounds(), with the host supplying the challenges through
-// `mailbox` (a device-visible pointer to pinned host memory, slots preset to kMailEmpty).
-// Lane 0 waits at most `spin_limit` polls per round; status[0] (device memory) becomes 0 on
-// completion and 1 if a wait ran out or the host posted kMailAbort.
-hipError_t rounds_mailbox(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, int nrounds, Mailbox* mailbox,
+// The same rounds as rounds(), for up to kRoundsMaxJobs independent proofs in one launch (one
+// workgroup each), with the host supplying the challenges: job p talks through mailboxes[p] (a
+// device-visible pointer to pinned host memory, slots preset to kMailEmpty).  tables of job p:
+// L = 2^rounds <= kRoundsMaxL entries each, folded in place.  Lane 0 of a workgroup waits at most
+// `spin_limit` polls per round; status[p] (device memory) becomes 0 on completion and 1 if a wait
+// ran out or the host posted kMailAbort.
+constexpr int kRoundsMaxJobs = 16;
+struct RoundsJob {
+    uint64_t* a;
+    uint64_t* b;
+    uint64_t L;
+    int rounds;
+    int _pad;
+};
+struct RoundsJobs {
+    RoundsJob job[kRoundsMaxJobs];
+};
+hipError_t rounds_mailbox(hipStream_t stream, const RoundsJobs& jobs, int count, Mailbox* mailboxes,
                           uint64_t spin_limit, uint64_t* status);
 
 }  // namespace k

@@ -794,10 +794,17 @@ __device__ __forceinline__ void quad_block_sum(Quad3& qd, uint32_t active_waves,
     }
 }
 
-__global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(uint64_t* __restrict__ a,
-                                                                     uint64_t* __restrict__ b, uint64_t L,
-                                                                     int rounds, Mailbox* mb, uint64_t spin_limit,
-                                                                     uint64_t* __restrict__ status) {
+// One workgroup per proof: independent proofs run their round loops side by side, each with its
+// own tables and mailbox, while one host thread serves all mailboxes in turn.
+__global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs jobs, Mailbox* mailboxes,
+                                                                     uint64_t spin_limit,
+                                                                     uint64_t* __restrict__ status_all) {
+    uint64_t* __restrict__ a = jobs.job[blockIdx.x].a;
+    uint64_t* __restrict__ b = jobs.job[blockIdx.x].b;
+    uint64_t L = jobs.job[blockIdx.x].L;
+    const int rounds = jobs.job[blockIdx.x].rounds;
+    Mailbox* mb = mailboxes + blockIdx.x;
+    uint64_t* status = status_all + blockIdx.x;
     __shared__ uint64_t lds3[kRoundsWaves][3];
     __shared__ uint64_t red[9][kRoundsBlock];  // 72 KiB of the CU's 160 KiB
     __shared__ uint64_t fin9[9];
@@ -1032,9 +1039,9 @@ hipError_t rounds(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, int 
     return hipGetLastError();
 }
 
-hipError_t rounds_mailbox(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, int nrounds, Mailbox* mailbox,
+hipError_t rounds_mailbox(hipStream_t stream, const RoundsJobs& jobs, int count, Mailbox* mailboxes,
                           uint64_t spin_limit, uint64_t* status) {
-    hipLaunchKernelGGL(rounds_mailbox_kernel, dim3(1), dim3(kRoundsBlock), 0, stream, a, b, L, nrounds, mailbox,
+    hipLaunchKernelGGL(rounds_mailbox_kernel, dim3((unsigned)count), dim3(kRoundsBlock), 0, stream, jobs, mailboxes,
                        spin_limit, status);
     return hipGetLastError();
 }

@@ -116,9 +116,9 @@ struct Profiler {
 
 struct imm_ctx {
     int device = 0;
-    imm::DevBuf encA, encB, eqx, eqy, a, b, partA, partB, round_scratch, words, snapA, snapB;
+    imm::DevBuf encA, encB, eqx, eqy, a, b, partA, partB, round_scratch, words, snapA, snapB, group_tables;
     uint64_t* pinned = nullptr;  // host staging, 4 KiB
-    imm::k::Mailbox* mailbox = nullptr;  // pinned + coherent: g_k out, r_k in (host-transcript mode)
+    imm::k::Mailbox* mailbox = nullptr;  // pinned + coherent, kRoundsMaxJobs of them: g_k out, r_k in
     int transcript_mode = IMM_TRANSCRIPT_HOST;
     uint64_t spin_limit = 1ull << 21;    // device polls per round before giving up (about 2 us each)
     int64_t host_wait_ms = 30000;        // host patience per mailbox slot
@@ -132,7 +132,8 @@ struct imm_ctx {
 
 namespace imm {
 
-constexpr size_t kWordsDev = k::kWordCount + 5;  // proof words and challenges, the 32-byte state, one status word
+// proof words and challenges, the 32-byte state, one status word per concurrent round loop
+constexpr size_t kWordsDev = k::kWordCount + 4 + k::kRoundsMaxJobs;
 
 static bool dim_ok(uint64_t v) { return v >= 1 && v <= (1ull << IMM_MAX_ROUNDS); }
 
@@ -225,111 +226,46 @@ static bool mail_wait(const uint64_t* slot, int64_t patience_ms, uint64_t* value
     }
 }
 
-// Rounds kk0 .. delta-1 with the round kernel running on the device and this thread hashing:
-// the kernel posts g_k, the host absorbs it, squeezes r_k and posts it back.
-static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, uint64_t* a, uint64_t* b, uint64_t L, int delta,
-                                       int kk0, bool claim_absorbed, Transcript& tr, imm_proof* out, uint64_t* rr,
-                                       uint64_t* status_dev) {
-    k::Mailbox* mb = ctx->mailbox;
-    std::memset(mb, 0xFF, sizeof(*mb));
-    std::atomic_thread_fence(std::memory_order_seq_cst);
-    int rc;
-    if ((rc = ctx->prof.begin(IMM_K_ROUND, s))) return rc;
-    IMM_HIP(k::rounds_mailbox(s, a, b, L, delta - kk0, mb, ctx->spin_limit, status_dev));
-    if ((rc = ctx->prof.end(IMM_K_ROUND, s))) return rc;
-    bool ok = true;
-    int slot = 0;
-    for (int kk = kk0; kk < delta && ok; ++kk, ++slot) {
-        uint64_t g[3];
-        for (int t = 0; t < 3 && ok; ++t) ok = mail_wait(&mb->g[slot][t], ctx->host_wait_ms, &g[t]);
-        if (!ok) break;
-        if (!claim_absorbed) {
-            out->c0 = hf::add(g[0], g[1]);
-            tr.absorb_words("clmC", &out->c0, 1);
-            claim_absorbed = true;
-        }
-        out->g[3 * kk] = g[0];
-        out->g[3 * kk + 1] = g[1];
-        out->g[3 * kk + 2] = g[2];
-        tr.absorb_words("rnd ", g, 3);
-        rr[kk] = tr.challenge();
-        __atomic_store_n(&mb->r[slot], rr[kk], __ATOMIC_RELEASE);
-    }
-    uint64_t fin[2] = {0, 0};
-    if (ok) ok = mail_wait(&mb->fin[0], ctx->host_wait_ms, &fin[0]) && mail_wait(&mb->fin[1], ctx->host_wait_ms, &fin[1]);
-    if (!ok) {
-        // release the kernel from whatever wait it is in, then let it drain
-        for (int t = 0; t < IMM_MAX_ROUNDS; ++t) __atomic_store_n(&mb->r[t], k::kMailAbort, __ATOMIC_RELEASE);
-        IMM_HIP(hipStreamSynchronize(s));
-        g_last_error = "round kernel and host transcript lost contact (mailbox wait ran out)";
-        return IMM_E_HIP;
-    }
-    out->vA = fin[0];
-    out->vB = fin[1];
-    tr.absorb_words("fin ", fin, 2);
-    // No stream synchronisation here: posting fin[] is the kernel's last access to the mailbox
-    // and to the tables, every result is already on the host, and whatever is launched next on
-    // this stream is ordered behind the kernel's last instructions anyway.
-    return IMM_OK;
-}
+// One statement on its way through the prover.
+struct Job {
+    const imm_matmul_desc* ds = nullptr;
+    imm_proof* out = nullptr;
+    int mu = 0, delta = 0, nu = 0;
+    uint64_t D = 1;
+    Transcript tr;
+    uint64_t rx[IMM_MAX_ROUNDS] = {}, ry[IMM_MAX_ROUNDS] = {}, rr[IMM_MAX_ROUNDS] = {};
+    uint64_t* a = nullptr;  // device tables of length D
+    uint64_t* b = nullptr;
+    uint64_t L = 1;         // current table length
+    int kk = 0;             // rounds already done
+    bool claim_absorbed = false;
+    explicit Job(const uint8_t state[32]) : tr(state) {}
+};
 
-// Rounds kk0 .. delta-1 in one launch that also hashes the transcript on the device; one copy
-// at the end brings back the proof words, the challenges and the new state.
-static int rounds_with_device_transcript(imm_ctx* ctx, hipStream_t s, uint64_t* a, uint64_t* b, uint64_t L, int delta,
-                                         int kk0, bool claim_absorbed, const Transcript& tr, imm_proof* out,
-                                         uint64_t* rr, uint64_t* words, uint8_t state[32]) {
-    int rc;
-    uint32_t st_in[8];
-    for (int i = 0; i < 8; ++i)
-        st_in[i] = (uint32_t)tr.s[4 * i] << 24 | (uint32_t)tr.s[4 * i + 1] << 16 | (uint32_t)tr.s[4 * i + 2] << 8 |
-                   (uint32_t)tr.s[4 * i + 3];
-    uint32_t* st_dev = reinterpret_cast<uint32_t*>(words + k::kWordCount);
-    if ((rc = ctx->prof.begin(IMM_K_ROUND, s))) return rc;
-    IMM_HIP(k::rounds(s, a, b, L, delta - kk0, kk0, !claim_absorbed, st_in, words, st_dev));
-    if ((rc = ctx->prof.end(IMM_K_ROUND, s))) return rc;
-    uint64_t hw[kWordsDev];
-    if ((rc = fetch_words(ctx, s, words, kWordsDev, hw))) return rc;
-    if (!claim_absorbed) out->c0 = hw[k::kWordC0];
-    for (int t = kk0; t < delta; ++t) {
-        out->g[3 * t] = hw[k::kWordG + 3 * t];
-        out->g[3 * t + 1] = hw[k::kWordG + 3 * t + 1];
-        out->g[3 * t + 2] = hw[k::kWordG + 3 * t + 2];
-        rr[t] = hw[k::kWordR + t];
-    }
-    out->vA = hw[k::kWordVA];
-    out->vB = hw[k::kWordVB];
-    const uint32_t* st_out = reinterpret_cast<const uint32_t*>(hw + k::kWordCount);
-    for (int i = 0; i < 8; ++i) {
-        state[4 * i] = (uint8_t)(st_out[i] >> 24);
-        state[4 * i + 1] = (uint8_t)(st_out[i] >> 16);
-        state[4 * i + 2] = (uint8_t)(st_out[i] >> 8);
-        state[4 * i + 3] = (uint8_t)st_out[i];
-    }
-    return IMM_OK;
-}
-
-static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uint8_t state[32], imm_proof* out) {
-    if (!ds.A_dev || !ds.B_dev || !ds.com || !state || !out) return IMM_E_NULL;
+static int check_desc(const imm_matmul_desc& ds) {
+    if (!ds.A_dev || !ds.B_dev || !ds.com) return IMM_E_NULL;
     if (!dim_ok(ds.m) || !dim_ok(ds.d) || !dim_ok(ds.n)) return IMM_E_SHAPE;
     if (ds.dtA != IMM_I16 && ds.dtA != IMM_F64P) return IMM_E_DTYPE;
     if (ds.dtB != IMM_I8 && ds.dtB != IMM_F64P) return IMM_E_DTYPE;
-    const uint64_t m = ds.m, d = ds.d, n = ds.n;
-    const int mu = hf::ceil_log2(m), delta = hf::ceil_log2(d), nu = hf::ceil_log2(n);
-    const uint64_t D = 1ull << delta;
-    int rc;
+    return IMM_OK;
+}
 
-    Transcript tr(state);
-    uint64_t rx[IMM_MAX_ROUNDS] = {}, ry[IMM_MAX_ROUNDS] = {}, rr[IMM_MAX_ROUNDS] = {};
-    tr.head(m, d, n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, mu, nu, rx, ry);
+// a0..a4: transcript head on the host, then eq vectors, encoding and the two streaming partial
+// evaluations on the stream; leaves a[], b[] (zero-padded to D) in job.a / job.b.
+static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job) {
+    const imm_matmul_desc& ds = *job.ds;
+    const uint64_t m = ds.m, d = ds.d, n = ds.n;
+    job.mu = hf::ceil_log2(m);
+    job.delta = hf::ceil_log2(d);
+    job.nu = hf::ceil_log2(n);
+    job.D = 1ull << job.delta;
+    job.L = job.D;
+    const uint64_t D = job.D;
+    int rc;
+    job.tr.head(m, d, n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, job.mu, job.nu, job.rx, job.ry);
 
     // a2: eq vectors for both points
-    if ((rc = build_eq(ctx, s, rx, mu, ry, nu))) return rc;
-    if ((rc = ctx->a.ensure(sizeof(uint64_t) * D))) return rc;
-    if ((rc = ctx->b.ensure(sizeof(uint64_t) * D))) return rc;
-    if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
-    uint64_t* a = ctx->a.u64();
-    uint64_t* b = ctx->b.u64();
-    uint64_t* words = ctx->words.u64();
+    if ((rc = build_eq(ctx, s, job.rx, job.mu, job.ry, job.nu))) return rc;
 
     // a1 + a3 for A, then a1 + a4 for B: each operand is widened into scratch (skipped for
     // pre-encoded tables or in narrow-read mode) and reduced right away, so the reduction of A
@@ -345,7 +281,8 @@ static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uin
         Ap = ctx->encA.p;
         dtA = IMM_F64P;
     }
-    if ((rc = partial_over_rows(ctx, s, IMM_K_REDUCE_A, Ap, dtA, m, d, d, ctx->eqx.u64(), D, ctx->partA, a))) return rc;
+    if ((rc = partial_over_rows(ctx, s, IMM_K_REDUCE_A, Ap, dtA, m, d, d, ctx->eqx.u64(), D, ctx->partA, job.a)))
+        return rc;
     if (ctx->widen && dtB != IMM_F64P) {
         if ((rc = ctx->encB.ensure(sizeof(uint64_t) * d * n))) return rc;
         if ((rc = ctx->prof.begin(IMM_K_ENCODE_B, s))) return rc;
@@ -354,72 +291,235 @@ static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uin
         Bp = ctx->encB.p;
         dtB = IMM_F64P;
     }
-    if ((rc = partial_over_cols(ctx, s, IMM_K_REDUCE_B, Bp, dtB, d, n, n, ctx->eqy.u64(), D, ctx->partB, b))) return rc;
+    if ((rc = partial_over_cols(ctx, s, IMM_K_REDUCE_B, Bp, dtB, d, n, n, ctx->eqy.u64(), D, ctx->partB, job.b)))
+        return rc;
 
+    std::memset(job.out, 0, sizeof(*job.out));
+    job.out->version = IMM_PROOF_VERSION;
+    job.out->mu = (uint32_t)job.mu;
+    job.out->delta = (uint32_t)job.delta;
+    job.out->nu = (uint32_t)job.nu;
+    return IMM_OK;
+}
+
+// delta == 0: a single shared index, the claim is the product of the two table entries.
+static int finish_without_rounds(imm_ctx* ctx, hipStream_t s, Job& job) {
+    int rc;
+    uint64_t av, bv;
+    if ((rc = fetch_words(ctx, s, job.a, 1, &av))) return rc;
+    if ((rc = fetch_words(ctx, s, job.b, 1, &bv))) return rc;
+    job.out->c0 = hf::mul(av, bv);
+    job.tr.absorb_words("clmC", &job.out->c0, 1);
+    job.out->vA = av;
+    job.out->vB = bv;
+    const uint64_t fin[2] = {av, bv};
+    job.tr.absorb_words("fin ", fin, 2);
+    return IMM_OK;
+}
+
+// Tables longer than the single-workgroup limit are first shortened with one launch and one
+// host round-trip per round.
+static int long_table_prefix(imm_ctx* ctx, hipStream_t s, Job& job) {
+    if (job.L <= k::kRoundsMaxL) return IMM_OK;
+    int rc;
+    uint64_t* words = ctx->words.u64();
+    uint64_t g[3];
+    if ((rc = run_round(ctx, s, job.a, job.b, job.L, false, 0, words + k::kWordG, g))) return rc;
+    job.out->c0 = hf::add(g[0], g[1]);
+    job.tr.absorb_words("clmC", &job.out->c0, 1);
+    job.claim_absorbed = true;
+    for (; job.L > k::kRoundsMaxL; ++job.kk) {
+        job.out->g[3 * job.kk] = g[0];
+        job.out->g[3 * job.kk + 1] = g[1];
+        job.out->g[3 * job.kk + 2] = g[2];
+        job.tr.absorb_words("rnd ", g, 3);
+        job.rr[job.kk] = job.tr.challenge();
+        if ((rc = run_round(ctx, s, job.a, job.b, job.L, true, job.rr[job.kk], words + k::kWordG, g))) return rc;
+        job.L >>= 1;
+    }
+    return IMM_OK;
+}
+
+// a5..a8 for up to kRoundsMaxJobs proofs at once: the round kernel (one workgroup per proof) runs
+// on the device while this thread hashes.  For every proof in turn the kernel posts g_k, the host
+// absorbs it, squeezes r_k and posts it back; independent proofs overlap their waits.
+static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, int count) {
+    k::Mailbox* mb = ctx->mailbox;
+    std::memset(mb, 0xFF, sizeof(k::Mailbox) * (size_t)count);
+    std::atomic_thread_fence(std::memory_order_seq_cst);
+    k::RoundsJobs rj{};
+    int max_rounds = 0;
+    for (int p = 0; p < count; ++p) {
+        rj.job[p].a = jobs[p]->a;
+        rj.job[p].b = jobs[p]->b;
+        rj.job[p].L = jobs[p]->L;
+        rj.job[p].rounds = jobs[p]->delta - jobs[p]->kk;
+        if (rj.job[p].rounds > max_rounds) max_rounds = rj.job[p].rounds;
+    }
+    int rc;
+    uint64_t* status_dev = ctx->words.u64() + k::kWordCount + 4;
+    if ((rc = ctx->prof.begin(IMM_K_ROUND, s))) return rc;
+    IMM_HIP(k::rounds_mailbox(s, rj, count, mb, ctx->spin_limit, status_dev));
+    if ((rc = ctx->prof.end(IMM_K_ROUND, s))) return rc;
+    bool ok = true;
+    for (int slot = 0; slot < max_rounds && ok; ++slot) {
+        for (int p = 0; p < count && ok; ++p) {
+            Job& job = *jobs[p];
+            if (slot >= rj.job[p].rounds) continue;
+            const int kk = job.kk + slot;
+            uint64_t g[3];
+            for (int t = 0; t < 3 && ok; ++t) ok = mail_wait(&mb[p].g[slot][t], ctx->host_wait_ms, &g[t]);
+            if (!ok) break;
+            if (!job.claim_absorbed) {
+                job.out->c0 = hf::add(g[0], g[1]);
+                job.tr.absorb_words("clmC", &job.out->c0, 1);
+                job.claim_absorbed = true;
+            }
+            job.out->g[3 * kk] = g[0];
+            job.out->g[3 * kk + 1] = g[1];
+            job.out->g[3 * kk + 2] = g[2];
+            job.tr.absorb_words("rnd ", g, 3);
+            job.rr[kk] = job.tr.challenge();
+            __atomic_store_n(&mb[p].r[slot], job.rr[kk], __ATOMIC_RELEASE);
+        }
+    }
+    for (int p = 0; p < count && ok; ++p) {
+        uint64_t fin[2] = {0, 0};
+        ok = mail_wait(&mb[p].fin[0], ctx->host_wait_ms, &fin[0]) && mail_wait(&mb[p].fin[1], ctx->host_wait_ms, &fin[1]);
+        if (!ok) break;
+        jobs[p]->out->vA = fin[0];
+        jobs[p]->out->vB = fin[1];
+        jobs[p]->tr.absorb_words("fin ", fin, 2);
+    }
+    if (!ok) {
+        // release every workgroup from whatever wait it is in, then let the kernel drain
+        for (int p = 0; p < count; ++p)
+            for (int t = 0; t < IMM_MAX_ROUNDS; ++t) __atomic_store_n(&mb[p].r[t], k::kMailAbort, __ATOMIC_RELEASE);
+        IMM_HIP(hipStreamSynchronize(s));
+        g_last_error = "round kernel and host transcript lost contact (mailbox wait ran out)";
+        return IMM_E_HIP;
+    }
+    // No stream synchronisation here: posting fin[] is a workgroup's last access to its mailbox
+    // and tables, every result is already on the host, and whatever is launched next on this
+    // stream is ordered behind the kernel's last instructions anyway.
+    return IMM_OK;
+}
+
+// a5..a8 in one launch that also hashes the transcript on the device; one copy at the end brings
+// back the proof words, the challenges and the new state.
+static int rounds_with_device_transcript(imm_ctx* ctx, hipStream_t s, Job& job) {
+    int rc;
+    uint64_t* words = ctx->words.u64();
+    const uint8_t* st = job.tr.s;
+    uint32_t st_in[8];
+    for (int i = 0; i < 8; ++i)
+        st_in[i] = (uint32_t)st[4 * i] << 24 | (uint32_t)st[4 * i + 1] << 16 | (uint32_t)st[4 * i + 2] << 8 |
+                   (uint32_t)st[4 * i + 3];
+    uint32_t* st_dev = reinterpret_cast<uint32_t*>(words + k::kWordCount);
+    if ((rc = ctx->prof.begin(IMM_K_ROUND, s))) return rc;
+    IMM_HIP(k::rounds(s, job.a, job.b, job.L, job.delta - job.kk, job.kk, !job.claim_absorbed, st_in, words, st_dev));
+    if ((rc = ctx->prof.end(IMM_K_ROUND, s))) return rc;
+    uint64_t hw[k::kWordCount + 4];
+    if ((rc = fetch_words(ctx, s, words, k::kWordCount + 4, hw))) return rc;
+    imm_proof* out = job.out;
+    if (!job.claim_absorbed) out->c0 = hw[k::kWordC0];
+    for (int t = job.kk; t < job.delta; ++t) {
+        out->g[3 * t] = hw[k::kWordG + 3 * t];
+        out->g[3 * t + 1] = hw[k::kWordG + 3 * t + 1];
+        out->g[3 * t + 2] = hw[k::kWordG + 3 * t + 2];
+        job.rr[t] = hw[k::kWordR + t];
+    }
+    out->vA = hw[k::kWordVA];
+    out->vB = hw[k::kWordVB];
+    const uint32_t* st_out = reinterpret_cast<const uint32_t*>(hw + k::kWordCount);
+    for (int i = 0; i < 8; ++i) {
+        job.tr.s[4 * i] = (uint8_t)(st_out[i] >> 24);
+        job.tr.s[4 * i + 1] = (uint8_t)(st_out[i] >> 16);
+        job.tr.s[4 * i + 2] = (uint8_t)(st_out[i] >> 8);
+        job.tr.s[4 * i + 3] = (uint8_t)st_out[i];
+    }
+    return IMM_OK;
+}
+
+// Everything after the streaming phase for one proof; leaves the new state in job.tr.
+static int finish_one(imm_ctx* ctx, hipStream_t s, Job& job) {
+    int rc;
+    if (job.delta == 0) return finish_without_rounds(ctx, s, job);
+    if ((rc = long_table_prefix(ctx, s, job))) return rc;
+    if (ctx->transcript_mode == IMM_TRANSCRIPT_HOST) {
+        Job* one = &job;
+        return rounds_with_host_transcript(ctx, s, &one, 1);
+    }
+    return rounds_with_device_transcript(ctx, s, job);
+}
+
+static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uint8_t state[32], imm_proof* out) {
+    if (!state || !out) return IMM_E_NULL;
+    int rc;
+    if ((rc = check_desc(ds))) return rc;
+    Job job(state);
+    job.ds = &ds;
+    job.out = out;
+    const uint64_t D = 1ull << hf::ceil_log2(ds.d);
+    if ((rc = ctx->a.ensure(sizeof(uint64_t) * D))) return rc;
+    if ((rc = ctx->b.ensure(sizeof(uint64_t) * D))) return rc;
+    if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
+    job.a = ctx->a.u64();
+    job.b = ctx->b.u64();
+    if ((rc = stream_phase(ctx, s, job))) return rc;
     if (ctx->debug) {
         if ((rc = ctx->snapA.ensure(sizeof(uint64_t) * D))) return rc;
         if ((rc = ctx->snapB.ensure(sizeof(uint64_t) * D))) return rc;
-        IMM_HIP(hipMemcpyAsync(ctx->snapA.p, a, sizeof(uint64_t) * D, hipMemcpyDeviceToDevice, s));
-        IMM_HIP(hipMemcpyAsync(ctx->snapB.p, b, sizeof(uint64_t) * D, hipMemcpyDeviceToDevice, s));
+        IMM_HIP(hipMemcpyAsync(ctx->snapA.p, job.a, sizeof(uint64_t) * D, hipMemcpyDeviceToDevice, s));
+        IMM_HIP(hipMemcpyAsync(ctx->snapB.p, job.b, sizeof(uint64_t) * D, hipMemcpyDeviceToDevice, s));
     }
+    if ((rc = finish_one(ctx, s, job))) return rc;
+    std::memcpy(state, job.tr.s, 32);
+    if (ctx->debug) {
+        ctx->dbg_mu = job.mu; ctx->dbg_delta = job.delta; ctx->dbg_nu = job.nu;
+        std::memcpy(ctx->dbg_rx, job.rx, sizeof(job.rx));
+        std::memcpy(ctx->dbg_ry, job.ry, sizeof(job.ry));
+        std::memcpy(ctx->dbg_r, job.rr, sizeof(job.rr));
+    }
+    return ctx->prof.mask ? ctx->prof.flush() : IMM_OK;
+}
 
-    std::memset(out, 0, sizeof(*out));
-    out->version = IMM_PROOF_VERSION;
-    out->mu = (uint32_t)mu;
-    out->delta = (uint32_t)delta;
-    out->nu = (uint32_t)nu;
-
-    if (delta == 0) {
-        // a single shared index: the claim is the product of the two table entries
-        uint64_t av, bv;
-        if ((rc = fetch_words(ctx, s, a, 1, &av))) return rc;
-        if ((rc = fetch_words(ctx, s, b, 1, &bv))) return rc;
-        out->c0 = hf::mul(av, bv);
-        tr.absorb_words("clmC", &out->c0, 1);
-        out->vA = av;
-        out->vB = bv;
-        const uint64_t fin[2] = {av, bv};
-        tr.absorb_words("fin ", fin, 2);
-        std::memcpy(state, tr.s, 32);
-    } else {
-        // a5..a8.  Tables longer than the single-workgroup limit are first shortened with one
-        // launch and one host round-trip per round; the remaining rounds run in one launch that
-        // hashes the transcript on the device.
-        uint64_t L = D;
-        int kk = 0;
-        bool claim_absorbed = false;
-        if (L > k::kRoundsMaxL) {
-            uint64_t g[3];
-            if ((rc = run_round(ctx, s, a, b, L, false, 0, words + k::kWordG, g))) return rc;
-            out->c0 = hf::add(g[0], g[1]);
-            tr.absorb_words("clmC", &out->c0, 1);
-            claim_absorbed = true;
-            for (; L > k::kRoundsMaxL; ++kk) {
-                out->g[3 * kk] = g[0];
-                out->g[3 * kk + 1] = g[1];
-                out->g[3 * kk + 2] = g[2];
-                tr.absorb_words("rnd ", g, 3);
-                rr[kk] = tr.challenge();
-                if ((rc = run_round(ctx, s, a, b, L, true, rr[kk], words + k::kWordG, g))) return rc;
-                L >>= 1;
+// Independent proofs (every one starts from `start`): the streaming phases are queued back to
+// back, each into its own pair of tables, and the round loops of a whole group then run in one
+// launch.  A statement that needs a different path (no rounds, very long tables) is proven on its
+// own.  states_out[p] receives the state after proof p.
+static int prove_independent(imm_ctx* ctx, hipStream_t s, int count, const imm_matmul_desc* descs,
+                             const uint8_t start[32], imm_proof* outs, uint8_t* states) {
+    int rc;
+    if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
+    for (int g0 = 0; g0 < count; g0 += k::kRoundsMaxJobs) {
+        const int g1 = g0 + k::kRoundsMaxJobs < count ? g0 + k::kRoundsMaxJobs : count;
+        uint64_t words_needed = 0;
+        for (int p = g0; p < g1; ++p) words_needed += 2ull << hf::ceil_log2(descs[p].d);
+        if ((rc = ctx->group_tables.ensure(sizeof(uint64_t) * words_needed))) return rc;
+        std::vector<Job> jobs;
+        jobs.reserve((size_t)(g1 - g0));
+        std::vector<Job*> grouped;
+        uint64_t* next = ctx->group_tables.u64();
+        for (int p = g0; p < g1; ++p) {
+            jobs.emplace_back(start);
+            Job& job = jobs.back();
+            job.ds = &descs[p];
+            job.out = &outs[p];
+            const uint64_t D = 1ull << hf::ceil_log2(descs[p].d);
+            job.a = next;
+            job.b = next + D;
+            next += 2 * D;
+            if ((rc = stream_phase(ctx, s, job))) return rc;
+            if (job.delta == 0 || job.L > k::kRoundsMaxL) {
+                if ((rc = finish_one(ctx, s, job))) return rc;
+            } else {
+                grouped.push_back(&job);
             }
         }
-        if (ctx->transcript_mode == IMM_TRANSCRIPT_HOST) {
-            if ((rc = rounds_with_host_transcript(ctx, s, a, b, L, delta, kk, claim_absorbed, tr, out, rr,
-                                                  words + k::kWordCount + 4)))
-                return rc;
-            std::memcpy(state, tr.s, 32);
-        } else {
-            if ((rc = rounds_with_device_transcript(ctx, s, a, b, L, delta, kk, claim_absorbed, tr, out, rr, words,
-                                                    state)))
-                return rc;
-        }
-    }
-    if (ctx->debug) {
-        ctx->dbg_mu = mu; ctx->dbg_delta = delta; ctx->dbg_nu = nu;
-        std::memcpy(ctx->dbg_rx, rx, sizeof(rx));
-        std::memcpy(ctx->dbg_ry, ry, sizeof(ry));
-        std::memcpy(ctx->dbg_r, rr, sizeof(rr));
+        if (!grouped.empty() && (rc = rounds_with_host_transcript(ctx, s, grouped.data(), (int)grouped.size())))
+            return rc;
+        for (int p = g0; p < g1; ++p) std::memcpy(states + 32 * (size_t)p, jobs[(size_t)(p - g0)].tr.s, 32);
     }
     return ctx->prof.mask ? ctx->prof.flush() : IMM_OK;
 }
@@ -448,7 +548,7 @@ extern "C" int imm_ctx_create(imm_ctx** out, int device, size_t scratch_bytes) {
         delete ctx;
         return fail_hip(e, "hipHostMalloc");
     }
-    e = hipHostMalloc(reinterpret_cast<void**>(&ctx->mailbox), sizeof(k::Mailbox),
+    e = hipHostMalloc(reinterpret_cast<void**>(&ctx->mailbox), sizeof(k::Mailbox) * k::kRoundsMaxJobs,
                       hipHostMallocMapped | hipHostMallocCoherent);
     if (e != hipSuccess) {
         (void)hipHostFree(ctx->pinned);
@@ -474,7 +574,7 @@ extern "C" int imm_ctx_destroy(imm_ctx* ctx) {
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
     for (DevBuf* bf : {&ctx->encA, &ctx->encB, &ctx->eqx, &ctx->eqy, &ctx->a, &ctx->b, &ctx->partA, &ctx->partB,
-                       &ctx->round_scratch, &ctx->words, &ctx->snapA, &ctx->snapB})
+                       &ctx->round_scratch, &ctx->words, &ctx->snapA, &ctx->snapB, &ctx->group_tables})
         bf->release();
     ctx->prof.destroy();
     if (ctx->pinned) (void)hipHostFree(ctx->pinned);
@@ -603,15 +703,20 @@ extern "C" int imm_sumcheck_matmul_prove_batch(imm_ctx* ctx, void* stream, int c
     hipStream_t s = static_cast<hipStream_t>(stream);
     // validate everything before the first launch
     for (int t = 0; t < count; ++t) {
-        const imm_matmul_desc& ds = descs[t];
-        if (!ds.A_dev || !ds.B_dev || !ds.com) return IMM_E_NULL;
-        if (!dim_ok(ds.m) || !dim_ok(ds.d) || !dim_ok(ds.n)) return IMM_E_SHAPE;
-        if (ds.dtA != IMM_I16 && ds.dtA != IMM_F64P) return IMM_E_DTYPE;
-        if (ds.dtB != IMM_I8 && ds.dtB != IMM_F64P) return IMM_E_DTYPE;
+        int rc = check_desc(descs[t]);
+        if (rc) return rc;
     }
     uint8_t start[32], cur[32];
     std::memcpy(start, transcript_state, 32);
     std::memcpy(cur, transcript_state, 32);
+    if (!chained && count > 1 && ctx->transcript_mode == IMM_TRANSCRIPT_HOST && !ctx->debug) {
+        std::vector<uint8_t> states((size_t)count * 32);
+        int rc = prove_independent(ctx, s, count, descs, start, outs_host, states.data());
+        if (rc) return rc;
+        if (states_out) std::memcpy(states_out, states.data(), states.size());
+        std::memcpy(transcript_state, states.data() + 32 * (size_t)(count - 1), 32);
+        return IMM_OK;
+    }
     for (int t = 0; t < count; ++t) {
         if (!chained) std::memcpy(cur, start, 32);
         int rc = prove_one(ctx, s, descs[t], cur, &outs_host[t]);

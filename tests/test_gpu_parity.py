@@ -305,7 +305,7 @@ def test_config5_dense_layers_chained(torch, ctx, oracle_fast):
 
 def test_batch_chained_and_independent_small(torch, ctx, oracle_fast):
     rng = np.random.default_rng(99)
-    shapes = [(5, 33, 12), (1, 64, 300), (9, 7, 2), (16, 128, 64)]
+    shapes = [(5, 33, 12), (1, 64, 300), (9, 7, 2), (16, 128, 64), (3, 1, 4), (2, 2, 2)]
     items, oracle_items = [], []
     for (m, d, n) in shapes:
         A = rng.integers(-2**15, 2**15, size=(m, d), dtype=np.int16)
@@ -327,6 +327,27 @@ def test_batch_chained_and_independent_small(torch, ctx, oracle_fast):
     # empty batch leaves the state alone
     g0, st0, f0 = ctx.imm_sumcheck_matmul_prove_batch([], True, ref.FS_INIT)
     assert g0 == [] and f0 == ref.FS_INIT
+
+
+def test_independent_batch_larger_than_one_group(torch, ctx, oracle_fast):
+    """More independent proofs than one launch of the round kernel takes, with mixed round counts."""
+    rng = np.random.default_rng(123)
+    items, oracle_items = [], []
+    for t in range(19):
+        m, d, n = 1 + t % 5, [16, 3, 64, 1, 200][t % 5], 16 * (1 + t % 3)
+        A = rng.integers(-2**15, 2**15, size=(m, d), dtype=np.int16)
+        B = rng.integers(-128, 128, size=(d, n), dtype=np.int8)
+        C = oracle_fast.matmul(A, B)
+        com = imm.imm_commit_matmul(A, B, C, m, d, n)
+        oracle_items.append((A, B, C, com.digests()))
+        items.append((dev(torch, A), dev(torch, B), com))
+    want, want_states = oracle_fast.prove_chain(oracle_items, chained=False)
+    for widen in (1, 0):
+        ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, widen)
+        got, states, final = ctx.imm_sumcheck_matmul_prove_batch(items, False, ref.FS_INIT)
+        assert [p.words() for p in got] == [ref.proof_words(p) for p in want]
+        assert states == want_states and final == want_states[-1]
+    ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
 
 
 def test_proofs_are_deterministic_and_survive_other_streams(torch, ctx, oracle_fast):
