@@ -193,6 +193,29 @@ def main():
                      "avg_launch_us": round(avg_ms * 1e3, 2), "algorithmic_bytes_per_launch": 8.0 * b_entries / max(launches_per_step, 1)},
     }
 
+    # Opening of C at (rx || ry): the bilinear MLE of the int64 product matrix, streamed once by the
+    # same row-wise reduction (8 B per entry), as a verifier-side check would need it.
+    if args.workload == "ffn_up":
+        A0, B0 = stmts[0][2], stmts[0][3]
+        Cd = (A0.double() @ B0.double()).round().to(torch.int64)
+        pr = [(0x9E3779B97F4A7C15 * (i + 1)) % 0xFFFFFFFF00000001 for i in range(11)]
+        pc = [(0xC2B2AE3D27D4EB4F * (i + 1)) % 0xFFFFFFFF00000001 for i in range(14)]
+        for _ in range(2):
+            ctx.imm_mle_eval(Cd, pr, pc)
+        ctx.imm_ctx_reset_profiling()
+        ctx.imm_ctx_set_profiling(1 << imm.IMM_K_REDUCE_B)
+        for _ in range(10):
+            ctx.imm_mle_eval(Cd, pr, pc)
+        ctx.imm_ctx_set_profiling(0)
+        nc, msc = ctx.imm_ctx_kernel_time(imm.IMM_K_REDUCE_B)
+        usc = msc * 1e3 / nc
+        cbytes = Cd.numel() * 8
+        result["mle_eval_C_int64"] = {"rows": Cd.shape[0], "cols": Cd.shape[1], "us_per_launch": round(usc, 1),
+                                      "algorithmic_MB": cbytes / 1e6, "GBps": round(cbytes / (usc * 1e-6) / 1e9, 1),
+                                      "frac_of_8TBps": round(cbytes / (usc * 1e-6) / 1e9 / HBM_PEAK_GBS, 3)}
+        ctx.imm_ctx_reset_profiling()
+        del Cd
+
     # The per-round kernel on tables large enough to be bandwidth-bound (the proof's own tables are
     # 2 x 32 KB, i.e. latency-bound): fold + evaluate on two tables of 2^26 elements, in place.
     # Algorithmic bytes per launch: 16 B read + 8 B written per table entry pair = 24 * L.
