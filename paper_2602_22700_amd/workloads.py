@@ -92,3 +92,27 @@ def dense_layer(layer: int, tokens: int = 1024) -> Iterator[Tuple[str, np.ndarra
         A = gaussian_int16((tokens, d), 5000 + 7 * layer + idx)
         B = uniform_int8((d, n), 1000 + 7 * layer + idx)
         yield name, A, B
+
+
+# --------------------------------------------------------------------------- logits for the distance step
+def round_to_bfloat16(x: np.ndarray) -> np.ndarray:
+    """float32 values rounded to the nearest bfloat16 (ties to even), returned as float32."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    return u.astype(np.uint32).view(np.float32).reshape(x.shape)
+
+
+def logits_pair(steps: int, vocab: int, seed: int, scale: float = 4.0, noise: float = 0.02):
+    """(deployed, reference) float32 logits of `steps` decision steps over `vocab` entries.
+    The reference is Gaussian with standard deviation `scale` (a moderately peaked softmax); the
+    deployed logits are the reference rounded to bfloat16 plus small Gaussian noise, which is what a
+    finite-precision serving stack does to them."""
+    rng = np.random.default_rng(seed)
+    ref = (scale * rng.standard_normal((steps, vocab), dtype=np.float32)).astype(np.float32)
+    dep = round_to_bfloat16(ref) + (noise * rng.standard_normal((steps, vocab), dtype=np.float32)).astype(np.float32)
+    return dep.astype(np.float32), ref
+
+
+def topk_indices(logits: np.ndarray, k: int) -> np.ndarray:
+    """Indices of the k largest entries of every row (what a server would record), int32."""
+    return np.argsort(-logits, axis=1, kind="stable")[:, :k].astype(np.int32)
