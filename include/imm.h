@@ -197,6 +197,37 @@ int imm_verify(const imm_commit* com, const uint8_t transcript_in[32], const imm
                const int16_t* A, const int8_t* B, const int64_t* C,
                uint8_t transcript_out[32], int* fail_round);
 
+/* ---- Logit distances of the audited decision steps ------------------------------------------
+ * Beside the matrix products, the audit proof reports how far the deployed logits l_i of each
+ * discrete decision step were from the reference logits l*_i (paper section 4.3, logit distance
+ * distribution; section 5.3, per-request statistic p(t1); appendix "Optimization: Verification of
+ * Top-K", top-K distance).  These calls compute those numbers for T steps over a vocabulary of n
+ * entries; logits are float32, row-major with leading dimension ld (elements), resident on the
+ * device.  Exponentials are evaluated in float32, every sum is accumulated in float64, results are
+ * float64.  All three are asynchronous on `stream` except where a HOST result is returned. */
+
+#define IMM_TOPK_MAX 64 /* largest supported K of imm_topk_distance */
+
+/* tv_out_dev[i] = 1/2 sum_j |p_j - q_j| and kl_out_dev[i] = sum_j p_j (log p_j - log q_j) with
+ * p = softmax(logits row i) (deployed) and q = softmax(ref row i) (reference).  Either output may
+ * be NULL.  logits_dev, ref_dev: DEVICE float32 T x n; outputs: DEVICE float64[T].
+ * Errors: IMM_E_NULL, IMM_E_SHAPE (T or n zero, ld < n), IMM_E_HIP. */
+int imm_ldd_tv_kl(imm_ctx* ctx, void* stream, const float* logits_dev, const float* ref_dev,
+                  uint64_t T, uint64_t n, uint64_t ld, double* tv_out_dev, double* kl_out_dev);
+
+/* out_dev[i] = min over l' with Top_K(l') = I_i of ||l' - l_i||_1: the smallest L1 change of row i
+ * of logits_dev after which the K recorded indices idx_dev[i*K .. i*K+K) are a valid top-K set
+ * (0 iff they already are).  idx_dev: DEVICE int32 T x K, 1 <= K <= IMM_TOPK_MAX, K < n; the
+ * indices of a row must be distinct and inside [0, n) -- a row that violates this yields NaN.
+ * out_dev: DEVICE float64[T].  Errors: IMM_E_NULL, IMM_E_SHAPE, IMM_E_HIP. */
+int imm_topk_distance(imm_ctx* ctx, void* stream, const float* logits_dev, uint64_t T, uint64_t n,
+                      uint64_t ld, const int32_t* idx_dev, uint32_t K, double* out_dev);
+
+/* *out_host = |{i < T : dist_dev[i] > t1}| / T, the per-request tail density p(t1).
+ * dist_dev: DEVICE float64[T].  Synchronises `stream`.  Errors: IMM_E_NULL, IMM_E_SHAPE, IMM_E_HIP. */
+int imm_tail_density(imm_ctx* ctx, void* stream, const double* dist_dev, uint64_t T, double t1,
+                     double* out_host);
+
 /* Test/diagnostic access to the intermediates of the most recent single proof of
  * this context: which = 0 eqx (2^mu), 1 eqy (2^nu), 2 a = A~(rx, .) (2^delta),
  * 3 b = B~(., ry) (2^delta), 4 rx, 5 ry, 6 r (the round challenges).  Copies at
@@ -231,7 +262,9 @@ int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value);
 #define IMM_K_REDUCE_B 4   /* partial MLE of B over its columns (row-wise reduction) */
 #define IMM_K_ROUND 5      /* evaluate g_k(0,1,2) + fold */
 #define IMM_K_COMBINE 6    /* sum of per-split partial vectors */
-#define IMM_K_COUNT 7
+#define IMM_K_LDD 7        /* TV / KL distances of the logits */
+#define IMM_K_TOPK 8       /* top-K distance */
+#define IMM_K_COUNT 9
 /* mask: bit k set = time kernel id k (0 = profiling off). */
 int imm_ctx_set_profiling(imm_ctx* ctx, uint32_t mask);
 /* Sum of durations (ms) and number of launches since the last reset. */

@@ -21,14 +21,16 @@ IMM_I8, IMM_I16, IMM_I64, IMM_F64P = 1, 2, 3, 4
 IMM_OPT_DEBUG_SNAPSHOTS, IMM_OPT_WIDEN, IMM_OPT_TRANSCRIPT, IMM_OPT_SPIN_LIMIT, IMM_OPT_HOST_WAIT_MS = 1, 2, 3, 4, 5
 IMM_TRANSCRIPT_DEVICE, IMM_TRANSCRIPT_HOST = 0, 1
 (IMM_K_ENCODE_A, IMM_K_ENCODE_B, IMM_K_EQ, IMM_K_REDUCE_A, IMM_K_REDUCE_B, IMM_K_ROUND,
- IMM_K_COMBINE, IMM_K_COUNT) = range(8)
-KERNEL_NAMES = ["encode_A", "encode_B", "eq_build", "reduce_A", "reduce_B", "round", "combine"]
+ IMM_K_COMBINE, IMM_K_LDD, IMM_K_TOPK, IMM_K_COUNT) = range(10)
+IMM_TOPK_MAX = 64
+KERNEL_NAMES = ["encode_A", "encode_B", "eq_build", "reduce_A", "reduce_B", "round", "combine", "ldd_tv_kl",
+                "topk_distance"]
 
 EXPORTS = [
     "imm_ctx_create", "imm_ctx_destroy", "imm_last_error", "imm_fs_init", "imm_commit_matmul", "imm_encode",
     "imm_mle_eval", "imm_sumcheck_matmul_prove", "imm_sumcheck_matmul_prove_batch", "imm_round_fold_eval",
     "imm_verify", "imm_debug_fetch", "imm_ctx_set_option", "imm_ctx_set_profiling", "imm_ctx_kernel_time",
-    "imm_ctx_reset_profiling",
+    "imm_ctx_reset_profiling", "imm_ldd_tv_kl", "imm_topk_distance", "imm_tail_density",
 ]
 
 
@@ -104,6 +106,9 @@ def load() -> ctypes.CDLL:
     L.imm_ctx_set_profiling.argtypes = [vp, u32]
     L.imm_ctx_kernel_time.argtypes = [vp, i32, ctypes.POINTER(u64), ctypes.POINTER(ctypes.c_double)]
     L.imm_ctx_reset_profiling.argtypes = [vp]
+    L.imm_ldd_tv_kl.argtypes = [vp, vp, vp, vp, u64, u64, u64, vp, vp]
+    L.imm_topk_distance.argtypes = [vp, vp, vp, u64, u64, u64, vp, u32, vp]
+    L.imm_tail_density.argtypes = [vp, vp, vp, u64, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
     for name in EXPORTS:
         if name != "imm_last_error":
             getattr(L, name).restype = i32
@@ -270,6 +275,43 @@ class Context:
         _check(rc, "imm_sumcheck_matmul_prove_batch")
         sb = bytes(states)
         return ([proofs[t].copy() for t in range(count)], [sb[32 * t:32 * t + 32] for t in range(count)], bytes(st))
+
+    def imm_ldd_tv_kl(self, logits, ref, want_tv: bool = True, want_kl: bool = True, stream=None):
+        """logits, ref: device float32 T x n.  Returns (tv, kl) device float64[T] tensors (None if not wanted)."""
+        import torch
+        assert logits.is_cuda and ref.is_cuda and logits.dtype == torch.float32 and ref.dtype == torch.float32
+        assert logits.dim() == 2 and logits.shape == ref.shape and logits.stride(1) == 1 and ref.stride(1) == 1
+        assert logits.stride(0) == ref.stride(0)
+        T, n = logits.shape
+        tv = torch.empty(T, dtype=torch.float64, device=logits.device) if want_tv else None
+        kl = torch.empty(T, dtype=torch.float64, device=logits.device) if want_kl else None
+        rc = load().imm_ldd_tv_kl(self._h, _stream_handle(stream), logits.data_ptr(), ref.data_ptr(), T, n,
+                                  logits.stride(0), tv.data_ptr() if want_tv else None,
+                                  kl.data_ptr() if want_kl else None)
+        _check(rc, "imm_ldd_tv_kl")
+        return tv, kl
+
+    def imm_topk_distance(self, logits, idx, stream=None):
+        """logits: device float32 T x n; idx: device int32 T x K.  Returns device float64[T]."""
+        import torch
+        assert logits.is_cuda and idx.is_cuda and logits.dtype == torch.float32 and idx.dtype == torch.int32
+        assert logits.dim() == 2 and idx.dim() == 2 and logits.stride(1) == 1 and idx.is_contiguous()
+        T, n = logits.shape
+        assert idx.shape[0] == T
+        out = torch.empty(T, dtype=torch.float64, device=logits.device)
+        rc = load().imm_topk_distance(self._h, _stream_handle(stream), logits.data_ptr(), T, n, logits.stride(0),
+                                      idx.data_ptr(), idx.shape[1], out.data_ptr())
+        _check(rc, "imm_topk_distance")
+        return out
+
+    def imm_tail_density(self, dist, t1: float, stream=None) -> float:
+        import torch
+        assert dist.is_cuda and dist.dtype == torch.float64 and dist.is_contiguous()
+        out = ctypes.c_double(0.0)
+        rc = load().imm_tail_density(self._h, _stream_handle(stream), dist.data_ptr(), dist.numel(), float(t1),
+                                     ctypes.byref(out))
+        _check(rc, "imm_tail_density")
+        return out.value
 
     def prepare_batch(self, items, chained: bool, state: bytes, stream=None) -> "PreparedBatch":
         """Marshal a batch once; PreparedBatch.run() then only performs the C call."""

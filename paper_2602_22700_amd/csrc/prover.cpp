@@ -13,6 +13,7 @@
 #include "../../include/imm.h"
 #include "host_field.h"
 #include "kernels.h"
+#include "ldd.h"
 #include "transcript.h"
 
 namespace imm {
@@ -768,5 +769,46 @@ extern "C" int imm_debug_fetch(imm_ctx* ctx, int which, uint64_t* out_host, uint
         IMM_HIP(hipDeviceSynchronize());
         IMM_HIP(hipMemcpy(out_host, dev_src, ncopy * sizeof(uint64_t), hipMemcpyDeviceToHost));
     }
+    return IMM_OK;
+}
+
+extern "C" int imm_ldd_tv_kl(imm_ctx* ctx, void* stream, const float* logits_dev, const float* ref_dev, uint64_t T,
+                             uint64_t n, uint64_t ld, double* tv_out_dev, double* kl_out_dev) {
+    if (!ctx || !logits_dev || !ref_dev || (!tv_out_dev && !kl_out_dev)) return IMM_E_NULL;
+    if (T == 0 || n == 0 || ld < n || T > 0x7FFFFFFFull) return IMM_E_SHAPE;
+    IMM_HIP(hipSetDevice(ctx->device));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc;
+    if ((rc = ctx->prof.begin(IMM_K_LDD, s))) return rc;
+    IMM_HIP(k::ldd_tv_kl(s, logits_dev, ref_dev, T, n, ld, tv_out_dev, kl_out_dev));
+    return ctx->prof.end(IMM_K_LDD, s);
+}
+
+extern "C" int imm_topk_distance(imm_ctx* ctx, void* stream, const float* logits_dev, uint64_t T, uint64_t n,
+                                 uint64_t ld, const int32_t* idx_dev, uint32_t K, double* out_dev) {
+    if (!ctx || !logits_dev || !idx_dev || !out_dev) return IMM_E_NULL;
+    if (T == 0 || n == 0 || ld < n || T > 0x7FFFFFFFull || n > 0x7FFFFFFFull) return IMM_E_SHAPE;
+    if (K < 1 || K > IMM_TOPK_MAX || K >= n) return IMM_E_SHAPE;
+    IMM_HIP(hipSetDevice(ctx->device));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc;
+    if ((rc = ctx->prof.begin(IMM_K_TOPK, s))) return rc;
+    IMM_HIP(k::topk_distance(s, logits_dev, T, n, ld, idx_dev, K, out_dev));
+    return ctx->prof.end(IMM_K_TOPK, s);
+}
+
+extern "C" int imm_tail_density(imm_ctx* ctx, void* stream, const double* dist_dev, uint64_t T, double t1,
+                                double* out_host) {
+    if (!ctx || !dist_dev || !out_host) return IMM_E_NULL;
+    if (T == 0) return IMM_E_SHAPE;
+    IMM_HIP(hipSetDevice(ctx->device));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc;
+    if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
+    unsigned long long* count_dev = reinterpret_cast<unsigned long long*>(ctx->words.u64());
+    IMM_HIP(k::tail_count(s, dist_dev, T, t1, count_dev));
+    uint64_t count = 0;
+    if ((rc = fetch_words(ctx, s, ctx->words.u64(), 1, &count))) return rc;
+    *out_host = (double)count / (double)T;
     return IMM_OK;
 }

@@ -96,23 +96,50 @@ def dense_layer(layer: int, tokens: int = 1024) -> Iterator[Tuple[str, np.ndarra
 
 # --------------------------------------------------------------------------- logits for the distance step
 def round_to_bfloat16(x: np.ndarray) -> np.ndarray:
-    """float32 values rounded to the nearest bfloat16 (ties to even), returned as float32."""
-    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
-    u = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
-    return u.astype(np.uint32).view(np.float32).reshape(x.shape)
+    """Finite float32 values rounded to the nearest bfloat16 (ties to even), returned as float32."""
+    u = np.array(x, dtype=np.float32, order="C").view(np.uint32)
+    bias = (u >> np.uint32(16)) & np.uint32(1)
+    bias += np.uint32(0x7FFF)
+    u += bias            # finite inputs cannot wrap: their exponent field is below 0xFF
+    u &= np.uint32(0xFFFF0000)
+    return u.view(np.float32).reshape(np.shape(x))
 
 
-def logits_pair(steps: int, vocab: int, seed: int, scale: float = 4.0, noise: float = 0.02):
+LOGITS_ROW_BLOCK = 64
+
+
+def logits_pair(steps: int, vocab: int, seed: int, scale: float = 4.0, noise: float = 0.02, workers: int = 8):
     """(deployed, reference) float32 logits of `steps` decision steps over `vocab` entries.
     The reference is Gaussian with standard deviation `scale` (a moderately peaked softmax); the
     deployed logits are the reference rounded to bfloat16 plus small Gaussian noise, which is what a
-    finite-precision serving stack does to them."""
-    rng = np.random.default_rng(seed)
-    ref = (scale * rng.standard_normal((steps, vocab), dtype=np.float32)).astype(np.float32)
-    dep = round_to_bfloat16(ref) + (noise * rng.standard_normal((steps, vocab), dtype=np.float32)).astype(np.float32)
-    return dep.astype(np.float32), ref
+    finite-precision serving stack does to them.  Every block of 64 rows has generators of its own,
+    seeded by (seed, block, which), so the values do not depend on how many threads fill the blocks."""
+    ref = np.empty((steps, vocab), dtype=np.float32)
+    dep = np.empty((steps, vocab), dtype=np.float32)
+
+    def fill(block: int) -> None:
+        rows = slice(block * LOGITS_ROW_BLOCK, min(steps, (block + 1) * LOGITS_ROW_BLOCK))
+        np.random.default_rng([seed, block, 0]).standard_normal(out=ref[rows], dtype=np.float32)
+        ref[rows] *= np.float32(scale)
+        np.random.default_rng([seed, block, 1]).standard_normal(out=dep[rows], dtype=np.float32)
+        dep[rows] *= np.float32(noise)
+        dep[rows] += round_to_bfloat16(ref[rows])
+
+    blocks = range((steps + LOGITS_ROW_BLOCK - 1) // LOGITS_ROW_BLOCK)
+    if workers > 1 and len(blocks) > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(workers) as pool:
+            list(pool.map(fill, blocks))
+    else:
+        for b in blocks:
+            fill(b)
+    return dep, ref
 
 
 def topk_indices(logits: np.ndarray, k: int) -> np.ndarray:
-    """Indices of the k largest entries of every row (what a server would record), int32."""
-    return np.argsort(-logits, axis=1, kind="stable")[:, :k].astype(np.int32)
+    """Indices of k largest entries of every row, largest first (what a server would record), int32.
+    Among equal values any choice is a valid top-k set; no particular one is promised."""
+    part = np.argpartition(-logits, k - 1, axis=1)[:, :k]
+    vals = np.take_along_axis(logits, part, axis=1)
+    order = np.argsort(-vals, axis=1, kind="stable")
+    return np.take_along_axis(part, order, axis=1).astype(np.int32)

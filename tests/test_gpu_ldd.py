@@ -1,0 +1,252 @@
+"""GPU parity of the logit-distance kernels (TV, KL, top-K distance, tail density) against the
+float64 oracle, on the same seeded logits.  All calls go through the C ABI (ctypes binding).
+
+Tolerances (floating point, so not bit-exact):
+
+* TV / KL.  The kernel takes e^d, d = x - max <= 0, as the fp32 base-2 exponential of d*log2(e).
+  A term's relative error is at most eps_i = 2^-24 (2.3 |d_i| + 4): half an ulp of d, half an ulp
+  of the product and the rounded constant scale with |d_i|, the exponential itself and the
+  four-term fp32 partial sums do not.  Weighted by the softmax, sum_i p_i |d_i| <= ln n, so every
+  normalised sum is off by at most E(n) = 2^-24 (2.3 ln n + 8).  TV carries that error in both
+  distributions, in numerator and normaliser: |dTV| <= 2 E(n).  KL = W/Z - lse(x) + lse(y) carries
+  it once in each log-sum-exp and, scaled by max|x - y|, twice in W/Z.
+* Top-K distance: the same at most 2K double-precision terms in a different order: 1e-12 relative
+  to the largest |logit| in the row.
+* Tail density: a count; exact on the distances the GPU produced.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import ldd as oracle
+from paper_2602_22700_amd import binding as imm
+from paper_2602_22700_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    if not t.cuda.is_available():
+        pytest.fail("a GPU test was selected but no GPU is visible")
+    return t
+
+
+@pytest.fixture(scope="module")
+def ctx(torch):
+    c = imm.Context(0)
+    yield c
+    c.close()
+
+
+@pytest.fixture(scope="module")
+def full_size():
+    """The shape the benchmark times: 2048 decision steps over a 128256-entry vocabulary."""
+    return workloads.logits_pair(2048, 128256, seed=2025)
+
+
+def E(n: int) -> float:
+    return 2.0 ** -24 * (2.3 * math.log(max(n, 2)) + 8.0)
+
+
+def check_tv_kl(torch, ctx, dep: np.ndarray, ref: np.ndarray, rows=None, dep_dev=None, ref_dev=None):
+    n = dep.shape[1]
+    if dep_dev is None:
+        dep_dev, ref_dev = torch.from_numpy(dep).cuda(), torch.from_numpy(ref).cuda()
+    tv, kl = ctx.imm_ldd_tv_kl(dep_dev, ref_dev)
+    tv, kl = tv.cpu().numpy(), kl.cpu().numpy()
+    worst = 0.0
+    for i in (range(dep.shape[0]) if rows is None else rows):
+        want_tv, want_kl = oracle.tv_distance(dep[i], ref[i]), oracle.kl_divergence(dep[i], ref[i])
+        span = float(np.abs(dep[i].astype(np.float64) - ref[i].astype(np.float64)).max())
+        assert abs(tv[i] - want_tv) <= 2 * E(n), (i, tv[i], want_tv)
+        assert abs(kl[i] - want_kl) <= E(n) * (2 + 2 * span), (i, kl[i], want_kl)
+        worst = max(worst, abs(tv[i] - want_tv) / (2 * E(n)))
+    return tv, kl, worst
+
+
+@pytest.mark.parametrize("steps,vocab", [(1, 1), (3, 2), (5, 7), (4, 1000), (3, 1024), (2, 4096), (3, 4099),
+                                         (2, 32000), (2, 128256)])
+def test_tv_kl_matches_oracle(torch, ctx, steps, vocab):
+    dep, ref = workloads.logits_pair(steps, vocab, seed=100 + vocab)
+    check_tv_kl(torch, ctx, dep, ref)
+
+
+def test_tv_kl_only_one_output_requested(torch, ctx):
+    dep, ref = workloads.logits_pair(4, 5000, seed=3)
+    d, r = torch.from_numpy(dep).cuda(), torch.from_numpy(ref).cuda()
+    tv_both, kl_both = ctx.imm_ldd_tv_kl(d, r)
+    tv_only, none_kl = ctx.imm_ldd_tv_kl(d, r, want_kl=False)
+    none_tv, kl_only = ctx.imm_ldd_tv_kl(d, r, want_tv=False)
+    assert none_kl is None and none_tv is None
+    assert torch.equal(tv_both, tv_only) and torch.equal(kl_both, kl_only)
+
+
+def test_tv_kl_unaligned_rows_take_the_scalar_path(torch, ctx):
+    """Row stride not a multiple of four floats, and a base address off the 16-byte grid."""
+    dep, ref = workloads.logits_pair(6, 3001, seed=11)
+    wide_d = torch.zeros((6, 3003), dtype=torch.float32, device="cuda")
+    wide_r = torch.zeros((6, 3003), dtype=torch.float32, device="cuda")
+    wide_d[:, 1:3002] = torch.from_numpy(dep).cuda()
+    wide_r[:, 1:3002] = torch.from_numpy(ref).cuda()
+    check_tv_kl(torch, ctx, dep, ref, dep_dev=wide_d[:, 1:3002], ref_dev=wide_r[:, 1:3002])
+
+
+def test_tv_kl_degenerate_rows(torch, ctx):
+    n = 2500
+    rng = np.random.default_rng(5)
+    base = (4 * rng.standard_normal(n)).astype(np.float32)
+    dep = np.stack([base, np.zeros(n, np.float32), base + 7.0, base, base * 8]).astype(np.float32)
+    ref = np.stack([base, np.zeros(n, np.float32), base, -base, base * 8 + 0.5 * (np.arange(n) % 2)]).astype(np.float32)
+    tv, kl, _ = check_tv_kl(torch, ctx, dep, ref)
+    assert tv[0] == 0.0 and tv[1] == 0.0          # identical inputs: identical arithmetic on both sides
+    assert abs(kl[0]) <= 1e-15 and abs(kl[1]) <= 1e-15
+    assert tv[2] <= 2 * E(n)                       # a common shift leaves the softmax unchanged
+
+
+def test_tv_kl_peaked_and_wide_range_logits(torch, ctx):
+    """One dominant entry (softmax nearly one-hot) and logits spanning +-80 (terms underflow)."""
+    n = 6000
+    rng = np.random.default_rng(8)
+    x = (20 * rng.standard_normal((3, n))).astype(np.float32)
+    y = x + (0.05 * rng.standard_normal((3, n))).astype(np.float32)
+    x[1, 17] = 200.0
+    y[1, 17] = 199.0
+    y[2, 5] = y[2].max() + 3.0                      # the reference prefers another token
+    check_tv_kl(torch, ctx, x, y)
+
+
+def test_tv_kl_full_size_sampled_rows(torch, ctx, full_size):
+    """Every row is computed, 50 sampled rows are compared with the oracle, the rest by invariants."""
+    dep, ref = full_size
+    steps, vocab = dep.shape
+    rows = sorted(np.random.default_rng(1).choice(steps, size=48, replace=False).tolist() + [0, steps - 1])
+    tv, kl, worst = check_tv_kl(torch, ctx, dep, ref, rows=rows)
+    assert np.isfinite(tv).all() and np.isfinite(kl).all()
+    assert (tv >= 0).all() and (tv <= 1).all() and (kl >= -E(vocab) * 3).all()
+    # Pinsker's inequality holds at any size (up to the error bound)
+    assert (tv <= np.sqrt(np.maximum(kl, 0) / 2) + 4 * E(vocab) + np.sqrt(6 * E(vocab))).all()
+    # tail density on the distances the GPU produced: an exact count
+    for t1 in (0.0, float(np.median(tv)), float(tv.max()), 1.0):
+        got = ctx.imm_tail_density(torch.from_numpy(tv).cuda(), t1)
+        assert got == oracle.tail_density(tv, t1)
+
+
+# ------------------------------------------------------------------ top-K distance
+def check_topk(torch, ctx, x: np.ndarray, idx: np.ndarray, rows=None, x_dev=None):
+    if x_dev is None:
+        x_dev = torch.from_numpy(x).cuda()
+    got = ctx.imm_topk_distance(x_dev, torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).cuda()).cpu().numpy()
+    for i in (range(x.shape[0]) if rows is None else rows):
+        want = oracle.topk_distance(x[i], idx[i])
+        assert abs(got[i] - want) <= 1e-12 * max(1.0, float(np.abs(x[i]).max())), (i, got[i], want)
+    return got
+
+
+def perturbed_sets(x: np.ndarray, K: int, seed: int) -> np.ndarray:
+    """Row r: the true top-K with r % (K+1) members swapped for random other indices."""
+    rng = np.random.default_rng(seed)
+    idx = workloads.topk_indices(x, K)
+    n = x.shape[1]
+    for r in range(x.shape[0]):
+        swaps = r % (K + 1)
+        others = np.setdiff1d(np.arange(n), idx[r])
+        if swaps and others.size:
+            swaps = min(swaps, others.size)
+            pos = rng.choice(K, size=swaps, replace=False)
+            idx[r, pos] = rng.choice(others, size=swaps, replace=False)
+    return idx
+
+
+@pytest.mark.parametrize("steps,vocab,K", [(4, 2, 1), (6, 7, 3), (6, 9, 5), (8, 65, 64), (8, 130, 64), (9, 1000, 20),
+                                           (9, 1024, 20), (7, 4099, 20), (5, 32000, 50), (4, 128256, 20),
+                                           (3, 128256, 64), (3, 128256, 1)])
+def test_topk_distance_matches_oracle(torch, ctx, steps, vocab, K):
+    dep, _ = workloads.logits_pair(steps, vocab, seed=7 * vocab + K)
+    idx = perturbed_sets(dep, K, seed=K)
+    got = check_topk(torch, ctx, dep, idx)
+    assert got[0] == 0.0                            # row 0 carries its true top-K
+
+
+def test_topk_distance_small_cases_against_brute_force(torch, ctx):
+    rng = np.random.default_rng(21)
+    for n, K in ((5, 2), (8, 3), (12, 6), (16, 5)):
+        x = rng.integers(-6, 7, size=(16, n)).astype(np.float32)      # many equal values
+        idx = np.stack([rng.choice(n, size=K, replace=False) for _ in range(16)]).astype(np.int32)
+        got = check_topk(torch, ctx, x, idx)
+        for i in range(16):
+            assert got[i] == oracle.topk_distance_bruteforce(x[i], idx[i])   # small integers: exact
+
+
+def test_topk_distance_ties_beyond_the_candidate_list(torch, ctx):
+    """More equal logits at the top than the in-LDS list holds: the exact slow path."""
+    n, K = 5000, 20
+    rng = np.random.default_rng(4)
+    x = np.zeros((4, n), dtype=np.float32)                       # row 0: all equal
+    x[1] = np.where(rng.random(n) < 0.6, 3.0, rng.standard_normal(n)).astype(np.float32)  # 3000 equal maxima
+    x[2] = np.floor(2 * rng.standard_normal(n)).astype(np.float32)                        # few distinct values
+    x[3] = x[2]
+    idx = np.stack([rng.choice(n, size=K, replace=False) for _ in range(4)]).astype(np.int32)
+    idx[3] = workloads.topk_indices(x[3:4], K)[0]
+    got = check_topk(torch, ctx, x, idx)
+    assert got[0] == 0.0 and got[3] == 0.0
+
+
+def test_topk_distance_unaligned_rows(torch, ctx):
+    dep, _ = workloads.logits_pair(5, 3001, seed=12)
+    wide = torch.zeros((5, 3003), dtype=torch.float32, device="cuda")
+    wide[:, 1:3002] = torch.from_numpy(dep).cuda()
+    check_topk(torch, ctx, dep, perturbed_sets(dep, 20, 1), x_dev=wide[:, 1:3002])
+
+
+def test_topk_distance_rejects_bad_index_sets(torch, ctx):
+    dep, _ = workloads.logits_pair(4, 500, seed=1)
+    idx = workloads.topk_indices(dep, 8)
+    idx[1, 3] = 500          # out of range
+    idx[2, 0] = -1           # negative
+    idx[3, 5] = idx[3, 2]    # repeated
+    got = ctx.imm_topk_distance(torch.from_numpy(dep).cuda(), torch.from_numpy(idx).cuda()).cpu().numpy()
+    assert got[0] == 0.0 and np.isnan(got[1:]).all()
+    x = torch.from_numpy(dep).cuda()
+    for K in (0, imm.IMM_TOPK_MAX + 1, 500):
+        with pytest.raises(imm.ImmError):
+            ctx.imm_topk_distance(x, torch.zeros((4, K), dtype=torch.int32, device="cuda"))
+
+
+def test_topk_distance_full_size_sampled_rows(torch, ctx, full_size):
+    dep, _ = full_size
+    (steps, vocab), K = dep.shape, 20
+    idx = perturbed_sets(dep, K, seed=9)
+    rows = sorted(np.random.default_rng(2).choice(steps, size=48, replace=False).tolist() + [0, steps - 1])
+    got = check_topk(torch, ctx, dep, idx, rows=rows)
+    assert np.isfinite(got).all() and (got >= 0).all()
+    unswapped = np.arange(steps) % (K + 1) == 0
+    assert (got[unswapped] == 0).all() and (got[~unswapped] > 0).all()
+
+
+def test_tail_density_counts_exactly(torch, ctx):
+    rng = np.random.default_rng(3)
+    for T in (1, 63, 1024, 100003, 3000000):
+        d = rng.random(T)
+        d[rng.integers(0, T, size=min(T, 50))] = 0.25        # values equal to the threshold are not counted
+        for t1 in (0.25, 0.9, -1.0, 2.0):
+            assert ctx.imm_tail_density(torch.from_numpy(d).cuda(), t1) == oracle.tail_density(d, t1)
+
+
+def test_ldd_kernels_are_profiled(torch, ctx):
+    dep, ref = workloads.logits_pair(8, 4096, seed=2)
+    d, r = torch.from_numpy(dep).cuda(), torch.from_numpy(ref).cuda()
+    idx = torch.from_numpy(workloads.topk_indices(dep, 20)).cuda()
+    ctx.imm_ctx_set_profiling((1 << imm.IMM_K_LDD) | (1 << imm.IMM_K_TOPK))
+    try:
+        ctx.imm_ctx_reset_profiling()
+        ctx.imm_ldd_tv_kl(d, r)
+        ctx.imm_topk_distance(d, idx)
+        torch.cuda.synchronize()
+        for kid in (imm.IMM_K_LDD, imm.IMM_K_TOPK):
+            launches, ms = ctx.imm_ctx_kernel_time(kid)
+            assert launches == 1 and ms > 0
+    finally:
+        ctx.imm_ctx_set_profiling(0)
