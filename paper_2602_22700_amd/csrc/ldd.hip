@@ -19,49 +19,62 @@ constexpr int kLddWaves = kLddBlock / 64;
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ double wave_sum_f64(double v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-    return v;
-}
-__device__ __forceinline__ float wave_max_f32(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_down(v, off, 64));
-    return v;
-}
-
-// Block-wide max / sum, result broadcast to every thread.  `lds` holds kLddWaves entries.
-__device__ __forceinline__ float block_max(float v, float* lds) {
-    v = wave_max_f32(v);
-    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
-    __syncthreads();
-    float r = lds[0];
-#pragma unroll
-    for (int w = 1; w < kLddWaves; ++w) r = fmaxf(r, lds[w]);
-    __syncthreads();
-    return r;
-}
-__device__ __forceinline__ double block_sum(double v, double* lds) {
-    v = wave_sum_f64(v);
-    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
-    __syncthreads();
-    double r = lds[0];
-#pragma unroll
-    for (int w = 1; w < kLddWaves; ++w) r += lds[w];
-    __syncthreads();
-    return r;
-}
-
 // ------------------------------------------------------------------ TV and KL
-// Pass 1 (HBM): row maxima.  Pass 2 (cache, reverse order): Z = sum e^(x-mx), Z' = sum e^(y-my)
-// and W = sum e^(x-mx) (x - y), which give KL = W/Z - (mx + log Z) + (my + log Z').
-// Pass 3 (cache): TV = 1/2 sum |e^(x-mx)/Z - e^(y-my)/Z'|.
+// A row pair of a 128k vocabulary is 1 MiB and a few hundred workgroups are resident at a time, so
+// with a workgroup per row far more than the caches hold is in flight, and every further pass over
+// a row comes from HBM again.  Here a row is cut into chunks of 16384 logits, one workgroup per
+// chunk, and a workgroup keeps its part of both rows in registers from the first load to the end,
+// so each logit is read from memory once:
 //
-// Arithmetic: e^d for d = x - mx <= 0 is the hardware base-2 exponential of d * log2(e), all in
-// fp32: relative error at most about 2^-24 (2.3 |d| + 4) per term (rounding of d, of the product,
-// of the constant, and of the exponential).  Four neighbouring terms are added in fp32, everything
-// beyond that is accumulated in fp64, so the error of a sum stays that of its terms.
+//   1. chunk maxima mx_c, my_c, then Z_c = sum e^(x - mx_c), Z'_c = sum e^(y - my_c) and
+//      W_c = sum e^(x - mx_c) (x - y), written to the slot of (row, chunk); the workgroup counts
+//      itself in on the row.
+//   2. merge, one chunk per lane: mx = max mx_c, Z = sum Z_c e^(mx_c - mx), likewise Z', W, and
+//      KL = W/Z - (mx + log Z) + (my + log Z').  For the KL that is returned this is done by a small
+//      second kernel, one wave per row; if only KL is wanted, steps 1 and 2 are all there is, and the
+//      first kernel is a plain streaming pass.
+//   3. if TV is wanted, the workgroup that counted in last on a row merges as well, right away, and
+//      posts mx, my, 1/Z, 1/Z' for the row; the other workgroups of the row wait for that post.  By
+//      then the registers hold e^(x - mx_c) and e^(y - my_c) in place of the logits, so a workgroup
+//      only scales them by alpha_c = e^(mx_c - mx)/Z and beta_c = e^(my_c - my)/Z' and sums
+//      |alpha_c e^(x - mx_c) - beta_c e^(y - my_c)|.  The parts of a row are added up as fixed-point
+//      numbers by one integer atomic add each (integer addition gives the same total in any order)
+//      that nobody waits for; the second kernel turns the total into TV and leaves counters, sums
+//      and posts as they were found, for the next call.
+//
+// The wait in step 3 is bounded.  The chunks of a row have neighbouring workgroup ids, the hardware
+// starts workgroups in id order, and none of them waits before it has counted in, so the post
+// normally arrives within microseconds.  A workgroup whose wait runs out stops depending on the
+// others: it works out the slots of all other chunks of its row itself and merges for itself (the
+// same arithmetic on the same data gives the same bits, so writing them again is harmless).  Every
+// workgroup therefore ends whatever the others do.
+//
+// Slots, counters and posts are written with agent-scope atomic stores (they go through to the
+// level all XCDs share) and read with agent-scope atomic loads; where order matters (slot before
+// count) the stores have completed before the count goes up.  The two words of a post need no
+// order: each is valid as soon as it differs from kNoPost.  No cache-wide write-back or invalidate
+// is involved, which is what a device-wide fence would cost here, tens of thousands of times per
+// launch.
+//
+// Arithmetic: e^d for d <= 0 is the hardware base-2 exponential of d * log2(e), all in fp32:
+// relative error at most about 2^-24 (2.3 |d| + 4) per term (rounding of d, of the product, of the
+// constant, and of the exponential).  Four neighbouring terms are added in fp32, everything beyond
+// that is accumulated in fp64, so the error of a sum stays that of its terms.  The factors
+// e^(mx_c - mx) of the merge come from the same fp32 exponential where the result feeds TV (the
+// fp64 library routine needs more registers than a workgroup that still holds its chunk can spare)
+// and from the fp64 routine where it feeds KL.
 constexpr float kLog2e = 1.44269504088896340736f;
+// Few threads with many registers each: what a CU holds of the rows while its workgroups wait for
+// their posts is what keeps HBM busy, and a thread's fixed register cost is paid once per thread.
+constexpr int kTvBlock = 256;
+constexpr int kTvWaves = kTvBlock / 64;
+constexpr int kPerThreadVec = 64;     // logits of each row held by a thread: aligned rows (16-byte loads) ..
+constexpr int kPerThreadScalar = 16;  // .. and the others (4-byte loads, one address each)
+constexpr int kTvWavesPerSimd = 3;    // register budget of the aligned kernels: 512 / 3 per thread
+constexpr float kAbsent = -3.402823466e38f;                 // stands in for positions past the row's end
+constexpr int kXcds = 8;
+constexpr uint64_t kNoPost = ~0ull;                         // two fp32 NaNs that no arithmetic here produces
+constexpr double kTvFixedOne = 4611686018427387904.0;       // 2^62
 
 __device__ __forceinline__ float exp_nonpos(float d) { return __builtin_amdgcn_exp2f(d * kLog2e); }
 
@@ -73,65 +86,309 @@ __device__ __forceinline__ float prob_gap(float ex, float izx, float ey, float i
     return fabsf(px - py);
 }
 
-template <bool VEC>
-__global__ __launch_bounds__(kLddBlock) void ldd_tv_kl_kernel(const float* __restrict__ X, const float* __restrict__ Y,
-                                                              uint64_t n, uint64_t ld, double* __restrict__ tv_out,
-                                                              double* __restrict__ kl_out) {
-    __shared__ float ldsf[kLddWaves];
-    __shared__ double ldsd[kLddWaves];
-    const float* x = X + (uint64_t)blockIdx.x * ld;
-    const float* y = Y + (uint64_t)blockIdx.x * ld;
-    const uint32_t tid = threadIdx.x;
-    const uint64_t n4 = VEC ? n >> 2 : 0;  // whole float4 groups
+// The thread's PER logits of the chunk of row x that starts at logit `first` and has `len`
+// (1 .. kTvBlock * PER) logits.  VEC (rows of a multiple of four logits, 16-byte aligned): groups of
+// four neighbours, groups kTvBlock apart; otherwise single logits kTvBlock apart.  Positions >= len
+// read as kAbsent.  Addresses are the row pointer plus a 32-bit byte offset (rows of at most 2^30
+// logits).  The loads are streaming: nobody reads the data again.
+template <bool VEC, int PER>
+__device__ __forceinline__ void load_chunk(const float* __restrict__ x, uint32_t first, uint32_t len, uint32_t tid,
+                                           float (&v)[PER]) {
+    const char* bytes = reinterpret_cast<const char*>(x);
+    if (VEC) {
+        if (len == kTvBlock * PER) {  // the same for the whole workgroup
+#pragma unroll
+            for (int j = 0; j < PER / 4; ++j) {
+                const uint32_t i = 4 * (tid + kTvBlock * j);
+                const v4f q = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(bytes + (first + i) * 4u));
+                v[4 * j] = q.x; v[4 * j + 1] = q.y; v[4 * j + 2] = q.z; v[4 * j + 3] = q.w;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < PER / 4; ++j) {
+                const uint32_t i = 4 * (tid + kTvBlock * j);
+                const bool ok = i < len;  // len is a multiple of four
+                const v4f q = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(bytes + (ok ? (first + i) * 4u : 0u)));
+                v[4 * j] = ok ? q.x : kAbsent; v[4 * j + 1] = ok ? q.y : kAbsent;
+                v[4 * j + 2] = ok ? q.z : kAbsent; v[4 * j + 3] = ok ? q.w : kAbsent;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const uint32_t i = tid + kTvBlock * j;
+            const bool ok = i < len;
+            const float t = __builtin_nontemporal_load(reinterpret_cast<const float*>(bytes + (ok ? (first + i) * 4u : 0u)));
+            v[j] = ok ? t : kAbsent;
+        }
+    }
+}
 
-    float mx = -INFINITY, my = -INFINITY;
-    for (uint64_t g = tid; g < n4; g += kLddBlock) {
-        v4f a = *reinterpret_cast<const v4f*>(x + 4 * g), b = *reinterpret_cast<const v4f*>(y + 4 * g);
-        mx = fmaxf(mx, fmaxf(fmaxf(a.x, a.y), fmaxf(a.z, a.w)));
-        my = fmaxf(my, fmaxf(fmaxf(b.x, b.y), fmaxf(b.z, b.w)));
-    }
-    for (uint64_t i = 4 * n4 + tid; i < n; i += kLddBlock) {
-        mx = fmaxf(mx, x[i]);
-        my = fmaxf(my, y[i]);
-    }
-    mx = block_max(mx, ldsf);
-    my = block_max(my, ldsf);
+__device__ __forceinline__ float wave_all_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+__device__ __forceinline__ double wave_all_sum(double v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
 
-    double zx = 0, zy = 0, w = 0;
-    for (uint64_t i = 4 * n4 + tid; i < n; i += kLddBlock) {
-        const float ex = exp_nonpos(x[i] - mx), ey = exp_nonpos(y[i] - my);
-        zx += ex; zy += ey; w += ex * (x[i] - y[i]);
-    }
-    for (uint64_t k = tid; k < n4; k += kLddBlock) {
-        const uint64_t g = n4 - 1 - k;  // most recently read groups first
-        v4f a = *reinterpret_cast<const v4f*>(x + 4 * g), b = *reinterpret_cast<const v4f*>(y + 4 * g);
+// One slot per (row, chunk), 32 bytes: zx, zy, w as fp64 bit patterns, mx | my << 32 as fp32 bit patterns.
+constexpr int kSlotWords = 4;
+// One post per row: mx | my << 32, then 1/Z | 1/Z' << 32, fp32 bit patterns; kNoPost when empty.
+constexpr int kPostWords = 2;
+
+__device__ __forceinline__ void put(uint64_t* p, uint64_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t peek(const uint64_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t bits(double v) { return (uint64_t)__double_as_longlong(v); }
+__device__ __forceinline__ double real(uint64_t v) { return __longlong_as_double((long long)v); }
+__device__ __forceinline__ uint64_t pair(float lo, float hi) {
+    const uint64_t v = (uint64_t)__float_as_uint(lo) | ((uint64_t)__float_as_uint(hi) << 32);
+    return v == kNoPost ? v - 1 : v;  // still two NaNs
+}
+__device__ __forceinline__ float lo_of(uint64_t v) { return __uint_as_float((uint32_t)v); }
+__device__ __forceinline__ float hi_of(uint64_t v) { return __uint_as_float((uint32_t)(v >> 32)); }
+
+// All stores of this thread so far have completed; then the count goes up.  Returns the old count.
+__device__ __forceinline__ uint32_t count_in(uint32_t* counter) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+    return __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct TvShared {
+    float wave_max[kTvWaves][2];
+    double wave_sum[kTvWaves][3];
+    uint64_t post[kPostWords];
+};
+
+// Step 1 for the chunk held in (a, b): every thread returns the chunk maxima, wave 0 returns the
+// three sums in all its lanes, and with KEEP a, b are left holding e^(a - mx), e^(b - my).  Groups
+// of four neighbouring terms are added in fp32; from there on the sums are fp64.  Two barriers.
+template <bool KEEP, int PER>
+__device__ __forceinline__ void chunk_stats(float (&a)[PER], float (&b)[PER], TvShared& sh, uint32_t lane, uint32_t wave,
+                                            float& mx, float& my, double& zx, double& zy, double& w) {
+    mx = a[0]; my = b[0];
+#pragma unroll
+    for (int j = 1; j < PER; ++j) { mx = fmaxf(mx, a[j]); my = fmaxf(my, b[j]); }
+    mx = wave_all_max(mx);
+    my = wave_all_max(my);
+    if (lane == 0) { sh.wave_max[wave][0] = mx; sh.wave_max[wave][1] = my; }
+    __syncthreads();
+#pragma unroll
+    for (int v = 0; v < kTvWaves; ++v) { mx = fmaxf(mx, sh.wave_max[v][0]); my = fmaxf(my, sh.wave_max[v][1]); }
+    zx = 0; zy = 0; w = 0;
+#pragma unroll
+    for (int j = 0; j < PER; j += 4) {
         float sx = 0.f, sy = 0.f, sw = 0.f;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float ex = exp_nonpos(a[j] - mx), ey = exp_nonpos(b[j] - my);
-            sx += ex; sy += ey; sw += ex * (a[j] - b[j]);
+        for (int c = 0; c < 4; ++c) {
+            const float ex = exp_nonpos(a[j + c] - mx), ey = exp_nonpos(b[j + c] - my);
+            sx += ex; sy += ey; sw += ex * (a[j + c] - b[j + c]);   // absent positions: 0 * 0
+            if (KEEP) { a[j + c] = ex; b[j + c] = ey; }
         }
         zx += sx; zy += sy; w += sw;
     }
-    zx = block_sum(zx, ldsd);
-    zy = block_sum(zy, ldsd);
-    w = block_sum(w, ldsd);
-    if (tid == 0 && kl_out) kl_out[blockIdx.x] = w / zx - ((double)mx + log(zx)) + ((double)my + log(zy));
-    if (!tv_out) return;
+    zx = wave_all_sum(zx);
+    zy = wave_all_sum(zy);
+    w = wave_all_sum(w);
+    if (lane == 0) { sh.wave_sum[wave][0] = zx; sh.wave_sum[wave][1] = zy; sh.wave_sum[wave][2] = w; }
+    __syncthreads();
+    if (wave == 0) {
+        const uint32_t src = lane < kTvWaves ? lane : 0;
+        const double keep = lane < kTvWaves ? 1.0 : 0.0;
+        zx = wave_all_sum(keep * sh.wave_sum[src][0]);
+        zy = wave_all_sum(keep * sh.wave_sum[src][1]);
+        w = wave_all_sum(keep * sh.wave_sum[src][2]);
+    }
+}
 
-    const float izx = (float)(1.0 / zx), izy = (float)(1.0 / zy);
+__device__ __forceinline__ void put_stats(uint64_t* slot, float mx, float my, double zx, double zy, double w) {
+    put(slot + 0, bits(zx));
+    put(slot + 1, bits(zy));
+    put(slot + 2, bits(w));
+    put(slot + 3, pair(mx, my));
+}
+
+// Step 2, by one wave: lane c takes chunk c (then c + 64, ... for rows of more than 64 chunks, merging
+// as it goes), then the lanes merge.  All loads of a chunk's slot are issued together.  EXACT takes the
+// factors e^(mx_c - mx) from the fp64 library exponential, otherwise from the fp32 one.
+template <bool EXACT>
+__device__ __forceinline__ double merge_factor(float d) {
+    return EXACT ? exp((double)d) : (double)exp_nonpos(d);
+}
+template <bool EXACT>
+__device__ __forceinline__ void merge_row(const uint64_t* slots, uint32_t S, uint32_t lane, float& gx, float& gy,
+                                          double& Zx, double& Zy, double& W) {
+    float lx = -INFINITY, ly = -INFINITY;
+    double zx = 0, zy = 0, w = 0;
+    for (uint32_t c = lane; c < S; c += 64) {
+        const uint64_t m = peek(slots + c * kSlotWords + 3);
+        const double cx = real(peek(slots + c * kSlotWords + 0));
+        const double cy = real(peek(slots + c * kSlotWords + 1));
+        const double cw = real(peek(slots + c * kSlotWords + 2));
+        const float nx = fmaxf(lx, lo_of(m)), ny = fmaxf(ly, hi_of(m));
+        const double ox = merge_factor<EXACT>(lx - nx), oy = merge_factor<EXACT>(ly - ny);  // e^(-inf) = 0 at first
+        const double fx = merge_factor<EXACT>(lo_of(m) - nx), fy = merge_factor<EXACT>(hi_of(m) - ny);
+        zx = zx * ox + cx * fx;
+        w = w * ox + cw * fx;
+        zy = zy * oy + cy * fy;
+        lx = nx; ly = ny;
+    }
+    gx = wave_all_max(lx);
+    gy = wave_all_max(ly);
+    const double fx = merge_factor<EXACT>(lx - gx), fy = merge_factor<EXACT>(ly - gy);  // lanes without a chunk: 0
+    Zx = wave_all_sum(zx * fx);
+    Zy = wave_all_sum(zy * fy);
+    W = wave_all_sum(w * fx);
+}
+
+template <bool VEC, bool WANT_TV>
+__global__ __launch_bounds__(kTvBlock, VEC ? kTvWavesPerSimd : 4) void ldd_tv_kl_kernel(
+    const float* __restrict__ X, const float* __restrict__ Y, uint32_t T, uint32_t n, uint64_t ld, uint32_t S,
+    uint64_t* slots_all, uint64_t* posts, uint64_t* sums, uint32_t* counters, uint64_t wait_polls) {
+    constexpr int PER = VEC ? kPerThreadVec : kPerThreadScalar;
+    constexpr uint32_t kChunk = kTvBlock * PER;  // logits of a row per workgroup
+    __shared__ TvShared sh;
+    // Consecutive workgroup ids go round the XCDs: id % 8 names the XCD, and within an XCD the ids
+    // walk through the chunks of one row before they move on to the next.
+    const uint32_t xcd = blockIdx.x % kXcds, slot_in_xcd = blockIdx.x / kXcds;
+    const uint32_t row = (slot_in_xcd / S) * kXcds + xcd, chunk = slot_in_xcd % S;
+    if (row >= T) return;  // the whole workgroup: T need not be a multiple of 8
+    const float* x = X + (uint64_t)row * ld;
+    const float* y = Y + (uint64_t)row * ld;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint64_t* slots = slots_all + (uint64_t)row * S * kSlotWords;
+    auto chunk_len = [&](uint32_t c) { return n - c * kChunk < kChunk ? n - c * kChunk : kChunk; };
+
+    // ---- step 1
+    float a[PER], b[PER], mx, my;
+    double zx, zy, w;
+    load_chunk<VEC>(x, chunk * kChunk, chunk_len(chunk), tid, a);
+    load_chunk<VEC>(y, chunk * kChunk, chunk_len(chunk), tid, b);
+    chunk_stats<WANT_TV>(a, b, sh, lane, wave, mx, my, zx, zy, w);
+
+    if (!WANT_TV) {  // KL only: the slot is all the finishing kernel needs
+        if (tid == 0) put_stats(slots + chunk * kSlotWords, mx, my, zx, zy, w);
+        return;
+    }
+
+    // ---- steps 2 and 3: count in; the last one merges and posts, the others wait (bounded) for the post
+    uint64_t* post = posts + (uint64_t)row * kPostWords;
+    float rmx = mx, rmy = my;  // the maxima that a, b refer to
+    if (wave == 0) {
+        uint32_t before = 0;
+        if (lane == 0) {
+            put_stats(slots + chunk * kSlotWords, mx, my, zx, zy, w);
+            before = count_in(counters + row);
+        }
+        before = __shfl(before, 0, 64);
+        uint64_t p0 = kNoPost, p1 = kNoPost;
+        if (before == S - 1) {
+            float gx, gy;
+            double Zx, Zy, W;
+            merge_row<false>(slots, S, lane, gx, gy, Zx, Zy, W);
+            p0 = pair(gx, gy);
+            p1 = pair(1.0f / (float)Zx, 1.0f / (float)Zy);
+            if (lane == 0) { put(post + 0, p0); put(post + 1, p1); }
+        } else if (lane == 0) {
+            for (uint64_t polls = 0; polls < wait_polls; ++polls) {
+                p0 = peek(post + 0);
+                p1 = peek(post + 1);
+                if (p0 != kNoPost && p1 != kNoPost) break;
+                __builtin_amdgcn_s_sleep(8);
+            }
+        }
+        if (lane == 0) { sh.post[0] = p0; sh.post[1] = p1; }
+    }
+    __syncthreads();
+    if (sh.post[0] == kNoPost || sh.post[1] == kNoPost) {  // the wait ran out: do without the others
+        __syncthreads();  // everybody has read sh.post
+        for (uint32_t c = 0; c < S; ++c) {
+            if (c == chunk) continue;
+            load_chunk<VEC>(x, c * kChunk, chunk_len(c), tid, a);
+            load_chunk<VEC>(y, c * kChunk, chunk_len(c), tid, b);
+            chunk_stats<false>(a, b, sh, lane, wave, mx, my, zx, zy, w);
+            if (tid == 0) put_stats(slots + c * kSlotWords, mx, my, zx, zy, w);
+        }
+        if (wave == 0) {
+            if (lane == 0) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_s_waitcnt(0);
+            }
+            __builtin_amdgcn_wave_barrier();
+            float gx, gy;
+            double Zx, Zy, W;
+            merge_row<false>(slots, S, lane, gx, gy, Zx, Zy, W);
+            if (lane == 0) {
+                sh.post[0] = pair(gx, gy);
+                sh.post[1] = pair(1.0f / (float)Zx, 1.0f / (float)Zy);
+            }
+        }
+        load_chunk<VEC>(x, chunk * kChunk, chunk_len(chunk), tid, a);
+        load_chunk<VEC>(y, chunk * kChunk, chunk_len(chunk), tid, b);
+        chunk_stats<true>(a, b, sh, lane, wave, rmx, rmy, zx, zy, w);  // its barriers come after the write of sh.post
+    }
+    const float alpha = exp_nonpos(rmx - lo_of(sh.post[0])) * lo_of(sh.post[1]);
+    const float beta = exp_nonpos(rmy - hi_of(sh.post[0])) * hi_of(sh.post[1]);
     double tv = 0;
-    for (uint64_t g = tid; g < n4; g += kLddBlock) {
-        v4f a = *reinterpret_cast<const v4f*>(x + 4 * g), b = *reinterpret_cast<const v4f*>(y + 4 * g);
+#pragma unroll
+    for (int j = 0; j < PER; j += 4) {
         float st = 0.f;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) st += prob_gap(exp_nonpos(a[j] - mx), izx, exp_nonpos(b[j] - my), izy);
+        for (int c = 0; c < 4; ++c) st += prob_gap(a[j + c], alpha, b[j + c], beta);
         tv += st;
     }
-    for (uint64_t i = 4 * n4 + tid; i < n; i += kLddBlock)
-        tv += prob_gap(exp_nonpos(x[i] - mx), izx, exp_nonpos(y[i] - my), izy);
-    tv = block_sum(tv, ldsd);
-    if (tid == 0) tv_out[blockIdx.x] = 0.5 * tv;
+    tv = wave_all_sum(tv);
+    if (lane == 0) sh.wave_sum[wave][0] = tv;   // everybody is past the reads of wave_sum in chunk_stats
+    __syncthreads();
+    if (wave == 0) {
+        tv = wave_all_sum(lane < kTvWaves ? sh.wave_sum[lane < kTvWaves ? lane : 0][0] : 0.0);
+        // The part, at most 1, goes onto the row's sum as a fixed-point number with 62 fraction bits.
+        // Nobody here needs the result, so the workgroup does not wait for it.
+        if (lane == 0)
+            (void)__hip_atomic_fetch_add(sums + row, (uint64_t)__double2ll_rn(tv * kTvFixedOne), __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// The end of a row, one wave per row, after the kernel above has ended: KL from the slots (step 2
+// with the fp64 factors), TV from the fixed-point sum, and posts, sums and counters back to the
+// state they were found in, for the next call.
+__global__ __launch_bounds__(256) void ldd_finish_kernel(uint32_t T, uint32_t S, const uint64_t* slots_all,
+                                                         uint64_t* posts, uint64_t* sums, uint32_t* counters,
+                                                         double* __restrict__ tv_out, double* __restrict__ kl_out) {
+    const uint32_t row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (row >= T) return;
+    if (kl_out) {
+        float gx, gy;
+        double Zx, Zy, W;
+        merge_row<true>(slots_all + (uint64_t)row * S * kSlotWords, S, lane, gx, gy, Zx, Zy, W);
+        if (lane == 0) kl_out[row] = W / Zx - ((double)gx + log(Zx)) + ((double)gy + log(Zy));
+    }
+    if (tv_out && lane == 0) {
+        tv_out[row] = 0.5 * ((double)peek(sums + row) / kTvFixedOne);
+        put(sums + row, 0);
+        put(posts + (uint64_t)row * kPostWords, kNoPost);
+        put(posts + (uint64_t)row * kPostWords + 1, kNoPost);
+        __hip_atomic_store(counters + row, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+__global__ void fill_u64_kernel(uint64_t* p, uint64_t count, uint64_t v) {
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = v;
+}
+
+__global__ void fill_u32_kernel(uint32_t* p, uint64_t count, uint32_t v) {
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = v;
 }
 
 // ------------------------------------------------------------------ top-K distance
@@ -166,6 +423,8 @@ __global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* _
     __shared__ float top_out[IMM_TOPK_MAX];  // K largest non-members
     __shared__ Cand cand[kTopkCap];
     __shared__ unsigned char cand_member[kTopkCap];
+    __shared__ unsigned short hot[kLddBlock];  // threads whose share reaches tau
+    __shared__ int hot_count;
     __shared__ int cand_count;
     __shared__ int bad_row;
     __shared__ double cost[2 * IMM_TOPK_MAX];
@@ -176,7 +435,7 @@ __global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* _
     // a row with fewer than 2K entries has fewer than K non-members: then every entry is accounted for
     const uint32_t Kn = (n - K < K) ? (uint32_t)(n - K) : K;
 
-    if (tid == 0) { cand_count = 0; bad_row = 0; }
+    if (tid == 0) { cand_count = 0; hot_count = 0; bad_row = 0; }
     __syncthreads();
     if (tid < K) {
         const int id = idx[tid];
@@ -193,11 +452,21 @@ __global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* _
         for (uint32_t j = 0; j < tid; ++j)
             if (member_idx[j] == member_idx[tid]) bad_row = 1;
 
-    // pass 1 (HBM): maximum of the thread's share
+    // pass 1 (HBM): maximum of the thread's share, eight loads in flight per thread
     float tmax = -INFINITY;
-    for (uint64_t g = tid; g < n4; g += kLddBlock) {
-        v4f a = *reinterpret_cast<const v4f*>(x + 4 * g);
-        tmax = fmaxf(tmax, fmaxf(fmaxf(a.x, a.y), fmaxf(a.z, a.w)));
+    uint64_t g = tid;
+    for (; g + 7 * (uint64_t)kLddBlock < n4; g += 8 * (uint64_t)kLddBlock) {
+        v4f q[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            q[j] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(x + 4 * (g + (uint64_t)kLddBlock * j)));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) tmax = fmaxf(tmax, fmaxf(fmaxf(q[j].x, q[j].y), fmaxf(q[j].z, q[j].w)));
+    }
+    for (; g < n4; g += kLddBlock) {
+        const v4f q = *reinterpret_cast<const v4f*>(x + 4 * g);
+        tmax = fmaxf(tmax, fmaxf(fmaxf(q.x, q.y), fmaxf(q.z, q.w)));
     }
     for (uint64_t i = 4 * n4 + tid; i < n; i += kLddBlock) tmax = fmaxf(tmax, x[i]);
 
@@ -221,22 +490,43 @@ __global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* _
 #pragma unroll
     for (int w = 1; w < kLddWaves; ++w) tau = fminf(tau, ldsf[w]);
 
-    // pass 2 (cache): threads that can hold a candidate append every logit >= tau of their share
-    if (tmax >= tau) {
-        for (uint64_t g = tid; g < n4; g += kLddBlock) {
-            v4f a = *reinterpret_cast<const v4f*>(x + 4 * g);
+    // pass 2: only threads whose maximum reaches tau can own a logit >= tau.  They put their names on
+    // a list, and the whole workgroup goes through the shares of the listed threads together, one
+    // (owner, position) pair per thread at a time, so the re-read costs one round trip, not one per
+    // position of a share.
+    if (tmax >= tau) hot[atomicAdd(&hot_count, 1)] = (unsigned short)tid;
+    __syncthreads();
+    if constexpr (VEC) {
+        const uint64_t per_owner = (n4 + kLddBlock - 1) / kLddBlock;
+        const uint64_t items = (uint64_t)hot_count * per_owner;
+        for (uint64_t w = tid; w < items; w += kLddBlock) {
+            const uint64_t u = hot[w / per_owner] + (uint64_t)kLddBlock * (w % per_owner);
+            if (u >= n4) continue;
+            const v4f q = *reinterpret_cast<const v4f*>(x + 4 * u);
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (a[j] >= tau) {
+                if (q[j] >= tau) {
                     const int slot = atomicAdd(&cand_count, 1);
-                    if (slot < kTopkCap) { cand[slot].v = a[j]; cand[slot].idx = (int)(4 * g + j); }
+                    if (slot < kTopkCap) { cand[slot].v = q[j]; cand[slot].idx = (int)(4 * u + j); }
                 }
         }
-        for (uint64_t i = 4 * n4 + tid; i < n; i += kLddBlock)
-            if (x[i] >= tau) {
+        const uint64_t i = 4 * n4 + tid;  // the up to three logits after the last whole group
+        if (i < n && x[i] >= tau) {
+            const int slot = atomicAdd(&cand_count, 1);
+            if (slot < kTopkCap) { cand[slot].v = x[i]; cand[slot].idx = (int)i; }
+        }
+    } else {
+        const uint64_t per_owner = (n + kLddBlock - 1) / kLddBlock;
+        const uint64_t items = (uint64_t)hot_count * per_owner;
+        for (uint64_t w = tid; w < items; w += kLddBlock) {
+            const uint64_t i = hot[w / per_owner] + (uint64_t)kLddBlock * (w % per_owner);
+            if (i >= n) continue;
+            const float v = x[i];
+            if (v >= tau) {
                 const int slot = atomicAdd(&cand_count, 1);
-                if (slot < kTopkCap) { cand[slot].v = x[i]; cand[slot].idx = (int)i; }
+                if (slot < kTopkCap) { cand[slot].v = v; cand[slot].idx = (int)i; }
             }
+        }
     }
     __syncthreads();
     const int c = cand_count;
@@ -248,15 +538,21 @@ __global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* _
             cand_member[i] = is_member ? 1 : 0;
         }
         __syncthreads();
-        // rank of every non-member candidate among the non-member candidates; ranks < Kn are the answer
-        for (int i = tid; i < c; i += kLddBlock) {
-            if (cand_member[i]) continue;
-            const float v = cand[i].v;
-            const int id = cand[i].idx;
+        // Rank of every non-member candidate among the non-member candidates; ranks < Kn are the answer.
+        // `per` neighbouring lanes share the comparisons of one candidate.
+        uint32_t per = 1;
+        while (per < 64 && 2 * per * (uint32_t)c <= (uint32_t)kLddBlock) per *= 2;
+        for (uint32_t base = 0; base < (uint32_t)c; base += kLddBlock / per) {
+            const uint32_t i = base + tid / per, sub = tid % per;
+            const bool mine = i < (uint32_t)c && !cand_member[i];
+            const float v = mine ? cand[i].v : 0.f;
+            const int id = mine ? cand[i].idx : 0;
             uint32_t rank = 0;
-            for (int j = 0; j < c; ++j)
-                rank += (!cand_member[j] && cand_before(cand[j].v, cand[j].idx, v, id)) ? 1u : 0u;
-            if (rank < Kn) top_out[rank] = v;
+            if (mine)
+                for (uint32_t j = sub; j < (uint32_t)c; j += per)
+                    rank += (!cand_member[j] && cand_before(cand[j].v, cand[j].idx, v, id)) ? 1u : 0u;
+            for (uint32_t off = per >> 1; off > 0; off >>= 1) rank += __shfl_xor(rank, off, 64);
+            if (mine && sub == 0 && rank < Kn) top_out[rank] = v;
         }
     } else {
         // More logits tie at (or crowd above) tau than the list holds: exact but slow path, K rounds
@@ -330,20 +626,48 @@ bool vec_ok(const void* p, uint64_t ld) { return reinterpret_cast<uintptr_t>(p) 
 
 }  // namespace
 
+uint32_t ldd_chunks(uint64_t n, bool vec) {
+    const uint64_t chunk = (uint64_t)kTvBlock * (vec ? kPerThreadVec : kPerThreadScalar);
+    return (uint32_t)((n + chunk - 1) / chunk);
+}
+size_t ldd_slot_bytes(uint64_t T, uint64_t n) { return (size_t)T * ldd_chunks(n, false) * kSlotWords * sizeof(uint64_t); }
+size_t ldd_post_bytes(uint64_t T) { return (size_t)T * kPostWords * sizeof(uint64_t); }
+size_t ldd_sum_bytes(uint64_t T) { return (size_t)T * sizeof(uint64_t); }
+size_t ldd_counter_bytes(uint64_t T) { return (size_t)T * sizeof(uint32_t); }
+
+hipError_t ldd_init_sync(hipStream_t stream, uint64_t* posts, size_t post_bytes, uint64_t* sums, size_t sum_bytes,
+                         uint32_t* counters, size_t counter_bytes) {
+    const uint64_t np = post_bytes / sizeof(uint64_t), ns = sum_bytes / sizeof(uint64_t),
+                   nc = counter_bytes / sizeof(uint32_t);
+    hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, stream, posts, np, kNoPost);
+    hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)((ns + 255) / 256)), dim3(256), 0, stream, sums, ns, 0ull);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((nc + 255) / 256)), dim3(256), 0, stream, counters, nc, 0u);
+    return hipGetLastError();
+}
+
 hipError_t ldd_tv_kl(hipStream_t stream, const float* X, const float* Y, uint64_t T, uint64_t n, uint64_t ld,
+                     uint64_t* slots, uint64_t* posts, uint64_t* sums, uint32_t* counters, uint64_t wait_polls,
                      double* tv_out, double* kl_out) {
-    if (vec_ok(X, ld) && vec_ok(Y, ld))
-        hipLaunchKernelGGL((ldd_tv_kl_kernel<true>), dim3((unsigned)T), dim3(kLddBlock), 0, stream, X, Y, n, ld, tv_out,
-                           kl_out);
-    else
-        hipLaunchKernelGGL((ldd_tv_kl_kernel<false>), dim3((unsigned)T), dim3(kLddBlock), 0, stream, X, Y, n, ld,
-                           tv_out, kl_out);
+    const bool vec = n % 4 == 0 && vec_ok(X, ld) && vec_ok(Y, ld);
+    const uint32_t S = ldd_chunks(n, vec);
+    const uint64_t blocks = (T + kXcds - 1) / kXcds * kXcds * S;
+    if (blocks > 0x7FFFFFFFull || n > (1ull << 30)) return hipErrorInvalidValue;
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kTvBlock), 0, stream, X, Y, (uint32_t)T, (uint32_t)n, ld,
+                           S, slots, posts, sums, counters, wait_polls);
+    };
+    if (vec && tv_out) launch(ldd_tv_kl_kernel<true, true>);
+    else if (vec) launch(ldd_tv_kl_kernel<true, false>);
+    else if (tv_out) launch(ldd_tv_kl_kernel<false, true>);
+    else launch(ldd_tv_kl_kernel<false, false>);
+    hipLaunchKernelGGL(ldd_finish_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, stream, (uint32_t)T, S, slots,
+                       posts, sums, counters, tv_out, kl_out);
     return hipGetLastError();
 }
 
 hipError_t topk_distance(hipStream_t stream, const float* X, uint64_t T, uint64_t n, uint64_t ld, const int32_t* idx,
                          uint32_t K, double* out) {
-    if (vec_ok(X, ld))
+    if (n >= 4 && vec_ok(X, ld))
         hipLaunchKernelGGL((topk_distance_kernel<true>), dim3((unsigned)T), dim3(kLddBlock), 0, stream, X, n, ld, idx, K,
                            out);
     else

@@ -117,7 +117,8 @@ struct Profiler {
 
 struct imm_ctx {
     int device = 0;
-    imm::DevBuf encA, encB, eqx, eqy, a, b, partA, partB, round_scratch, words, snapA, snapB, group_tables;
+    imm::DevBuf encA, encB, eqx, eqy, a, b, partA, partB, round_scratch, words, snapA, snapB, group_tables,
+        ldd_partial, ldd_post, ldd_sum, ldd_arrive;
     uint64_t* pinned = nullptr;  // host staging, 4 KiB
     imm::k::Mailbox* mailbox = nullptr;  // pinned + coherent, kRoundsMaxJobs of them: g_k out, r_k in
     int transcript_mode = IMM_TRANSCRIPT_HOST;
@@ -575,7 +576,8 @@ extern "C" int imm_ctx_destroy(imm_ctx* ctx) {
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
     for (DevBuf* bf : {&ctx->encA, &ctx->encB, &ctx->eqx, &ctx->eqy, &ctx->a, &ctx->b, &ctx->partA, &ctx->partB,
-                       &ctx->round_scratch, &ctx->words, &ctx->snapA, &ctx->snapB, &ctx->group_tables})
+                       &ctx->round_scratch, &ctx->words, &ctx->snapA, &ctx->snapB, &ctx->group_tables,
+                       &ctx->ldd_partial, &ctx->ldd_post, &ctx->ldd_sum, &ctx->ldd_arrive})
         bf->release();
     ctx->prof.destroy();
     if (ctx->pinned) (void)hipHostFree(ctx->pinned);
@@ -775,12 +777,24 @@ extern "C" int imm_debug_fetch(imm_ctx* ctx, int which, uint64_t* out_host, uint
 extern "C" int imm_ldd_tv_kl(imm_ctx* ctx, void* stream, const float* logits_dev, const float* ref_dev, uint64_t T,
                              uint64_t n, uint64_t ld, double* tv_out_dev, double* kl_out_dev) {
     if (!ctx || !logits_dev || !ref_dev || (!tv_out_dev && !kl_out_dev)) return IMM_E_NULL;
-    if (T == 0 || n == 0 || ld < n || T > 0x7FFFFFFFull) return IMM_E_SHAPE;
+    if (T == 0 || n == 0 || ld < n || T > 0x7FFFFFFFull || n > (1ull << 30)) return IMM_E_SHAPE;
     IMM_HIP(hipSetDevice(ctx->device));
     hipStream_t s = static_cast<hipStream_t>(stream);
     int rc;
+    if ((rc = ctx->ldd_partial.ensure(k::ldd_slot_bytes(T, n)))) return rc;
+    if (ctx->ldd_post.bytes < k::ldd_post_bytes(T) || ctx->ldd_sum.bytes < k::ldd_sum_bytes(T) ||
+        ctx->ldd_arrive.bytes < k::ldd_counter_bytes(T)) {
+        if ((rc = ctx->ldd_post.ensure(k::ldd_post_bytes(T)))) return rc;
+        if ((rc = ctx->ldd_sum.ensure(k::ldd_sum_bytes(T)))) return rc;
+        if ((rc = ctx->ldd_arrive.ensure(k::ldd_counter_bytes(T)))) return rc;
+        IMM_HIP(k::ldd_init_sync(s, ctx->ldd_post.u64(), ctx->ldd_post.bytes, ctx->ldd_sum.u64(), ctx->ldd_sum.bytes,
+                                 static_cast<uint32_t*>(ctx->ldd_arrive.p), ctx->ldd_arrive.bytes));
+    }
+    // a workgroup whose wait runs out finishes on its own, so the bound can be short: about 50 ms
+    const uint64_t wait_polls = ctx->spin_limit < (1ull << 15) ? ctx->spin_limit : (1ull << 15);
     if ((rc = ctx->prof.begin(IMM_K_LDD, s))) return rc;
-    IMM_HIP(k::ldd_tv_kl(s, logits_dev, ref_dev, T, n, ld, tv_out_dev, kl_out_dev));
+    IMM_HIP(k::ldd_tv_kl(s, logits_dev, ref_dev, T, n, ld, ctx->ldd_partial.u64(), ctx->ldd_post.u64(),
+                         ctx->ldd_sum.u64(), static_cast<uint32_t*>(ctx->ldd_arrive.p), wait_polls, tv_out_dev, kl_out_dev));
     return ctx->prof.end(IMM_K_LDD, s);
 }
 
