@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fold-log2", type=int, default=26,
                     help="log2 of the table length of the stand-alone fold-kernel measurement (0 = skip)")
+    ap.add_argument("--ldd-steps", type=int, default=2048,
+                    help="decision steps of the logit-distance measurement (vocabulary 128256, K = 20); 0 skips it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy three times (reference dispatches for scaling "
                          "hardware byte counters collected with rocprofv3 --pmc)")
@@ -237,6 +239,53 @@ def main():
                                               "frac_of_8TBps": round(24 * Lf / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 3)}
         ctx.imm_ctx_reset_profiling()
         del ta, tb
+
+    # The logit-distance step of the audit on the logits of `ldd_steps` decision steps over a
+    # 128256-entry vocabulary: TV and KL of the two softmax rows (8 B per vocabulary entry: one fp32
+    # logit of each model) and the top-K distance of the deployed row (4 B per entry), K = 20.
+    if args.ldd_steps > 0:
+        Tl, nl, Kl = args.ldd_steps, 128256, 20
+        dep_h, ref_h = workloads.logits_pair(Tl, nl, seed=2025)
+        idx_h = workloads.topk_indices(dep_h, Kl)
+        dep_d, ref_d, idx_d = torch.from_numpy(dep_h).cuda(), torch.from_numpy(ref_h).cuda(), torch.from_numpy(idx_h).cuda()
+
+        def timed(kid, fn, reps=20):
+            for _ in range(3):
+                fn()
+            ctx.imm_ctx_reset_profiling()
+            ctx.imm_ctx_set_profiling(1 << kid)
+            for _ in range(reps):
+                fn()
+            ctx.imm_ctx_set_profiling(0)
+            nk, msk = ctx.imm_ctx_kernel_time(kid)
+            ctx.imm_ctx_reset_profiling()
+            return msk * 1e3 / nk
+
+        def line(us, nbytes):
+            return {"us_per_launch": round(us, 1), "algorithmic_MB": nbytes / 1e6,
+                    "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
+                    "frac_of_8TBps": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 3)}
+
+        ldd = {"steps": Tl, "vocab": nl, "K": Kl, "dtype": "f32 logits, f64 sums"}
+        ldd["tv_and_kl"] = line(timed(imm.IMM_K_LDD, lambda: ctx.imm_ldd_tv_kl(dep_d, ref_d)), 8 * Tl * nl)
+        ldd["kl_only"] = line(timed(imm.IMM_K_LDD, lambda: ctx.imm_ldd_tv_kl(dep_d, ref_d, want_tv=False)), 8 * Tl * nl)
+        ldd["topk_distance"] = line(timed(imm.IMM_K_TOPK, lambda: ctx.imm_topk_distance(dep_d, idx_d)), 4 * Tl * nl)
+        if not args.no_cpu_baseline:
+            from oracle import ldd as oracle_ldd
+            rows = list(range(0, Tl, max(1, Tl // 16)))[:16]
+            t0 = time.perf_counter()
+            for i in rows:
+                oracle_ldd.tv_distance(dep_h[i], ref_h[i])
+                oracle_ldd.kl_divergence(dep_h[i], ref_h[i])
+            t1 = time.perf_counter()
+            for i in rows:
+                oracle_ldd.topk_distance(dep_h[i], idx_h[i])
+            t2 = time.perf_counter()
+            ldd["cpu_oracle"] = {"tv_and_kl_ms_per_step": round((t1 - t0) * 1e3 / len(rows), 2),
+                                 "topk_ms_per_step": round((t2 - t1) * 1e3 / len(rows), 2), "cores": 1,
+                                 "sample": "%d of the %d steps" % (len(rows), Tl)}
+        result["logit_distance"] = ldd
+        del dep_d, ref_d, idx_d, dep_h, ref_h
 
     if args.calibrate_copy:
         src = torch.arange(64 << 20, dtype=torch.int64, device="cuda")   # 512 MiB

@@ -249,7 +249,10 @@ int imm_debug_fetch(imm_ctx* ctx, int which, uint64_t* out_host, uint64_t capaci
 #define IMM_TRANSCRIPT_DEVICE 0
 #define IMM_TRANSCRIPT_HOST 1
 #define IMM_OPT_SPIN_LIMIT 4      /* host-transcript mode: polls the kernel spends per round waiting for r_k
-                                     before it gives up and exits (default 2^21, about four seconds) */
+                                     before it gives up and exits (default 2^21, about four seconds).
+                                     imm_ldd_tv_kl: polls a workgroup spends waiting for the merged statistics
+                                     of its row (at most 2^15 are used) before it works them out itself; the
+                                     results do not depend on it, 0 makes every workgroup do so */
 #define IMM_OPT_HOST_WAIT_MS 5    /* host-transcript mode: milliseconds the host waits for a mailbox slot
                                      before it aborts the kernel and returns IMM_E_HIP (default 30000) */
 int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value);

@@ -399,8 +399,10 @@ __global__ void fill_u32_kernel(uint32_t* p, uint64_t count, uint32_t v) {
 // the 2K largest logits of the row.  Those are found without sorting the row: every thread keeps
 // the maximum of its own (strided) share while the row streams in from HBM; if tau is the smallest,
 // over the 16 waves, of the r-th largest thread maximum of the wave (16 r >= 2K), then at least 2K
-// logits are >= tau, and only threads whose maximum reaches tau can hold such logits.  Those few
-// threads re-read their share (cache-resident) and append what reaches tau to a candidate list.
+// logits are >= tau, and only threads whose maximum reaches tau can hold such logits.  A thread
+// also keeps its second largest logit and the place of the largest, so that it can tell whether it
+// holds one such logit (then it knows which) or more (then its share is read again, which is rare:
+// a share is scattered over the row, so reading it again touches a cache line per four logits).
 constexpr int kTopkCap = 1024;  // candidate list capacity; beyond it the slow exact path is taken
 
 struct Cand {
@@ -452,8 +454,17 @@ __global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* _
         for (uint32_t j = 0; j < tid; ++j)
             if (member_idx[j] == member_idx[tid]) bad_row = 1;
 
-    // pass 1 (HBM): maximum of the thread's share, eight loads in flight per thread
-    float tmax = -INFINITY;
+    // pass 1 (HBM): the two largest logits of the thread's share and where the largest one sits,
+    // eight loads in flight per thread.  A position is a group of four (VEC), one of the up to three
+    // logits after the last whole group (VEC, numbered from n4 on), or a single logit.
+    float tmax = -INFINITY, second = -INFINITY;
+    uint32_t at = 0;
+    auto take = [&](float v) { second = __builtin_amdgcn_fmed3f(tmax, second, v); tmax = fmaxf(tmax, v); };
+    auto take4 = [&](const v4f& q, uint64_t pos) {
+        const float before = tmax;
+        take(q.x); take(q.y); take(q.z); take(q.w);
+        at = tmax > before ? (uint32_t)pos : at;
+    };
     uint64_t g = tid;
     for (; g + 7 * (uint64_t)kLddBlock < n4; g += 8 * (uint64_t)kLddBlock) {
         v4f q[8];
@@ -462,13 +473,14 @@ __global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* _
             q[j] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(x + 4 * (g + (uint64_t)kLddBlock * j)));
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) tmax = fmaxf(tmax, fmaxf(fmaxf(q[j].x, q[j].y), fmaxf(q[j].z, q[j].w)));
+        for (int j = 0; j < 8; ++j) take4(q[j], g + (uint64_t)kLddBlock * j);
     }
-    for (; g < n4; g += kLddBlock) {
-        const v4f q = *reinterpret_cast<const v4f*>(x + 4 * g);
-        tmax = fmaxf(tmax, fmaxf(fmaxf(q.x, q.y), fmaxf(q.z, q.w)));
+    for (; g < n4; g += kLddBlock) take4(*reinterpret_cast<const v4f*>(x + 4 * g), g);
+    for (uint64_t i = 4 * n4 + tid; i < n; i += kLddBlock) {
+        const float before = tmax;
+        take(x[i]);
+        at = tmax > before ? (uint32_t)(VEC ? n4 + (i - 4 * n4) : i) : at;
     }
-    for (uint64_t i = 4 * n4 + tid; i < n; i += kLddBlock) tmax = fmaxf(tmax, x[i]);
 
     // r-th largest thread maximum of this wave (ties between lanes broken by lane number)
     const uint32_t r = (2 * K + kLddWaves - 1) / kLddWaves;
@@ -490,11 +502,28 @@ __global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* _
 #pragma unroll
     for (int w = 1; w < kLddWaves; ++w) tau = fminf(tau, ldsf[w]);
 
-    // pass 2: only threads whose maximum reaches tau can own a logit >= tau.  They put their names on
-    // a list, and the whole workgroup goes through the shares of the listed threads together, one
-    // (owner, position) pair per thread at a time, so the re-read costs one round trip, not one per
-    // position of a share.
-    if (tmax >= tau) hot[atomicAdd(&hot_count, 1)] = (unsigned short)tid;
+    // pass 2: only threads whose maximum reaches tau can own a logit >= tau.  Most of them own just
+    // that one (their second largest is below tau) and know where it sits.  The few that own more put
+    // their names on a list, and the whole workgroup goes through the shares of the listed threads
+    // together, one (owner, position) pair per thread at a time, so that this re-read costs one
+    // round trip, not one per position of a share.
+    if (tmax >= tau) {
+        if (second >= tau) {
+            hot[atomicAdd(&hot_count, 1)] = (unsigned short)tid;
+        } else {
+            uint64_t where = at;
+            if (VEC) {
+                if (at < n4) {
+                    const v4f q = *reinterpret_cast<const v4f*>(x + 4 * (uint64_t)at);
+                    where = 4 * (uint64_t)at + (q.x == tmax ? 0 : q.y == tmax ? 1 : q.z == tmax ? 2 : 3);
+                } else {
+                    where = 4 * n4 + (at - n4);
+                }
+            }
+            const int slot = atomicAdd(&cand_count, 1);
+            if (slot < kTopkCap) { cand[slot].v = tmax; cand[slot].idx = (int)where; }
+        }
+    }
     __syncthreads();
     if constexpr (VEC) {
         const uint64_t per_owner = (n4 + kLddBlock - 1) / kLddBlock;

@@ -88,6 +88,24 @@ def test_tv_kl_only_one_output_requested(torch, ctx):
     assert torch.equal(tv_both, tv_only) and torch.equal(kl_both, kl_only)
 
 
+def test_tv_kl_workgroups_that_stop_waiting_give_the_same_bits(torch, ctx):
+    """With no polls allowed, every workgroup but the last one of a row works out the other chunks of
+    its row itself instead of waiting for the posted merge.  The results are the same bit for bit."""
+    for steps, vocab in ((5, 70000), (3, 40001)):      # aligned (5 chunks) and unaligned (10 chunks) rows
+        dep, ref = workloads.logits_pair(steps, vocab, seed=77)
+        d, r = torch.from_numpy(dep).cuda(), torch.from_numpy(ref).cuda()
+        tv_wait, kl_wait = ctx.imm_ldd_tv_kl(d, r)
+        ctx.imm_ctx_set_option(imm.IMM_OPT_SPIN_LIMIT, 0)
+        try:
+            tv_alone, kl_alone = ctx.imm_ldd_tv_kl(d, r)
+            tv_again, kl_again = ctx.imm_ldd_tv_kl(d, r)     # and the working memory is left clean
+        finally:
+            ctx.imm_ctx_set_option(imm.IMM_OPT_SPIN_LIMIT, 1 << 21)
+        assert torch.equal(tv_wait, tv_alone) and torch.equal(kl_wait, kl_alone)
+        assert torch.equal(tv_wait, tv_again) and torch.equal(kl_wait, kl_again)
+        check_tv_kl(torch, ctx, dep, ref)
+
+
 def test_tv_kl_unaligned_rows_take_the_scalar_path(torch, ctx):
     """Row stride not a multiple of four floats, and a base address off the 16-byte grid."""
     dep, ref = workloads.logits_pair(6, 3001, seed=11)
