@@ -28,7 +28,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 //
 //   1. chunk maxima mx_c, my_c, then Z_c = sum e^(x - mx_c), Z'_c = sum e^(y - my_c) and
 //      W_c = sum e^(x - mx_c) (x - y), written to the slot of (row, chunk); the workgroup counts
-//      itself in on the row.
+//      itself in on the row (TV only).
 //   2. merge, one chunk per lane: mx = max mx_c, Z = sum Z_c e^(mx_c - mx), likewise Z', W, and
 //      KL = W/Z - (mx + log Z) + (my + log Z').  For the KL that is returned this is done by a small
 //      second kernel, one wave per row; if only KL is wanted, steps 1 and 2 are all there is, and the
@@ -39,8 +39,8 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 //      only scales them by alpha_c = e^(mx_c - mx)/Z and beta_c = e^(my_c - my)/Z' and sums
 //      |alpha_c e^(x - mx_c) - beta_c e^(y - my_c)|.  The parts of a row are added up as fixed-point
 //      numbers by one integer atomic add each (integer addition gives the same total in any order)
-//      that nobody waits for; the second kernel turns the total into TV and leaves counters, sums
-//      and posts as they were found, for the next call.
+//      that nobody waits for; the second kernel turns the total into TV and leaves slots, counters,
+//      sums and posts as they were found, for the next call.
 //
 // The wait in step 3 is bounded.  The chunks of a row have neighbouring workgroup ids, the hardware
 // starts workgroups in id order, and none of them waits before it has counted in, so the post
@@ -50,11 +50,12 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 // workgroup therefore ends whatever the others do.
 //
 // Slots, counters and posts are written with agent-scope atomic stores (they go through to the
-// level all XCDs share) and read with agent-scope atomic loads; where order matters (slot before
-// count) the stores have completed before the count goes up.  The two words of a post need no
-// order: each is valid as soon as it differs from kNoPost.  No cache-wide write-back or invalidate
-// is involved, which is what a device-wide fence would cost here, tens of thousands of times per
-// launch.
+// level all XCDs share) and read with agent-scope atomic loads.  Nothing relies on the order in
+// which such stores become visible: an empty word of a slot or a post is kNoPost, which no result
+// can be, so every word says for itself whether it is there, and the workgroup that merges a row
+// looks again until all words of all slots are (the count only tells it that they are on their
+// way).  No cache-wide write-back or invalidate is involved, which is what a device-wide fence
+// would cost here, tens of thousands of times per launch.
 //
 // Arithmetic: e^d for d <= 0 is the hardware base-2 exponential of d * log2(e), all in fp32:
 // relative error at most about 2^-24 (2.3 |d| + 4) per term (rounding of d, of the product, of the
@@ -73,7 +74,7 @@ constexpr int kPerThreadScalar = 16;  // .. and the others (4-byte loads, one ad
 constexpr int kTvWavesPerSimd = 3;    // register budget of the aligned kernels: 512 / 3 per thread
 constexpr float kAbsent = -3.402823466e38f;                 // stands in for positions past the row's end
 constexpr int kXcds = 8;
-constexpr uint64_t kNoPost = ~0ull;                         // two fp32 NaNs that no arithmetic here produces
+constexpr uint64_t kNoPost = ~0ull;                         // "not there yet": a NaN pattern that no result takes
 constexpr double kTvFixedOne = 4611686018427387904.0;       // 2^62
 
 __device__ __forceinline__ float exp_nonpos(float d) { return __builtin_amdgcn_exp2f(d * kLog2e); }
@@ -146,19 +147,18 @@ __device__ __forceinline__ void put(uint64_t* p, uint64_t v) {
 __device__ __forceinline__ uint64_t peek(const uint64_t* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ uint64_t bits(double v) { return (uint64_t)__double_as_longlong(v); }
+__device__ __forceinline__ uint64_t never_empty(uint64_t v) { return v == kNoPost ? v - 1 : v; }  // still a NaN
+__device__ __forceinline__ uint64_t bits(double v) { return never_empty((uint64_t)__double_as_longlong(v)); }
 __device__ __forceinline__ double real(uint64_t v) { return __longlong_as_double((long long)v); }
 __device__ __forceinline__ uint64_t pair(float lo, float hi) {
-    const uint64_t v = (uint64_t)__float_as_uint(lo) | ((uint64_t)__float_as_uint(hi) << 32);
-    return v == kNoPost ? v - 1 : v;  // still two NaNs
+    return never_empty((uint64_t)__float_as_uint(lo) | ((uint64_t)__float_as_uint(hi) << 32));
 }
 __device__ __forceinline__ float lo_of(uint64_t v) { return __uint_as_float((uint32_t)v); }
 __device__ __forceinline__ float hi_of(uint64_t v) { return __uint_as_float((uint32_t)(v >> 32)); }
 
-// All stores of this thread so far have completed; then the count goes up.  Returns the old count.
+// The count goes up; returns the old count.  The count is not ordered against the stores to the slot:
+// whoever reads slots because of a count checks that every word is there.
 __device__ __forceinline__ uint32_t count_in(uint32_t* counter) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0);
     return __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -223,16 +223,18 @@ template <bool EXACT>
 __device__ __forceinline__ double merge_factor(float d) {
     return EXACT ? exp((double)d) : (double)exp_nonpos(d);
 }
+// Returns whether every word of every slot of the row was there (the same answer in all lanes).
 template <bool EXACT>
-__device__ __forceinline__ void merge_row(const uint64_t* slots, uint32_t S, uint32_t lane, float& gx, float& gy,
+__device__ __forceinline__ bool merge_row(const uint64_t* slots, uint32_t S, uint32_t lane, float& gx, float& gy,
                                           double& Zx, double& Zy, double& W) {
     float lx = -INFINITY, ly = -INFINITY;
     double zx = 0, zy = 0, w = 0;
+    bool there = true;
     for (uint32_t c = lane; c < S; c += 64) {
-        const uint64_t m = peek(slots + c * kSlotWords + 3);
-        const double cx = real(peek(slots + c * kSlotWords + 0));
-        const double cy = real(peek(slots + c * kSlotWords + 1));
-        const double cw = real(peek(slots + c * kSlotWords + 2));
+        const uint64_t m = peek(slots + c * kSlotWords + 3), w0 = peek(slots + c * kSlotWords + 0),
+                       w1 = peek(slots + c * kSlotWords + 1), w2 = peek(slots + c * kSlotWords + 2);
+        there = there && m != kNoPost && w0 != kNoPost && w1 != kNoPost && w2 != kNoPost;
+        const double cx = real(w0), cy = real(w1), cw = real(w2);
         const float nx = fmaxf(lx, lo_of(m)), ny = fmaxf(ly, hi_of(m));
         const double ox = merge_factor<EXACT>(lx - nx), oy = merge_factor<EXACT>(ly - ny);  // e^(-inf) = 0 at first
         const double fx = merge_factor<EXACT>(lo_of(m) - nx), fy = merge_factor<EXACT>(hi_of(m) - ny);
@@ -247,6 +249,7 @@ __device__ __forceinline__ void merge_row(const uint64_t* slots, uint32_t S, uin
     Zx = wave_all_sum(zx * fx);
     Zy = wave_all_sum(zy * fy);
     W = wave_all_sum(w * fx);
+    return __all(there);
 }
 
 template <bool VEC, bool WANT_TV>
@@ -291,12 +294,17 @@ __global__ __launch_bounds__(kTvBlock, VEC ? kTvWavesPerSimd : 4) void ldd_tv_kl
         before = __shfl(before, 0, 64);
         uint64_t p0 = kNoPost, p1 = kNoPost;
         if (before == S - 1) {
+            // everybody has counted in; the words of their slots may still be on their way
             float gx, gy;
             double Zx, Zy, W;
-            merge_row<false>(slots, S, lane, gx, gy, Zx, Zy, W);
-            p0 = pair(gx, gy);
-            p1 = pair(1.0f / (float)Zx, 1.0f / (float)Zy);
-            if (lane == 0) { put(post + 0, p0); put(post + 1, p1); }
+            bool there = false;
+            for (uint64_t polls = 0; polls <= wait_polls && !there; ++polls)
+                there = merge_row<false>(slots, S, lane, gx, gy, Zx, Zy, W);
+            if (there) {
+                p0 = pair(gx, gy);
+                p1 = pair(1.0f / (float)Zx, 1.0f / (float)Zy);
+                if (lane == 0) { put(post + 0, p0); put(post + 1, p1); }
+            }
         } else if (lane == 0) {
             for (uint64_t polls = 0; polls < wait_polls; ++polls) {
                 p0 = peek(post + 0);
@@ -329,6 +337,8 @@ __global__ __launch_bounds__(kTvBlock, VEC ? kTvWavesPerSimd : 4) void ldd_tv_kl
             if (lane == 0) {
                 sh.post[0] = pair(gx, gy);
                 sh.post[1] = pair(1.0f / (float)Zx, 1.0f / (float)Zy);
+                put(post + 0, sh.post[0]);  // the same bits whoever posts
+                put(post + 1, sh.post[1]);
             }
         }
         load_chunk<VEC>(x, chunk * kChunk, chunk_len(chunk), tid, a);
@@ -361,17 +371,20 @@ __global__ __launch_bounds__(kTvBlock, VEC ? kTvWavesPerSimd : 4) void ldd_tv_kl
 // The end of a row, one wave per row, after the kernel above has ended: KL from the slots (step 2
 // with the fp64 factors), TV from the fixed-point sum, and posts, sums and counters back to the
 // state they were found in, for the next call.
-__global__ __launch_bounds__(256) void ldd_finish_kernel(uint32_t T, uint32_t S, const uint64_t* slots_all,
-                                                         uint64_t* posts, uint64_t* sums, uint32_t* counters,
-                                                         double* __restrict__ tv_out, double* __restrict__ kl_out) {
+__global__ __launch_bounds__(256) void ldd_finish_kernel(uint32_t T, uint32_t S, uint64_t* slots_all, uint64_t* posts,
+                                                         uint64_t* sums, uint32_t* counters, double* __restrict__ tv_out,
+                                                         double* __restrict__ kl_out) {
     const uint32_t row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (row >= T) return;
+    uint64_t* slots = slots_all + (uint64_t)row * S * kSlotWords;
     if (kl_out) {
         float gx, gy;
         double Zx, Zy, W;
-        merge_row<true>(slots_all + (uint64_t)row * S * kSlotWords, S, lane, gx, gy, Zx, Zy, W);
+        merge_row<true>(slots, S, lane, gx, gy, Zx, Zy, W);
         if (lane == 0) kl_out[row] = W / Zx - ((double)gx + log(Zx)) + ((double)gy + log(Zy));
     }
+    for (uint32_t c = lane; c < S; c += 64)  // the lane that read a slot is the one that clears it
+        for (int k = 0; k < kSlotWords; ++k) put(slots + c * kSlotWords + k, kNoPost);
     if (tv_out && lane == 0) {
         tv_out[row] = 0.5 * ((double)peek(sums + row) / kTvFixedOne);
         put(sums + row, 0);
@@ -664,10 +677,11 @@ size_t ldd_post_bytes(uint64_t T) { return (size_t)T * kPostWords * sizeof(uint6
 size_t ldd_sum_bytes(uint64_t T) { return (size_t)T * sizeof(uint64_t); }
 size_t ldd_counter_bytes(uint64_t T) { return (size_t)T * sizeof(uint32_t); }
 
-hipError_t ldd_init_sync(hipStream_t stream, uint64_t* posts, size_t post_bytes, uint64_t* sums, size_t sum_bytes,
-                         uint32_t* counters, size_t counter_bytes) {
-    const uint64_t np = post_bytes / sizeof(uint64_t), ns = sum_bytes / sizeof(uint64_t),
-                   nc = counter_bytes / sizeof(uint32_t);
+hipError_t ldd_init_sync(hipStream_t stream, uint64_t* slots, size_t slot_bytes, uint64_t* posts, size_t post_bytes,
+                         uint64_t* sums, size_t sum_bytes, uint32_t* counters, size_t counter_bytes) {
+    const uint64_t nl = slot_bytes / sizeof(uint64_t), np = post_bytes / sizeof(uint64_t),
+                   ns = sum_bytes / sizeof(uint64_t), nc = counter_bytes / sizeof(uint32_t);
+    hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)((nl + 255) / 256)), dim3(256), 0, stream, slots, nl, kNoPost);
     hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, stream, posts, np, kNoPost);
     hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)((ns + 255) / 256)), dim3(256), 0, stream, sums, ns, 0ull);
     hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((nc + 255) / 256)), dim3(256), 0, stream, counters, nc, 0u);

@@ -781,13 +781,14 @@ extern "C" int imm_ldd_tv_kl(imm_ctx* ctx, void* stream, const float* logits_dev
     IMM_HIP(hipSetDevice(ctx->device));
     hipStream_t s = static_cast<hipStream_t>(stream);
     int rc;
-    if ((rc = ctx->ldd_partial.ensure(k::ldd_slot_bytes(T, n)))) return rc;
-    if (ctx->ldd_post.bytes < k::ldd_post_bytes(T) || ctx->ldd_sum.bytes < k::ldd_sum_bytes(T) ||
-        ctx->ldd_arrive.bytes < k::ldd_counter_bytes(T)) {
+    if (ctx->ldd_partial.bytes < k::ldd_slot_bytes(T, n) || ctx->ldd_post.bytes < k::ldd_post_bytes(T) ||
+        ctx->ldd_sum.bytes < k::ldd_sum_bytes(T) || ctx->ldd_arrive.bytes < k::ldd_counter_bytes(T)) {
+        if ((rc = ctx->ldd_partial.ensure(k::ldd_slot_bytes(T, n)))) return rc;
         if ((rc = ctx->ldd_post.ensure(k::ldd_post_bytes(T)))) return rc;
         if ((rc = ctx->ldd_sum.ensure(k::ldd_sum_bytes(T)))) return rc;
         if ((rc = ctx->ldd_arrive.ensure(k::ldd_counter_bytes(T)))) return rc;
-        IMM_HIP(k::ldd_init_sync(s, ctx->ldd_post.u64(), ctx->ldd_post.bytes, ctx->ldd_sum.u64(), ctx->ldd_sum.bytes,
+        IMM_HIP(k::ldd_init_sync(s, ctx->ldd_partial.u64(), ctx->ldd_partial.bytes, ctx->ldd_post.u64(),
+                                 ctx->ldd_post.bytes, ctx->ldd_sum.u64(), ctx->ldd_sum.bytes,
                                  static_cast<uint32_t*>(ctx->ldd_arrive.p), ctx->ldd_arrive.bytes));
     }
     // a workgroup whose wait runs out finishes on its own, so the bound can be short: about 50 ms
