@@ -255,6 +255,10 @@ int imm_debug_fetch(imm_ctx* ctx, int which, uint64_t* out_host, uint64_t capaci
                                      results do not depend on it, 0 makes every workgroup do so */
 #define IMM_OPT_HOST_WAIT_MS 5    /* host-transcript mode: milliseconds the host waits for a mailbox slot
                                      before it aborts the kernel and returns IMM_E_HIP (default 30000) */
+#define IMM_OPT_REPLY_IN_DEVICE_MEMORY 6 /* host-transcript mode: 1 (default) the host writes r_k straight into device
+                                     memory, where the kernel polls it locally (needs the device memory mapped
+                                     into the host's address space; otherwise, and with 0, r_k goes through the
+                                     mailbox in pinned host memory) */
 int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value);
 
 /* Per-kernel timing with HIP events on the launch stream.  Kernel ids: */

@@ -85,7 +85,9 @@ struct Mailbox {
 // device-visible pointer to pinned host memory, slots preset to kMailEmpty).  tables of job p:
 // L = 2^rounds <= kRoundsMaxL entries each, folded in place.  Lane 0 of a workgroup waits at most
 // `spin_limit` polls per round; status[p] (device memory) becomes 0 on completion and 1 if a wait
-// ran out or the host posted kMailAbort.
+// ran out or the host posted kMailAbort.  If `replies` is not null, job p reads r_k from
+// replies[p * IMM_MAX_ROUNDS + k] (device memory that the host writes into directly, preset to
+// kMailEmpty) instead of from its mailbox: polling local memory costs a fraction of a read over PCIe.
 constexpr int kRoundsMaxJobs = 16;
 struct RoundsJob {
     uint64_t* a;
@@ -98,7 +100,7 @@ struct RoundsJobs {
     RoundsJob job[kRoundsMaxJobs];
 };
 hipError_t rounds_mailbox(hipStream_t stream, const RoundsJobs& jobs, int count, Mailbox* mailboxes,
-                          uint64_t spin_limit, uint64_t* status);
+                          const uint64_t* replies, uint64_t spin_limit, uint64_t* status);
 
 }  // namespace k
 }  // namespace imm

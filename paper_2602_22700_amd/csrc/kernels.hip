@@ -765,11 +765,11 @@ __device__ __forceinline__ void quad_accumulate(uint64_t (&c)[3], uint64_t A, ui
     c[2] = gl::add(c[2], p2);
 }
 
-// Sum the nine coefficients over the block; the result is valid in thread 0.  A single wave
+// Sum the nine coefficients over the block into fin9 (visible to all threads on return).  A single wave
 // issues an instruction every few nanoseconds, so the reduction is spread out: every thread of
 // an active wave drops its nine values into LDS, then wave v adds up column v (one value per
 // lane and active wave, then a wave64 shuffle tree), so the nine sums proceed side by side.
-__device__ __forceinline__ void quad_block_sum(Quad3& qd, uint32_t active_waves, uint64_t (*red)[kRoundsBlock],
+__device__ __forceinline__ void quad_block_sum(const Quad3& qd, uint32_t active_waves, uint64_t (*red)[kRoundsBlock],
                                                uint64_t* fin9) {
     const uint32_t tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     if (w < active_waves) {
@@ -786,24 +786,19 @@ __device__ __forceinline__ void quad_block_sum(Quad3& qd, uint32_t active_waves,
         if (lane == 0) fin9[w] = v;
     }
     __syncthreads();
-    if (tid == 0) {
-#pragma unroll
-        for (int t = 0; t < 3; ++t)
-#pragma unroll
-            for (int e = 0; e < 3; ++e) qd.c[t][e] = fin9[3 * t + e];
-    }
 }
 
 // One workgroup per proof: independent proofs run their round loops side by side, each with its
 // own tables and mailbox, while one host thread serves all mailboxes in turn.
 __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs jobs, Mailbox* mailboxes,
-                                                                     uint64_t spin_limit,
+                                                                     const uint64_t* replies, uint64_t spin_limit,
                                                                      uint64_t* __restrict__ status_all) {
     uint64_t* __restrict__ a = jobs.job[blockIdx.x].a;
     uint64_t* __restrict__ b = jobs.job[blockIdx.x].b;
     uint64_t L = jobs.job[blockIdx.x].L;
     const int rounds = jobs.job[blockIdx.x].rounds;
     Mailbox* mb = mailboxes + blockIdx.x;
+    const uint64_t* reply = replies ? replies + (uint64_t)blockIdx.x * IMM_MAX_ROUNDS : mb->r;
     uint64_t* status = status_all + blockIdx.x;
     __shared__ uint64_t lds3[kRoundsWaves][3];
     __shared__ uint64_t red[9][kRoundsBlock];  // 72 KiB of the CU's 160 KiB
@@ -824,39 +819,48 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs
         mail_post(&mb->g[0][2], g.g2);
     }
 
-    for (int kk = 0; kk < rounds; ++kk) {
-        const uint64_t h = L >> 1, q = L >> 2;
-        // coefficients of g_{kk+2}(t) as polynomials in the challenge that is still on its way
-        Quad3 qd;
+    // coefficients of g_2(t) as polynomials in r_1, from the tables as they are
+    auto clear = [](Quad3& qd) {
 #pragma unroll
         for (int t = 0; t < 3; ++t) qd.c[t][0] = qd.c[t][1] = qd.c[t][2] = 0;
-        if (L >= 4) {
-            for (uint64_t i = tid; i < q; i += kRoundsBlock) {
-                const uint64_t x0 = a[i], x1 = a[i + q], y0 = b[i], y1 = b[i + q];
-                const uint64_t dx0 = gl::sub(a[i + h], x0), dx1 = gl::sub(a[i + h + q], x1);
-                const uint64_t dy0 = gl::sub(b[i + h], y0), dy1 = gl::sub(b[i + h + q], y1);
-                quad_accumulate(qd.c[0], x0, dx0, y0, dy0);
-                quad_accumulate(qd.c[1], x1, dx1, y1, dy1);
-                quad_accumulate(qd.c[2], gl::sub(gl::add(x1, x1), x0), gl::sub(gl::add(dx1, dx1), dx0),
-                                gl::sub(gl::add(y1, y1), y0), gl::sub(gl::add(dy1, dy1), dy0));
-            }
-            const uint32_t active = (uint32_t)((q + 63) / 64 < kRoundsWaves ? (q + 63) / 64 : kRoundsWaves);
-            quad_block_sum(qd, active, red, fin9);
-        }
-        if (tid == 0) {
+    };
+    auto accumulate = [](Quad3& qd, uint64_t x0, uint64_t x1, uint64_t xh0, uint64_t xh1, uint64_t y0, uint64_t y1,
+                         uint64_t yh0, uint64_t yh1) {
+        const uint64_t dx0 = gl::sub(xh0, x0), dx1 = gl::sub(xh1, x1), dy0 = gl::sub(yh0, y0), dy1 = gl::sub(yh1, y1);
+        quad_accumulate(qd.c[0], x0, dx0, y0, dy0);
+        quad_accumulate(qd.c[1], x1, dx1, y1, dy1);
+        quad_accumulate(qd.c[2], gl::sub(gl::add(x1, x1), x0), gl::sub(gl::add(dx1, dx1), dx0),
+                        gl::sub(gl::add(y1, y1), y0), gl::sub(gl::add(dy1, dy1), dy0));
+    };
+    auto waves_for = [](uint64_t items) {
+        return (uint32_t)((items + 63) / 64 < kRoundsWaves ? (items + 63) / 64 : kRoundsWaves);
+    };
+    if (L >= 4) {
+        const uint64_t h = L >> 1, q = L >> 2;
+        Quad3 qd;
+        clear(qd);
+        for (uint64_t i = tid; i < q; i += kRoundsBlock)
+            accumulate(qd, a[i], a[i + q], a[i + h], a[i + h + q], b[i], b[i + q], b[i + h], b[i + h + q]);
+        quad_block_sum(qd, waves_for(q), red, fin9);
+    }
+
+    for (int kk = 0; kk < rounds; ++kk) {
+        const uint64_t h = L >> 1;
+        // fin9 holds the coefficients of g_{kk+2} (if there is such a round).  Wave 0: lane 0 waits for
+        // r_{kk+1}; lanes 0..2 then evaluate one value each, g_{kk+2}(t) = c0 + r (c1 + r c2), and post
+        // it to the host before the tables are touched.
+        if (tid < 64) {
             uint64_t r = kMailEmpty;
-            for (uint64_t spin = 0; spin < spin_limit; ++spin) {
-                r = mail_peek(&mb->r[kk]);
-                if (r != kMailEmpty) break;
-            }
-            if (r < gl::P && L >= 4) {
-                // g_{kk+2}(t) = c0 + r (c1 + r c2): out to the host before the tables are touched
-#pragma unroll
-                for (int t = 0; t < 3; ++t)
-                    mail_post(&mb->g[kk + 1][t],
-                              gl::add(qd.c[t][0], gl::mul(r, gl::add(qd.c[t][1], gl::mul(r, qd.c[t][2])))));
-            }
-            r_shared = r;
+            if (tid == 0)
+                for (uint64_t spin = 0; spin < spin_limit; ++spin) {
+                    r = mail_peek(&reply[kk]);
+                    if (r != kMailEmpty) break;
+                }
+            r = __shfl(r, 0, 64);
+            if (r < gl::P && L >= 4 && tid < 3)
+                mail_post(&mb->g[kk + 1][tid],
+                          gl::add(fin9[3 * tid], gl::mul(r, gl::add(fin9[3 * tid + 1], gl::mul(r, fin9[3 * tid + 2])))));
+            if (tid == 0) r_shared = r;
         }
         __syncthreads();
         const uint64_t r = r_shared;
@@ -864,14 +868,37 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs
             if (tid == 0) status[0] = 1;
             return;
         }
-        // bind the leading variable: x[i] <- x[i] + r (x[i + h] - x[i]), in place
-        for (uint64_t i = tid; i < h; i += kRoundsBlock) {
-            const uint64_t x = a[i], y = b[i];
-            a[i] = gl::add(x, gl::mul(r, gl::sub(a[i + h], x)));
-            b[i] = gl::add(y, gl::mul(r, gl::sub(b[i + h], y)));
+        // Bind the leading variable, x[j] <- x[j] + r (x[j + h] - x[j]), in place.  If another round with
+        // prepared coefficients follows (h >= 4), a thread folds exactly the four entries of each table
+        // that its share of the next coefficients is made of, and accumulates them right away: one
+        // pass over the tables and one reduction per round, while the host hashes.
+        if (h >= 4) {
+            const uint64_t h2 = h >> 1, q2 = h >> 2;
+            Quad3 qd;
+            clear(qd);
+            for (uint64_t i = tid; i < q2; i += kRoundsBlock) {
+                const uint64_t j[4] = {i, i + q2, i + h2, i + h2 + q2};
+                uint64_t fa[4], fb[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint64_t x = a[j[e]], y = b[j[e]];
+                    fa[e] = gl::add(x, gl::mul(r, gl::sub(a[j[e] + h], x)));
+                    fb[e] = gl::add(y, gl::mul(r, gl::sub(b[j[e] + h], y)));
+                    a[j[e]] = fa[e];
+                    b[j[e]] = fb[e];
+                }
+                accumulate(qd, fa[0], fa[1], fa[2], fa[3], fb[0], fb[1], fb[2], fb[3]);
+            }
+            quad_block_sum(qd, waves_for(q2), red, fin9);  // its barriers also publish the folded entries
+        } else {
+            for (uint64_t i = tid; i < h; i += kRoundsBlock) {
+                const uint64_t x = a[i], y = b[i];
+                a[i] = gl::add(x, gl::mul(r, gl::sub(a[i + h], x)));
+                b[i] = gl::add(y, gl::mul(r, gl::sub(b[i + h], y)));
+            }
+            __syncthreads();
         }
         L = h;
-        __syncthreads();
     }
     if (tid == 0) {
         mail_post(&mb->fin[0], a[0]);
@@ -1040,9 +1067,9 @@ hipError_t rounds(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, int 
 }
 
 hipError_t rounds_mailbox(hipStream_t stream, const RoundsJobs& jobs, int count, Mailbox* mailboxes,
-                          uint64_t spin_limit, uint64_t* status) {
+                          const uint64_t* replies, uint64_t spin_limit, uint64_t* status) {
     hipLaunchKernelGGL(rounds_mailbox_kernel, dim3((unsigned)count), dim3(kRoundsBlock), 0, stream, jobs, mailboxes,
-                       spin_limit, status);
+                       replies, spin_limit, status);
     return hipGetLastError();
 }
 

@@ -2,6 +2,8 @@
 // transcript glue and proof assembly.  The arithmetic runs in kernels.hip; the
 // host only hashes and moves a few words per round.
 #include <hip/hip_runtime.h>
+#include <mutex>
+#include <emmintrin.h>
 
 #include <atomic>
 #include <chrono>
@@ -113,6 +115,46 @@ struct Profiler {
     }
 };
 
+// Reply slots that the host writes and the round kernel polls: fine-grained device memory, reachable
+// from the host through the PCIe aperture when the whole device memory is mapped there.  Blocks are
+// handed from context to context and never given back to the runtime while the process lives.
+constexpr size_t kReplyWords = (size_t)k::kRoundsMaxJobs * IMM_MAX_ROUNDS;
+static std::mutex g_reply_mutex;
+static std::vector<std::pair<int, uint64_t*>> g_reply_pool;  // (device, block)
+
+static uint64_t* reply_block_take(int device) {
+    {
+        std::lock_guard<std::mutex> lock(g_reply_mutex);
+        for (size_t i = 0; i < g_reply_pool.size(); ++i)
+            if (g_reply_pool[i].first == device) {
+                uint64_t* p = g_reply_pool[i].second;
+                g_reply_pool.erase(g_reply_pool.begin() + (long)i);
+                return p;
+            }
+    }
+    int large_bar = 0;
+    if (hipDeviceGetAttribute(&large_bar, hipDeviceAttributeIsLargeBar, device) != hipSuccess || large_bar != 1) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    void* p = nullptr;
+    if (hipExtMallocWithFlags(&p, kReplyWords * sizeof(uint64_t), hipDeviceMallocFinegrained) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    return static_cast<uint64_t*>(p);
+}
+static void reply_block_give(int device, uint64_t* p) {
+    if (!p) return;
+    std::lock_guard<std::mutex> lock(g_reply_mutex);
+    g_reply_pool.emplace_back(device, p);
+}
+// A store into device memory from the host: through the aperture, pushed out of the write buffers.
+static inline void reply_store(uint64_t* slot, uint64_t v) {
+    *reinterpret_cast<volatile uint64_t*>(slot) = v;
+    _mm_sfence();
+}
+
 }  // namespace imm
 
 struct imm_ctx {
@@ -121,6 +163,8 @@ struct imm_ctx {
         ldd_partial, ldd_post, ldd_sum, ldd_arrive;
     uint64_t* pinned = nullptr;  // host staging, 4 KiB
     imm::k::Mailbox* mailbox = nullptr;  // pinned + coherent, kRoundsMaxJobs of them: g_k out, r_k in
+    uint64_t* replies = nullptr;         // host-writable device memory for r_k, or null (then the mailbox carries them)
+    bool reply_in_device_memory = true;
     int transcript_mode = IMM_TRANSCRIPT_HOST;
     uint64_t spin_limit = 1ull << 21;    // device polls per round before giving up (about 2 us each)
     int64_t host_wait_ms = 30000;        // host patience per mailbox slot
@@ -349,6 +393,7 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
     k::Mailbox* mb = ctx->mailbox;
     std::memset(mb, 0xFF, sizeof(k::Mailbox) * (size_t)count);
     std::atomic_thread_fence(std::memory_order_seq_cst);
+    uint64_t* replies = ctx->reply_in_device_memory ? ctx->replies : nullptr;
     k::RoundsJobs rj{};
     int max_rounds = 0;
     for (int p = 0; p < count; ++p) {
@@ -358,10 +403,16 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
         rj.job[p].rounds = jobs[p]->delta - jobs[p]->kk;
         if (rj.job[p].rounds > max_rounds) max_rounds = rj.job[p].rounds;
     }
+    if (replies) {  // ahead of the launch on the same path to the device, so the kernel finds them empty
+        for (int p = 0; p < count; ++p)
+            for (int t = 0; t < rj.job[p].rounds; ++t)
+                *reinterpret_cast<volatile uint64_t*>(replies + (size_t)p * IMM_MAX_ROUNDS + t) = k::kMailEmpty;
+        _mm_sfence();
+    }
     int rc;
     uint64_t* status_dev = ctx->words.u64() + k::kWordCount + 4;
     if ((rc = ctx->prof.begin(IMM_K_ROUND, s))) return rc;
-    IMM_HIP(k::rounds_mailbox(s, rj, count, mb, ctx->spin_limit, status_dev));
+    IMM_HIP(k::rounds_mailbox(s, rj, count, mb, replies, ctx->spin_limit, status_dev));
     if ((rc = ctx->prof.end(IMM_K_ROUND, s))) return rc;
     bool ok = true;
     for (int slot = 0; slot < max_rounds && ok; ++slot) {
@@ -382,7 +433,10 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
             job.out->g[3 * kk + 2] = g[2];
             job.tr.absorb_words("rnd ", g, 3);
             job.rr[kk] = job.tr.challenge();
-            __atomic_store_n(&mb[p].r[slot], job.rr[kk], __ATOMIC_RELEASE);
+            if (replies)
+                reply_store(replies + (size_t)p * IMM_MAX_ROUNDS + slot, job.rr[kk]);
+            else
+                __atomic_store_n(&mb[p].r[slot], job.rr[kk], __ATOMIC_RELEASE);
         }
     }
     for (int p = 0; p < count && ok; ++p) {
@@ -396,7 +450,10 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
     if (!ok) {
         // release every workgroup from whatever wait it is in, then let the kernel drain
         for (int p = 0; p < count; ++p)
-            for (int t = 0; t < IMM_MAX_ROUNDS; ++t) __atomic_store_n(&mb[p].r[t], k::kMailAbort, __ATOMIC_RELEASE);
+            for (int t = 0; t < IMM_MAX_ROUNDS; ++t) {
+                __atomic_store_n(&mb[p].r[t], k::kMailAbort, __ATOMIC_RELEASE);
+                if (replies) reply_store(replies + (size_t)p * IMM_MAX_ROUNDS + t, k::kMailAbort);
+            }
         IMM_HIP(hipStreamSynchronize(s));
         g_last_error = "round kernel and host transcript lost contact (mailbox wait ran out)";
         return IMM_E_HIP;
@@ -557,6 +614,7 @@ extern "C" int imm_ctx_create(imm_ctx** out, int device, size_t scratch_bytes) {
         delete ctx;
         return fail_hip(e, "hipHostMalloc(mailbox)");
     }
+    ctx->replies = reply_block_take(device);  // may be null: then the mailbox carries the challenges
     if (scratch_bytes) {
         // the hint goes to the widened weight table, by far the largest scratch buffer
         int rc = ctx->encB.ensure(scratch_bytes);
@@ -580,6 +638,7 @@ extern "C" int imm_ctx_destroy(imm_ctx* ctx) {
                        &ctx->ldd_partial, &ctx->ldd_post, &ctx->ldd_sum, &ctx->ldd_arrive})
         bf->release();
     ctx->prof.destroy();
+    reply_block_give(ctx->device, ctx->replies);
     if (ctx->pinned) (void)hipHostFree(ctx->pinned);
     if (ctx->mailbox) (void)hipHostFree(ctx->mailbox);
     delete ctx;
@@ -591,6 +650,7 @@ extern "C" int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value) {
     switch (option) {
     case IMM_OPT_DEBUG_SNAPSHOTS: ctx->debug = value != 0; return IMM_OK;
     case IMM_OPT_WIDEN: ctx->widen = value != 0; return IMM_OK;
+    case IMM_OPT_REPLY_IN_DEVICE_MEMORY: ctx->reply_in_device_memory = value != 0; return IMM_OK;
     case IMM_OPT_TRANSCRIPT:
         if (value != IMM_TRANSCRIPT_DEVICE && value != IMM_TRANSCRIPT_HOST) return IMM_E_SHAPE;
         ctx->transcript_mode = (int)value;

@@ -2,6 +2,9 @@
 // 5.1.1 (padding), 5.3.3 (initial hash value), 6.2.2 (hash computation).
 #include "sha256.h"
 
+#include <cpuid.h>
+#include <immintrin.h>
+
 #include <cstring>
 
 namespace imm {
@@ -20,7 +23,7 @@ const uint32_t K[64] = {
 
 inline uint32_t rotr(uint32_t x, int s) { return (x >> s) | (x << (32 - s)); }
 
-void compress(uint32_t h[8], const uint8_t block[64]) {
+void compress_portable(uint32_t h[8], const uint8_t block[64]) {
     uint32_t w[64];
     for (int t = 0; t < 16; ++t)
         w[t] = (uint32_t)block[4 * t] << 24 | (uint32_t)block[4 * t + 1] << 16 | (uint32_t)block[4 * t + 2] << 8 |
@@ -43,7 +46,61 @@ void compress(uint32_t h[8], const uint8_t block[64]) {
     h[0] += a; h[1] += b; h[2] += c; h[3] += d; h[4] += e; h[5] += f; h[6] += g; h[7] += hh;
 }
 
+// The same compression with the x86 SHA extensions.  SHA256RNDS2 does two rounds on a state kept as
+// the register pair (A,B,E,F) / (C,D,G,H), taking W+K for the two rounds from the low half of its
+// third operand and leaving the new (A,B,E,F) in place of (C,D,G,H), whose role the old (A,B,E,F)
+// takes over; SHA256MSG1/MSG2 do the sigma0 / sigma1 parts of four message-schedule words.
+__attribute__((target("sha,sse4.1,ssse3"))) void compress_shaext(uint32_t h[8], const uint8_t block[64]) {
+    const __m128i be = _mm_set_epi64x(0x0c0d0e0f08090a0bll, 0x0405060700010203ll);  // big-endian words
+    __m128i abcd = _mm_loadu_si128(reinterpret_cast<const __m128i*>(h));        // dwords A,B,C,D
+    __m128i efgh = _mm_loadu_si128(reinterpret_cast<const __m128i*>(h + 4));    // dwords E,F,G,H
+    __m128i t = _mm_shuffle_epi32(abcd, 0xB1);                                    // B,A,D,C
+    efgh = _mm_shuffle_epi32(efgh, 0x1B);                                         // H,G,F,E
+    __m128i abef = _mm_alignr_epi8(t, efgh, 8);                                   // F,E,B,A
+    __m128i cdgh = _mm_blend_epi16(efgh, t, 0xF0);                                // H,G,D,C
+    const __m128i abef0 = abef, cdgh0 = cdgh;
+    __m128i m[4];
+    for (int i = 0; i < 4; ++i)
+        m[i] = _mm_shuffle_epi8(_mm_loadu_si128(reinterpret_cast<const __m128i*>(block + 16 * i)), be);
+    for (int i = 0; i < 16; ++i) {  // four rounds per trip
+        __m128i wk = _mm_add_epi32(m[i & 3], _mm_loadu_si128(reinterpret_cast<const __m128i*>(K + 4 * i)));
+        cdgh = _mm_sha256rnds2_epu32(cdgh, abef, wk);
+        wk = _mm_shuffle_epi32(wk, 0x0E);
+        abef = _mm_sha256rnds2_epu32(abef, cdgh, wk);
+        if (i < 12) {  // W[t..t+3], t = 4 (i + 4), replace W[t-16..t-13]
+            __m128i x = _mm_sha256msg1_epu32(m[i & 3], m[(i + 1) & 3]);                      // + sigma0(W[t-15..t-12])
+            x = _mm_add_epi32(x, _mm_alignr_epi8(m[(i + 3) & 3], m[(i + 2) & 3], 4));        // + W[t-7..t-4]
+            m[i & 3] = _mm_sha256msg2_epu32(x, m[(i + 3) & 3]);                              // + sigma1(W[t-2..t+1])
+        }
+    }
+    abef = _mm_add_epi32(abef, abef0);
+    cdgh = _mm_add_epi32(cdgh, cdgh0);
+    t = _mm_shuffle_epi32(abef, 0x1B);                                            // A,B,E,F
+    cdgh = _mm_shuffle_epi32(cdgh, 0xB1);                                         // G,H,C,D
+    _mm_storeu_si128(reinterpret_cast<__m128i*>(h), _mm_blend_epi16(t, cdgh, 0xF0));      // A,B,C,D
+    _mm_storeu_si128(reinterpret_cast<__m128i*>(h + 4), _mm_alignr_epi8(cdgh, t, 8));     // E,F,G,H
+}
+
+bool cpu_has_shaext() {
+    unsigned a, b, c, d;
+    if (!__get_cpuid(1, &a, &b, &c, &d) || !(c & (1u << 9)) || !(c & (1u << 19))) return false;  // SSSE3, SSE4.1
+    if (!__get_cpuid_count(7, 0, &a, &b, &c, &d) || !(b & (1u << 29))) return false;             // SHA
+    // trust, but verify: one block through both
+    uint8_t block[64];
+    for (int i = 0; i < 64; ++i) block[i] = (uint8_t)(37 * i + 11);
+    uint32_t h1[8], h2[8];
+    for (int i = 0; i < 8; ++i) h1[i] = h2[i] = 0x9e3779b9u * (uint32_t)(i + 1);
+    compress_portable(h1, block);
+    compress_shaext(h2, block);
+    return std::memcmp(h1, h2, sizeof(h1)) == 0;
+}
+
+using CompressFn = void (*)(uint32_t*, const uint8_t*);
+const CompressFn compress = cpu_has_shaext() ? compress_shaext : compress_portable;
+
 }  // namespace
+
+bool sha256_uses_cpu_extensions() { return compress == compress_shaext; }
 
 void Sha256::reset() {
     // first 32 bits of the fractional parts of the square roots of the first 8 primes

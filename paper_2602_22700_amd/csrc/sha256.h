@@ -19,4 +19,7 @@ struct Sha256 {
 
 void sha256(const void* data, size_t len, uint8_t out[32]);
 
+// Whether the compression function runs on the CPU's SHA extensions (checked against the portable one at start-up).
+bool sha256_uses_cpu_extensions();
+
 }  // namespace imm

@@ -441,3 +441,22 @@ def test_profiling_counts_launches(torch, ctx, oracle_fast):
     assert all(ms > 0 for (n, ms) in counts.values() if n)
     ctx.imm_ctx_reset_profiling()
     assert ctx.imm_ctx_kernel_time(imm.IMM_K_ROUND) == (0, 0.0)
+
+
+def test_challenges_through_the_mailbox_or_through_device_memory(torch, ctx, oracle_fast):
+    """The host hands r_k to the round kernel either in device memory (default where the device memory
+    is mapped into the host's address space) or in the pinned mailbox; the proofs are the same."""
+    rng = np.random.default_rng(77)
+    A = rng.integers(-2**15, 2**15, size=(37, 300), dtype=np.int16)
+    B = rng.integers(-128, 128, size=(300, 41), dtype=np.int8)
+    C = oracle_fast.matmul(A, B)
+    com = imm.imm_commit_matmul(A, B, C, 37, 300, 41)
+    want, s_want = oracle_fast.prove(A, B, C, com.digests())
+    Ad, Bd = dev(torch, A), dev(torch, B)
+    try:
+        for mode in (0, 1, 0, 1):
+            ctx.imm_ctx_set_option(imm.IMM_OPT_REPLY_IN_DEVICE_MEMORY, mode)
+            got, s_got = ctx.imm_sumcheck_matmul_prove(Ad, Bd, com, imm.imm_fs_init())
+            assert got.words() == ref.proof_words(want) and s_got == s_want
+    finally:
+        ctx.imm_ctx_set_option(imm.IMM_OPT_REPLY_IN_DEVICE_MEMORY, 1)
