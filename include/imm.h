@@ -204,14 +204,18 @@ int imm_verify(const imm_commit* com, const uint8_t transcript_in[32], const imm
  * Top-K", top-K distance).  These calls compute those numbers for T steps over a vocabulary of n
  * entries; logits are float32, row-major with leading dimension ld (elements), resident on the
  * device.  Exponentials are evaluated in float32, every sum is accumulated in float64, results are
- * float64.  All three are asynchronous on `stream` except where a HOST result is returned. */
+ * float64.  Logits must be finite (a masked entry is a large negative number, not -inf).  All three
+ * are asynchronous on `stream` except where a HOST result is returned.  They use working memory of
+ * the context: calls on one context must not overlap, also not on different streams. */
 
 #define IMM_TOPK_MAX 64 /* largest supported K of imm_topk_distance */
 
 /* tv_out_dev[i] = 1/2 sum_j |p_j - q_j| and kl_out_dev[i] = sum_j p_j (log p_j - log q_j) with
  * p = softmax(logits row i) (deployed) and q = softmax(ref row i) (reference).  Either output may
  * be NULL.  logits_dev, ref_dev: DEVICE float32 T x n; outputs: DEVICE float64[T].
- * Errors: IMM_E_NULL, IMM_E_SHAPE (T or n zero, ld < n), IMM_E_HIP. */
+ * Rows that are 16-byte aligned with n a multiple of four take the fast path.
+ * Errors: IMM_E_NULL (also: both outputs NULL), IMM_E_SHAPE (T or n zero, ld < n, T >= 2^31,
+ * n > 2^30), IMM_E_NOMEM, IMM_E_HIP. */
 int imm_ldd_tv_kl(imm_ctx* ctx, void* stream, const float* logits_dev, const float* ref_dev,
                   uint64_t T, uint64_t n, uint64_t ld, double* tv_out_dev, double* kl_out_dev);
 

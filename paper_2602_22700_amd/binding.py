@@ -24,6 +24,7 @@ IMM_TRANSCRIPT_DEVICE, IMM_TRANSCRIPT_HOST = 0, 1
 (IMM_K_ENCODE_A, IMM_K_ENCODE_B, IMM_K_EQ, IMM_K_REDUCE_A, IMM_K_REDUCE_B, IMM_K_ROUND,
  IMM_K_COMBINE, IMM_K_LDD, IMM_K_TOPK, IMM_K_COUNT) = range(10)
 IMM_TOPK_MAX = 64
+IMM_OK, IMM_E_NULL, IMM_E_SHAPE, IMM_E_DTYPE, IMM_E_NOMEM, IMM_E_HIP, IMM_E_STATE = 0, -1, -2, -3, -4, -5, -6
 KERNEL_NAMES = ["encode_A", "encode_B", "eq_build", "reduce_A", "reduce_B", "round", "combine", "ldd_tv_kl",
                 "topk_distance"]
 

@@ -248,6 +248,45 @@ def test_topk_distance_full_size_sampled_rows(torch, ctx, full_size):
     assert (got[unswapped] == 0).all() and (got[~unswapped] > 0).all()
 
 
+def test_ldd_argument_errors(torch, ctx):
+    import ctypes
+    lib = imm.load()
+    x = torch.zeros((4, 64), dtype=torch.float32, device="cuda")
+    out = torch.zeros(4, dtype=torch.float64, device="cuda")
+    idx = torch.zeros((4, 2), dtype=torch.int32, device="cuda")
+    h = ctx._h
+    tvkl = lambda *a: lib.imm_ldd_tv_kl(h, None, *a)
+    assert tvkl(None, x.data_ptr(), 4, 64, 64, out.data_ptr(), None) == imm.IMM_E_NULL
+    assert tvkl(x.data_ptr(), x.data_ptr(), 4, 64, 64, None, None) == imm.IMM_E_NULL
+    assert tvkl(x.data_ptr(), x.data_ptr(), 0, 64, 64, out.data_ptr(), None) == imm.IMM_E_SHAPE
+    assert tvkl(x.data_ptr(), x.data_ptr(), 4, 0, 64, out.data_ptr(), None) == imm.IMM_E_SHAPE
+    assert tvkl(x.data_ptr(), x.data_ptr(), 4, 64, 63, out.data_ptr(), None) == imm.IMM_E_SHAPE
+    assert tvkl(x.data_ptr(), x.data_ptr(), 4, (1 << 30) + 4, (1 << 30) + 4, out.data_ptr(), None) == imm.IMM_E_SHAPE
+    topk = lambda *a: lib.imm_topk_distance(h, None, *a)
+    assert topk(x.data_ptr(), 4, 64, 64, None, 2, out.data_ptr()) == imm.IMM_E_NULL
+    assert topk(x.data_ptr(), 4, 64, 63, idx.data_ptr(), 2, out.data_ptr()) == imm.IMM_E_SHAPE
+    assert topk(x.data_ptr(), 4, 64, 64, idx.data_ptr(), 64, out.data_ptr()) == imm.IMM_E_SHAPE     # K < n
+    res = ctypes.c_double(0)
+    assert lib.imm_tail_density(h, None, out.data_ptr(), 0, 0.5, ctypes.byref(res)) == imm.IMM_E_SHAPE
+    assert lib.imm_tail_density(h, None, None, 4, 0.5, ctypes.byref(res)) == imm.IMM_E_NULL
+    assert lib.imm_ldd_tv_kl(None, None, x.data_ptr(), x.data_ptr(), 4, 64, 64, out.data_ptr(), None) == imm.IMM_E_NULL
+
+
+def test_contexts_can_come_and_go(torch, oracle_fast=None):
+    """Contexts hand their host-writable reply block on to the next one; proofs and distances still agree."""
+    dep, ref = workloads.logits_pair(3, 5000, seed=4)
+    d, r = torch.from_numpy(dep).cuda(), torch.from_numpy(ref).cuda()
+    first = None
+    for _ in range(4):
+        c = imm.Context(0)
+        tv, kl = c.imm_ldd_tv_kl(d, r)
+        torch.cuda.synchronize()
+        if first is None:
+            first = (tv.clone(), kl.clone())
+        assert torch.equal(first[0], tv) and torch.equal(first[1], kl)
+        c.close()
+
+
 def test_tail_density_counts_exactly(torch, ctx):
     rng = np.random.default_rng(3)
     for T in (1, 63, 1024, 100003, 3000000):
