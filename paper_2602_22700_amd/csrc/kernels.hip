@@ -624,6 +624,8 @@ __global__ void fold_last_kernel(uint64_t* __restrict__ a, uint64_t* __restrict_
 // entries (they stay L2-resident), so the loop is bound by the three SHA-256 compressions per
 // round that lane 0 performs, not by memory; the host is not involved until the final copy.
 constexpr int kRoundsBlock = 1024;
+constexpr uint64_t kRoundsLdsTable = 4096;  // entries per table that the host-transcript loop keeps in LDS
+constexpr uint32_t kRoundsTaskMax = 512;    // longest table whose round is cut into one-multiplication tasks
 constexpr int kRoundsWaves = kRoundsBlock / 64;
 
 struct Triple {
@@ -788,13 +790,175 @@ __device__ __forceinline__ void quad_block_sum(const Quad3& qd, uint32_t active_
     __syncthreads();
 }
 
+// The loop for tables that fit into LDS (2 x 4096 entries), which is every table that has not gone
+// through the one-launch-per-round prefix.  A round is a chain of dependent steps, and a single wave
+// issues an instruction every two to four nanoseconds, so what counts is the number of instructions
+// a wave executes between the arrival of r_k and the moment the coefficients of the next message
+// are ready.  The work of a round is therefore cut into tasks of one modular multiplication each,
+// spread over all 1024 threads:
+//   fold tasks     one per table entry: x[j] <- x[j] + r (x[j + h] - x[j]);
+//   product tasks  nine per group of four entries (i, i+q, i+h, i+h+q of the folded tables): with
+//                  A_t, A_t + dA_t the lower/upper entries seen from evaluation point t = 0, 1, 2
+//                  (likewise B), the products A_t B_t, dA_t dB_t and (A_t + dA_t)(B_t + dB_t), whose
+//                  sums S0_t, S2_t, Sm_t give g(t) = S0_t + r (Sm_t - S0_t - S2_t) + r^2 S2_t.
+// A wave works on one kind of product at a time (task = kind * padded group count + group), adds its
+// 64 products by shuffles, and lane 0 adds the sum to the wave's slot of that kind; nine threads
+// add the slots up.  The tables never leave LDS; a[0], b[0] go out through the mailbox.
+__device__ __forceinline__ void rounds_in_lds(const uint64_t* ga, const uint64_t* gb, uint64_t L0, int rounds,
+                                              Mailbox* mb, const uint64_t* reply, uint64_t spin_limit, uint64_t* status,
+                                              uint64_t (*near)[kRoundsLdsTable], uint64_t (*part)[kRoundsWaves],
+                                              uint64_t (*red)[kRoundsBlock], uint64_t* fin9, uint64_t (*lds3)[3],
+                                              uint64_t* r_shared) {
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t L = (uint32_t)L0;
+    for (uint32_t i = tid; i < L; i += kRoundsBlock) {
+        near[0][i] = ga[i];
+        near[1][i] = gb[i];
+    }
+    if (tid < 9 * kRoundsWaves) part[tid / kRoundsWaves][tid % kRoundsWaves] = 0;
+    __syncthreads();
+
+    // round 1: plain evaluation of the tables as they are
+    Triple g = {0, 0, 0};
+    for (uint32_t i = tid; i < (L >> 1); i += kRoundsBlock)
+        pair_eval(g, near[0][i], near[0][i + (L >> 1)], near[1][i], near[1][i + (L >> 1)]);
+    g = rounds_block_sum(g, lds3);
+    if (tid == 0) {
+        mail_post(&mb->g[0][0], g.g0);
+        mail_post(&mb->g[0][1], g.g1);
+        mail_post(&mb->g[0][2], g.g2);
+    }
+
+    // Product sums of the message after the next challenge, from tables of length len >= 4.
+    // Expects part[][] zeroed and the tables visible; ends with fin9 valid and part[][] zeroed again.
+    auto prepare = [&](uint32_t len) {
+        const uint32_t h = len >> 1, q = len >> 2;
+        const uint32_t qpad = q < 64 ? 64 : q;  // a power of two: one kind of product per wave and trip
+        const uint32_t qshift = 31 - __builtin_clz(qpad);
+        for (uint32_t task = tid; task < 9 * qpad; task += kRoundsBlock) {
+            const uint32_t v = task >> qshift, i = task & (qpad - 1), kind = v / 3, t = v % 3;
+            uint64_t val = 0;
+            if (i < q) {
+                uint64_t lo[2], up[2];  // A_t and A_t + dA_t, then the same for B
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb) {
+                    const uint64_t f0 = near[tb][i], f1 = near[tb][i + q], f2 = near[tb][i + h], f3 = near[tb][i + h + q];
+                    lo[tb] = t == 0 ? f0 : t == 1 ? f1 : gl::sub(gl::add(f1, f1), f0);
+                    up[tb] = t == 0 ? f2 : t == 1 ? f3 : gl::sub(gl::add(f3, f3), f2);
+                }
+                const uint64_t x = kind == 0 ? lo[0] : kind == 2 ? up[0] : gl::sub(up[0], lo[0]);
+                const uint64_t y = kind == 0 ? lo[1] : kind == 2 ? up[1] : gl::sub(up[1], lo[1]);
+                val = gl::mul(x, y);
+            }
+            val = wave_sum(val);
+            if (lane == 0) part[v][wave] = gl::add(part[v][wave], val);
+        }
+        __syncthreads();
+        if (tid < 9) {
+            uint64_t total = 0;
+#pragma unroll
+            for (int w = 0; w < kRoundsWaves; ++w) total = gl::add(total, part[tid][w]);
+            fin9[tid] = total;  // S0_t at t, S2_t at 3 + t, Sm_t at 6 + t
+        }
+        __syncthreads();
+        if (tid < 9 * kRoundsWaves) part[tid / kRoundsWaves][tid % kRoundsWaves] = 0;  // ordered by the next barrier
+    };
+    // Long tables (more than kRoundsTaskMax entries after the fold) have enough groups of four to keep
+    // every thread busy with a whole group: fold its eight entries with r (if `fold`), form the nine
+    // products, one reduction of nine values per thread at the end.  Fewer instructions in total, a
+    // longer chain per thread; below that length the chain is what costs, above it the total.
+    auto prepare_by_groups = [&](uint32_t len, bool fold, uint64_t r) {
+        const uint32_t h = len >> 1, q = len >> 2;
+        Quad3 sums;
+#pragma unroll
+        for (int kind = 0; kind < 3; ++kind) sums.c[kind][0] = sums.c[kind][1] = sums.c[kind][2] = 0;
+        for (uint32_t i = tid; i < q; i += kRoundsBlock) {
+            const uint32_t j[4] = {i, i + q, i + h, i + h + q};
+            uint64_t f[2][4];
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    uint64_t x = near[tb][j[e]];
+                    if (fold) {
+                        x = gl::add(x, gl::mul(r, gl::sub(near[tb][j[e] + len], x)));
+                        near[tb][j[e]] = x;
+                    }
+                    f[tb][e] = x;
+                }
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {
+                uint64_t lo[2], up[2];
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb) {
+                    lo[tb] = t == 0 ? f[tb][0] : t == 1 ? f[tb][1] : gl::sub(gl::add(f[tb][1], f[tb][1]), f[tb][0]);
+                    up[tb] = t == 0 ? f[tb][2] : t == 1 ? f[tb][3] : gl::sub(gl::add(f[tb][3], f[tb][3]), f[tb][2]);
+                }
+                sums.c[0][t] = gl::add(sums.c[0][t], gl::mul(lo[0], lo[1]));
+                sums.c[1][t] = gl::add(sums.c[1][t], gl::mul(gl::sub(up[0], lo[0]), gl::sub(up[1], lo[1])));
+                sums.c[2][t] = gl::add(sums.c[2][t], gl::mul(up[0], up[1]));
+            }
+        }
+        const uint32_t active = (q + 63) / 64 < (uint32_t)kRoundsWaves ? (q + 63) / 64 : (uint32_t)kRoundsWaves;
+        quad_block_sum(sums, active, red, fin9);  // fin9[3 kind + t]; its barriers also publish the folded entries
+    };
+    if (L > kRoundsTaskMax) prepare_by_groups(L, false, 0);
+    else if (L >= 4) prepare(L);
+
+    for (int kk = 0; kk < rounds; ++kk) {
+        const uint32_t h = L >> 1;
+        // Wave 0: lane 0 waits for r_{kk+1}; lanes 0..2 then evaluate one value each of g_{kk+2} and
+        // post it to the host before the tables are touched.
+        if (tid < 64) {
+            uint64_t r = kMailEmpty;
+            if (tid == 0)
+                for (uint64_t spin = 0; spin < spin_limit; ++spin) {
+                    r = mail_peek(&reply[kk]);
+                    if (r != kMailEmpty) break;
+                }
+            r = __shfl(r, 0, 64);
+            if (r < gl::P && L >= 4 && tid < 3) {
+                const uint64_t s0 = fin9[tid], s2 = fin9[3 + tid], sm = fin9[6 + tid];
+                const uint64_t c1 = gl::sub(gl::sub(sm, s0), s2);
+                mail_post(&mb->g[kk + 1][tid], gl::add(s0, gl::mul(r, gl::add(c1, gl::mul(r, s2)))));
+            }
+            if (tid == 0) *r_shared = r;
+        }
+        __syncthreads();
+        const uint64_t r = *r_shared;
+        if (r >= gl::P) {  // no answer within the limit, or the host gave up: uniform exit
+            if (tid == 0) status[0] = 1;
+            return;
+        }
+        if (h > kRoundsTaskMax) {
+            prepare_by_groups(h, true, r);
+            L = h;
+            continue;
+        }
+        // bind the leading variable, one entry per task: entries h .. 2h-1 are only read
+        for (uint32_t task = tid; task < 2 * h; task += kRoundsBlock) {
+            const uint32_t tb = task >= h ? 1 : 0, j = task - tb * h;
+            const uint64_t x = near[tb][j];
+            near[tb][j] = gl::add(x, gl::mul(r, gl::sub(near[tb][j + h], x)));
+        }
+        __syncthreads();
+        L = h;
+        if (L >= 4) prepare(L);
+    }
+    if (tid == 0) {
+        mail_post(&mb->fin[0], near[0][0]);
+        mail_post(&mb->fin[1], near[1][0]);
+        status[0] = 0;
+    }
+}
+
 // One workgroup per proof: independent proofs run their round loops side by side, each with its
 // own tables and mailbox, while one host thread serves all mailboxes in turn.
 __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs jobs, Mailbox* mailboxes,
                                                                      const uint64_t* replies, uint64_t spin_limit,
                                                                      uint64_t* __restrict__ status_all) {
-    uint64_t* __restrict__ a = jobs.job[blockIdx.x].a;
-    uint64_t* __restrict__ b = jobs.job[blockIdx.x].b;
+    uint64_t* a = jobs.job[blockIdx.x].a;
+    uint64_t* b = jobs.job[blockIdx.x].b;
     uint64_t L = jobs.job[blockIdx.x].L;
     const int rounds = jobs.job[blockIdx.x].rounds;
     Mailbox* mb = mailboxes + blockIdx.x;
@@ -804,7 +968,14 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs
     __shared__ uint64_t red[9][kRoundsBlock];  // 72 KiB of the CU's 160 KiB
     __shared__ uint64_t fin9[9];
     __shared__ uint64_t r_shared;
+    __shared__ uint64_t near[2][kRoundsLdsTable];  // 64 KiB: tables short enough live here from the start
+    __shared__ uint64_t part[9][kRoundsWaves];
     const uint32_t tid = threadIdx.x;
+
+    if (L <= kRoundsLdsTable) {  // the usual case: tables of at most 4096 entries
+        rounds_in_lds(a, b, L, rounds, mb, reply, spin_limit, status, near, part, red, fin9, lds3, &r_shared);
+        return;
+    }
 
     // round 1: plain evaluation of the tables as they are
     Triple g = {0, 0, 0};
