@@ -854,11 +854,12 @@ __device__ __forceinline__ void rounds_in_lds(const uint64_t* ga, const uint64_t
             if (lane == 0) part[v][wave] = gl::add(part[v][wave], val);
         }
         __syncthreads();
-        if (tid < 9) {
-            uint64_t total = 0;
+        if (tid < 192) {  // three whole waves: 16 neighbouring lanes add up the slots of one kind
+            const uint32_t v = tid / kRoundsWaves, w = tid % kRoundsWaves;
+            uint64_t total = v < 9 ? part[v][w] : 0;
 #pragma unroll
-            for (int w = 0; w < kRoundsWaves; ++w) total = gl::add(total, part[tid][w]);
-            fin9[tid] = total;  // S0_t at t, S2_t at 3 + t, Sm_t at 6 + t
+            for (int off = kRoundsWaves / 2; off > 0; off >>= 1) total = gl::add(total, __shfl_down(total, off, 64));
+            if (v < 9 && w == 0) fin9[v] = total;  // S0_t at t, S2_t at 3 + t, Sm_t at 6 + t
         }
         __syncthreads();
         if (tid < 9 * kRoundsWaves) part[tid / kRoundsWaves][tid % kRoundsWaves] = 0;  // ordered by the next barrier
