@@ -804,29 +804,40 @@ __device__ __forceinline__ void quad_block_sum(const Quad3& qd, uint32_t active_
 // A wave works on one kind of product at a time (task = kind * padded group count + group), adds its
 // 64 products by shuffles, and lane 0 adds the sum to the wave's slot of that kind; nine threads
 // add the slots up.  The tables never leave LDS; a[0], b[0] go out through the mailbox.
-__device__ __forceinline__ void rounds_in_lds(const uint64_t* ga, const uint64_t* gb, uint64_t L0, int rounds,
+__device__ __forceinline__ void rounds_in_lds(const uint64_t* ga, const uint64_t* gb, uint64_t L0, int first, int rounds,
+                                              uint64_t fold_r,
                                               Mailbox* mb, const uint64_t* reply, uint64_t spin_limit, uint64_t* status,
                                               uint64_t (*near)[kRoundsLdsTable], uint64_t (*part)[kRoundsWaves],
                                               uint64_t (*red)[kRoundsBlock], uint64_t* fin9, uint64_t (*lds3)[3],
                                               uint64_t* r_shared) {
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // first == 0: the tables come in as they are and round 1 starts here.  first > 0: the loop takes
+    // over before round first + 1 from the loop on tables in global memory: the tables there still
+    // have 2 L0 entries and are bound to fold_r = r_first on their way into LDS; the message of round
+    // first + 1 has gone out already.
     uint32_t L = (uint32_t)L0;
     for (uint32_t i = tid; i < L; i += kRoundsBlock) {
-        near[0][i] = ga[i];
-        near[1][i] = gb[i];
+        uint64_t x = ga[i], y = gb[i];
+        if (first) {
+            x = gl::add(x, gl::mul(fold_r, gl::sub(ga[i + L], x)));
+            y = gl::add(y, gl::mul(fold_r, gl::sub(gb[i + L], y)));
+        }
+        near[0][i] = x;
+        near[1][i] = y;
     }
     if (tid < 9 * kRoundsWaves) part[tid / kRoundsWaves][tid % kRoundsWaves] = 0;
     __syncthreads();
 
-    // round 1: plain evaluation of the tables as they are
-    Triple g = {0, 0, 0};
-    for (uint32_t i = tid; i < (L >> 1); i += kRoundsBlock)
-        pair_eval(g, near[0][i], near[0][i + (L >> 1)], near[1][i], near[1][i + (L >> 1)]);
-    g = rounds_block_sum(g, lds3);
-    if (tid == 0) {
-        mail_post(&mb->g[0][0], g.g0);
-        mail_post(&mb->g[0][1], g.g1);
-        mail_post(&mb->g[0][2], g.g2);
+    if (!first) {  // round 1: plain evaluation of the tables as they are
+        Triple g = {0, 0, 0};
+        for (uint32_t i = tid; i < (L >> 1); i += kRoundsBlock)
+            pair_eval(g, near[0][i], near[0][i + (L >> 1)], near[1][i], near[1][i + (L >> 1)]);
+        g = rounds_block_sum(g, lds3);
+        if (tid == 0) {
+            mail_post(&mb->g[0][0], g.g0);
+            mail_post(&mb->g[0][1], g.g1);
+            mail_post(&mb->g[0][2], g.g2);
+        }
     }
 
     // Product sums of the message after the next challenge, from tables of length len >= 4.
@@ -906,7 +917,7 @@ __device__ __forceinline__ void rounds_in_lds(const uint64_t* ga, const uint64_t
     if (L > kRoundsTaskMax) prepare_by_groups(L, false, 0);
     else if (L >= 4) prepare(L);
 
-    for (int kk = 0; kk < rounds; ++kk) {
+    for (int kk = first; kk < rounds; ++kk) {
         const uint32_t h = L >> 1;
         // Wave 0: lane 0 waits for r_{kk+1}; lanes 0..2 then evaluate one value each of g_{kk+2} and
         // post it to the host before the tables are touched.
@@ -974,7 +985,7 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs
     const uint32_t tid = threadIdx.x;
 
     if (L <= kRoundsLdsTable) {  // the usual case: tables of at most 4096 entries
-        rounds_in_lds(a, b, L, rounds, mb, reply, spin_limit, status, near, part, red, fin9, lds3, &r_shared);
+        rounds_in_lds(a, b, L, 0, rounds, 0, mb, reply, spin_limit, status, near, part, red, fin9, lds3, &r_shared);
         return;
     }
 
@@ -1038,6 +1049,11 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs
         const uint64_t r = r_shared;
         if (r >= gl::P) {  // no answer within the limit, or the host gave up: uniform exit
             if (tid == 0) status[0] = 1;
+            return;
+        }
+        if (h <= kRoundsLdsTable) {  // from here on the tables fit into LDS: the other loop takes over
+            rounds_in_lds(a, b, h, kk + 1, rounds, r, mb, reply, spin_limit, status, near, part, red, fin9, lds3,
+                          &r_shared);
             return;
         }
         // Bind the leading variable, x[j] <- x[j] + r (x[j + h] - x[j]), in place.  If another round with
