@@ -46,6 +46,8 @@ def make_workload(name, torch, imm, workloads):
         pairs = [workloads.tiny()]
     elif name == "dense_layer":
         pairs = [(A, B) for (_, A, B) in workloads.dense_layer(0)]
+    elif name == "dense_request":   # the whole audited request: 32 layers x 7 matmuls, one chained transcript
+        pairs = [(A, B) for layer in range(32) for (_, A, B) in workloads.dense_layer(layer)]
     elif name == "moe":
         X, routes = workloads.moe_activations()
         pairs = [(np.ascontiguousarray(X[routes[e]]), workloads.moe_expert_weight(e)) for e in range(8)]
@@ -65,7 +67,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="ffn_up", choices=["ffn_up", "attn", "tiny", "dense_layer", "moe"])
+    ap.add_argument("--workload", default="ffn_up", choices=["ffn_up", "attn", "tiny", "dense_layer", "dense_request", "moe"],
+                    help="dense_request (224 chained proofs) wants --steps 3 --warmup 1")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="time budget of the CPU-oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fold-log2", type=int, default=26,
@@ -181,7 +184,9 @@ def main():
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u64 (Goldilocks field)",
         "data": "synthetic",
         "config": {"workload": args.workload,
-                   "statements": [{"m": A.shape[0], "d": A.shape[1], "n": B.shape[1]} for (A, B, _, _, _) in stmts],
+                   "statements": ([{"m": A.shape[0], "d": A.shape[1], "n": B.shape[1]} for (A, B, _, _, _) in stmts]
+                                  if len(stmts) <= 8 else "%d chained statements: 32 decoder layers x (Wq, Wk, Wv, Wo, "
+                                  "W_gate, W_up, W_down), 1024 tokens" % len(stmts)),
                    "A": "int16 Gaussian sigma=2^10", "B": "int8 uniform", "transcript": "SHA-256 Fiat-Shamir, hashed on the " + args.transcript,
                    "includes": ("eq, narrow-read reduce A+B, rounds, hashing" if args.narrow
                                 else "encode A+B, eq, reduce A+B, rounds, hashing")},
