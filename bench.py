@@ -85,7 +85,7 @@ def main():
                     help="who hashes the round messages: lane 0 of the round kernel, or the host via the mailbox")
     args = ap.parse_args()
     if args.gpus != 1:
-        raise SystemExit("bench.py measures one GPU only: the prover path has no multi-GPU part in this build "
+        raise SystemExit("bench.py measures one GPU only: the prover path has no multi-GPU part "
                          "(run with --gpus 1)")
 
     import torch
