@@ -202,7 +202,8 @@ def check_proof(torch, ctx, oracle_fast, A, B, C=None, state=ref.FS_INIT, interm
 
 @pytest.mark.parametrize("shape", [(1, 1, 1), (1, 5, 3), (3, 1, 2), (2, 2, 2), (4, 4, 4), (5, 6, 7), (2, 9, 1),
                                    (33, 70, 129), (17, 300, 1030), (129, 1025, 515), (7, 2048, 2049),
-                                   (2, 32768, 5), (2, 65539, 3), (1, 131072, 2), (5, 67, 8208), (19, 40, 4096), (8, 8, 16)])
+                                   (2, 32768, 5), (2, 65539, 3), (1, 131072, 2), (5, 67, 8208), (19, 40, 4096), (8, 8, 16),
+                                   (2, 200, 3), (3, 1000, 5), (2, 4096, 3), (2, 5000, 2), (3, 16384, 2)])
 def test_prove_small_and_ragged_shapes(torch, ctx, oracle_fast, shape):
     m, d, n = shape
     rng = np.random.default_rng(m * 10007 + d * 101 + n)
