@@ -146,6 +146,9 @@ def test_tv_kl_full_size_sampled_rows(torch, ctx, full_size):
     steps, vocab = dep.shape
     rows = sorted(np.random.default_rng(1).choice(steps, size=48, replace=False).tolist() + [0, steps - 1])
     tv, kl, worst = check_tv_kl(torch, ctx, dep, ref, rows=rows)
+    # whichever workgroup merges a row and in whatever order the parts arrive, the bits are the same
+    tv2, kl2 = ctx.imm_ldd_tv_kl(torch.from_numpy(dep).cuda(), torch.from_numpy(ref).cuda())
+    assert np.array_equal(tv2.cpu().numpy(), tv) and np.array_equal(kl2.cpu().numpy(), kl)
     assert np.isfinite(tv).all() and np.isfinite(kl).all()
     assert (tv >= 0).all() and (tv <= 1).all() and (kl >= -E(vocab) * 3).all()
     # Pinsker's inequality holds at any size (up to the error bound)
