@@ -263,6 +263,8 @@ int imm_debug_fetch(imm_ctx* ctx, int which, uint64_t* out_host, uint64_t capaci
                                      memory, where the kernel polls it locally (needs the device memory mapped
                                      into the host's address space; otherwise, and with 0, r_k goes through the
                                      mailbox in pinned host memory) */
+#define IMM_OPT_FUSE_REDUCTIONS 7 /* 1 (default): in narrow-read mode the partial evaluations of A and of B run in
+                                     one launch where the operand forms allow it; 0: always one launch each */
 int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value);
 
 /* Per-kernel timing with HIP events on the launch stream.  Kernel ids: */

@@ -28,6 +28,8 @@ struct Split {
     uint64_t per_split;   // rows (or columns) covered by one partial vector
 };
 Split plan_over_rows(uint64_t rows, uint64_t cols);
+// the same for a reduction that shares its launch with a larger one that streams `other_bytes`
+Split plan_over_rows_beside(uint64_t rows, uint64_t cols, size_t elem_bytes, uint64_t other_bytes);
 Split plan_over_cols(uint64_t rows, uint64_t cols, int dtype);
 
 // partial[s][j] = sum over the rows i of split s of eq[i] * T[i][j]   (j < cols)
@@ -37,6 +39,14 @@ hipError_t reduce_over_rows(hipStream_t stream, const void* T, int dtype, uint64
 // partial[s][i] = sum over the columns j of split s of eq[j] * T[i][j]   (i < rows)
 hipError_t reduce_over_cols(hipStream_t stream, const void* T, int dtype, uint64_t rows, uint64_t cols, uint64_t ld,
                             const uint64_t* eq_cols, uint64_t* partial, Split sp);
+
+// Both reductions of one statement in a single launch, A's workgroups first: same arguments and results
+// as reduce_over_rows(A ...) followed by reduce_over_cols(B ...).  Covers the aligned forms of widened A
+// with widened B, int16 A with widened B and int16 A with int8 B; for anything else nothing is launched
+// and *done is false.
+hipError_t reduce_both(hipStream_t stream, const void* A, int dtA, uint64_t rowsA, uint64_t colsA, uint64_t ldA,
+                       const uint64_t* eq_rows, uint64_t* partA, Split spA, const void* B, int dtB, uint64_t rowsB,
+                       uint64_t colsB, uint64_t ldB, const uint64_t* eq_cols, uint64_t* partB, Split spB, bool* done);
 
 // out[j] = sum_s partial[s][j] for j < len, 0 for len <= j < padded
 hipError_t combine(hipStream_t stream, const uint64_t* partial, uint32_t nsplit, uint64_t len, uint64_t padded,

@@ -190,14 +190,13 @@ __device__ __forceinline__ void cols_full_tile(const S* __restrict__ base, uint6
     }
 }
 
+// The work of workgroup (bx, by) of the grid (row blocks, column splits).
 template <typename S, int R, int U, bool VEC>
-__global__ __launch_bounds__(kBlock) void reduce_over_cols_kernel(const S* __restrict__ T, uint64_t ld, uint64_t rows,
-                                                                  uint64_t cols, const uint64_t* __restrict__ eq,
-                                                                  uint64_t* __restrict__ partial,
-                                                                  uint64_t cols_per_split) {
-    __shared__ uint64_t lds[kWaves];
-    const uint64_t row0 = (uint64_t)blockIdx.x * R;
-    const uint64_t c_begin = (uint64_t)blockIdx.y * cols_per_split;
+__device__ __forceinline__ void reduce_over_cols_block(const S* __restrict__ T, uint64_t ld, uint64_t rows, uint64_t cols,
+                                                       const uint64_t* __restrict__ eq, uint64_t* __restrict__ partial,
+                                                       uint64_t cols_per_split, uint32_t bx, uint32_t by, uint64_t* lds) {
+    const uint64_t row0 = (uint64_t)bx * R;
+    const uint64_t c_begin = (uint64_t)by * cols_per_split;
     uint64_t c_end = c_begin + cols_per_split;
     if (c_end > cols) c_end = cols;
     const uint64_t span = c_end - c_begin;
@@ -223,8 +222,17 @@ __global__ __launch_bounds__(kBlock) void reduce_over_cols_kernel(const S* __res
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         uint64_t total = block_sum(gl::acc_reduce(acc[r]), lds);
-        if (threadIdx.x == 0 && row0 + r < rows) partial[(uint64_t)blockIdx.y * rows + row0 + r] = total;
+        if (threadIdx.x == 0 && row0 + r < rows) partial[(uint64_t)by * rows + row0 + r] = total;
     }
+}
+
+template <typename S, int R, int U, bool VEC>
+__global__ __launch_bounds__(kBlock) void reduce_over_cols_kernel(const S* __restrict__ T, uint64_t ld, uint64_t rows,
+                                                                  uint64_t cols, const uint64_t* __restrict__ eq,
+                                                                  uint64_t* __restrict__ partial,
+                                                                  uint64_t cols_per_split) {
+    __shared__ uint64_t lds[kWaves];
+    reduce_over_cols_block<S, R, U, VEC>(T, ld, rows, cols, eq, partial, cols_per_split, blockIdx.x, blockIdx.y, lds);
 }
 
 constexpr int kRowsPerBlock = 2;
@@ -279,15 +287,13 @@ __device__ __forceinline__ uint64_t combine_limb_sums(uint64_t lo, uint64_t hi) 
     return gl::reduce128(low, high);
 }
 
-__global__ __launch_bounds__(kBlock) void reduce_over_cols_i8_kernel(const int8_t* __restrict__ T, uint64_t ld,
-                                                                     uint64_t rows, uint64_t cols,
-                                                                     const uint64_t* __restrict__ eq,
-                                                                     uint64_t* __restrict__ partial,
-                                                                     uint64_t cols_per_split) {
+__device__ __forceinline__ void reduce_over_cols_i8_block(const int8_t* __restrict__ T, uint64_t ld, uint64_t rows,
+                                                          uint64_t cols, const uint64_t* __restrict__ eq,
+                                                          uint64_t* __restrict__ partial, uint64_t cols_per_split,
+                                                          uint32_t bx, uint32_t by, uint64_t (*lds)[2 * kI8Rows + 2]) {
     constexpr int R = kI8Rows;
-    __shared__ uint64_t lds[kWaves][2 * R + 2];
-    const uint64_t row0 = (uint64_t)blockIdx.x * R;
-    const uint64_t c_begin = (uint64_t)blockIdx.y * cols_per_split;
+    const uint64_t row0 = (uint64_t)bx * R;
+    const uint64_t c_begin = (uint64_t)by * cols_per_split;
     uint64_t c_end = c_begin + cols_per_split;
     if (c_end > cols) c_end = cols;
 
@@ -352,8 +358,17 @@ __global__ __launch_bounds__(kBlock) void reduce_over_cols_i8_kernel(const int8_
         }
         const uint64_t sum = combine_limb_sums(a, b);
         const uint64_t corr = gl::mul(128, combine_limb_sums(ka, kb));
-        partial[(uint64_t)blockIdx.y * rows + row0 + r] = gl::sub(sum, corr);
+        partial[(uint64_t)by * rows + row0 + r] = gl::sub(sum, corr);
     }
+}
+
+__global__ __launch_bounds__(kBlock) void reduce_over_cols_i8_kernel(const int8_t* __restrict__ T, uint64_t ld,
+                                                                     uint64_t rows, uint64_t cols,
+                                                                     const uint64_t* __restrict__ eq,
+                                                                     uint64_t* __restrict__ partial,
+                                                                     uint64_t cols_per_split) {
+    __shared__ uint64_t lds[kWaves][2 * kI8Rows + 2];
+    reduce_over_cols_i8_block(T, ld, rows, cols, eq, partial, cols_per_split, blockIdx.x, blockIdx.y, lds);
 }
 
 // The fast int8 kernel needs 16-byte rows and whole 16-column groups.
@@ -365,18 +380,18 @@ bool i8_fast_shape(uint64_t cols) { return cols % 16 == 0; }
 // (a scalar load).
 constexpr int kRowsUnroll = 8;
 
+// The work of workgroup (bx, by) of the grid (column blocks, row splits).  No barriers.
 template <typename S, bool VEC>
-__global__ __launch_bounds__(kBlock) void reduce_over_rows_kernel(const S* __restrict__ T, uint64_t ld, uint64_t rows,
-                                                                  uint64_t cols, const uint64_t* __restrict__ eq,
-                                                                  uint64_t* __restrict__ partial,
-                                                                  uint64_t rows_per_split) {
-    const uint64_t r_begin = (uint64_t)blockIdx.y * rows_per_split;
+__device__ __forceinline__ void reduce_over_rows_block(const S* __restrict__ T, uint64_t ld, uint64_t rows, uint64_t cols,
+                                                       const uint64_t* __restrict__ eq, uint64_t* __restrict__ partial,
+                                                       uint64_t rows_per_split, uint32_t bx, uint32_t by) {
+    const uint64_t r_begin = (uint64_t)by * rows_per_split;
     uint64_t r_end = r_begin + rows_per_split;
     if (r_end > rows) r_end = rows;
-    uint64_t* out = partial + (uint64_t)blockIdx.y * cols;
+    uint64_t* out = partial + (uint64_t)by * cols;
     if (VEC) {
         using Raw = typename RawPair<S>::type;
-        const uint64_t col = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 2;
+        const uint64_t col = ((uint64_t)bx * kBlock + threadIdx.x) * 2;
         if (col >= cols) return;
         gl::Acc a0, a1;
         gl::acc_clear(a0);
@@ -415,12 +430,54 @@ __global__ __launch_bounds__(kBlock) void reduce_over_rows_kernel(const S* __res
             out[col] = gl::acc_reduce(a0);
         }
     } else {
-        const uint64_t col = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+        const uint64_t col = (uint64_t)bx * kBlock + threadIdx.x;
         if (col >= cols) return;
         gl::Acc a0;
         gl::acc_clear(a0);
         for (uint64_t i = r_begin; i < r_end; ++i) gl::acc_mac(a0, to_field<S>(T[i * ld + col]), eq[i]);
         out[col] = gl::acc_reduce(a0);
+    }
+}
+
+template <typename S, bool VEC>
+__global__ __launch_bounds__(kBlock) void reduce_over_rows_kernel(const S* __restrict__ T, uint64_t ld, uint64_t rows,
+                                                                  uint64_t cols, const uint64_t* __restrict__ eq,
+                                                                  uint64_t* __restrict__ partial,
+                                                                  uint64_t rows_per_split) {
+    reduce_over_rows_block<S, VEC>(T, ld, rows, cols, eq, partial, rows_per_split, blockIdx.x, blockIdx.y);
+}
+
+// ------------------------------------------------------------------ both reductions of a statement in one launch
+// The table of A is small next to B's (67 MB against 470 MB at the FFN shape): on its own its kernel
+// spends a third of its time filling and draining the machine.  Here the workgroups of the
+// row-direction reduction of A come first in the grid of the column-direction reduction of B, so
+// they stream alongside it.  Only the aligned forms of the three operand combinations that the
+// prover produces are covered (both widened; int16 activations with widened or with int8 weights).
+struct ReduceArgs {
+    const void* T;
+    uint64_t ld, rows, cols;
+    const uint64_t* eq;
+    uint64_t* partial;
+    uint64_t per_split;
+    uint32_t grid_x, grid_y;
+};
+
+template <typename SA, typename SB, bool B_IS_I8>
+__global__ __launch_bounds__(kBlock) void reduce_both_kernel(ReduceArgs a, ReduceArgs b) {
+    __shared__ uint64_t lds[kWaves][2 * kI8Rows + 2];
+    const uint32_t a_blocks = a.grid_x * a.grid_y;
+    if (blockIdx.x < a_blocks) {
+        reduce_over_rows_block<SA, true>(static_cast<const SA*>(a.T), a.ld, a.rows, a.cols, a.eq, a.partial, a.per_split,
+                                         blockIdx.x % a.grid_x, blockIdx.x / a.grid_x);
+    } else {
+        const uint32_t id = blockIdx.x - a_blocks;
+        if (B_IS_I8)
+            reduce_over_cols_i8_block(static_cast<const int8_t*>(b.T), b.ld, b.rows, b.cols, b.eq, b.partial,
+                                      b.per_split, id % b.grid_x, id / b.grid_x, lds);
+        else
+            reduce_over_cols_block<SB, kRowsPerBlock, kColsUnroll, true>(static_cast<const SB*>(b.T), b.ld, b.rows, b.cols,
+                                                                         b.eq, b.partial, b.per_split, id % b.grid_x,
+                                                                         id / b.grid_x, &lds[0][0]);
     }
 }
 
@@ -1145,6 +1202,22 @@ Split plan_over_rows(uint64_t rows, uint64_t cols) {
     return sp;
 }
 
+Split plan_over_rows_beside(uint64_t rows, uint64_t cols, size_t elem_bytes, uint64_t other_bytes) {
+    // Beside a larger reduction that fills the machine on its own, few long-lived workgroups stream best:
+    // each takes about as many bytes as half a CU's share of the other table, at least 128 KiB.
+    uint64_t target = other_bytes / 512;
+    if (target < (128u << 10)) target = 128u << 10;
+    const uint64_t width = cols < 2 * kBlock ? cols : 2 * kBlock;  // columns of a workgroup
+    uint64_t per = target / (width * elem_bytes);
+    if (per < 32) per = 32;
+    per = (per + kRowsUnroll - 1) / kRowsUnroll * kRowsUnroll;
+    if (per > rows) per = rows;
+    Split sp;
+    sp.per_split = per;
+    sp.nsplit = (uint32_t)((rows + per - 1) / per);
+    return sp;
+}
+
 Split plan_over_cols(uint64_t rows, uint64_t cols, int dtype) {
     Split sp;
     if (dtype == IMM_I8 && i8_fast_shape(cols)) {
@@ -1199,6 +1272,36 @@ hipError_t reduce_over_cols(hipStream_t stream, const void* T, int dtype, uint64
     case IMM_F64P: return launch_over_cols<uint64_t>(stream, T, rows, cols, ld, eq_cols, partial, sp);
     default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t reduce_both(hipStream_t stream, const void* A, int dtA, uint64_t rowsA, uint64_t colsA, uint64_t ldA,
+                       const uint64_t* eq_rows, uint64_t* partA, Split spA, const void* B, int dtB, uint64_t rowsB,
+                       uint64_t colsB, uint64_t ldB, const uint64_t* eq_cols, uint64_t* partB, Split spB, bool* done) {
+    *done = false;
+    const size_t sa = dtA == IMM_F64P ? 8 : dtA == IMM_I16 ? 2 : 0;
+    if (!sa || reinterpret_cast<uintptr_t>(A) % (2 * sa) != 0 || ldA % 2 != 0) return hipSuccess;
+    const bool eq_ok = reinterpret_cast<uintptr_t>(eq_cols) % 16 == 0;
+    const bool b_wide = dtB == IMM_F64P && reinterpret_cast<uintptr_t>(B) % 16 == 0 && ldB % 2 == 0 &&
+                        spB.per_split % 2 == 0 && eq_ok;
+    const bool b_i8 = dtB == IMM_I8 && dtA == IMM_I16 && i8_fast_shape(colsB) && spB.per_split % kI8ColsPerPass == 0 &&
+                      spB.per_split <= kI8MaxSplit && reinterpret_cast<uintptr_t>(B) % 16 == 0 && ldB % 16 == 0 && eq_ok;
+    if (!b_wide && !b_i8) return hipSuccess;
+    ReduceArgs a{A, ldA, rowsA, colsA, eq_rows, partA, spA.per_split,
+                 (uint32_t)(((colsA + 1) / 2 + kBlock - 1) / kBlock), spA.nsplit};
+    ReduceArgs b{B, ldB, rowsB, colsB, eq_cols, partB, spB.per_split,
+                 (uint32_t)(b_i8 ? (rowsB + kI8Rows - 1) / kI8Rows : (rowsB + kRowsPerBlock - 1) / kRowsPerBlock),
+                 spB.nsplit};
+    const uint64_t blocks = (uint64_t)a.grid_x * a.grid_y + (uint64_t)b.grid_x * b.grid_y;
+    if (blocks > 0x7FFFFFFFull) return hipSuccess;
+    const dim3 grid((unsigned)blocks);
+    if (b_i8)
+        hipLaunchKernelGGL((reduce_both_kernel<int16_t, int8_t, true>), grid, dim3(kBlock), 0, stream, a, b);
+    else if (dtA == IMM_F64P)
+        hipLaunchKernelGGL((reduce_both_kernel<uint64_t, uint64_t, false>), grid, dim3(kBlock), 0, stream, a, b);
+    else
+        hipLaunchKernelGGL((reduce_both_kernel<int16_t, uint64_t, false>), grid, dim3(kBlock), 0, stream, a, b);
+    *done = true;
+    return hipGetLastError();
 }
 
 hipError_t combine(hipStream_t stream, const uint64_t* partial, uint32_t nsplit, uint64_t len, uint64_t padded,

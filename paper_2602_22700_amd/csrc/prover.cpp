@@ -94,6 +94,9 @@ struct Profiler {
         IMM_HIP(hipEventRecord(ev[recs.back().first + 1], s));
         return IMM_OK;
     }
+    void cancel(int id) {  // drops the pair opened by the last begin(id): nothing was launched after all
+        if (wants(id) && !recs.empty()) recs.pop_back();
+    }
     int flush() {
         for (const Rec& r : recs) {
             IMM_HIP(hipEventSynchronize(ev[r.first + 1]));
@@ -171,6 +174,7 @@ struct imm_ctx {
     imm::Profiler prof;
     bool debug = false;
     bool widen = true;
+    bool fuse_reductions = true;
     // intermediates of the last single proof (debug)
     int dbg_mu = -1, dbg_delta = -1, dbg_nu = -1;
     uint64_t dbg_rx[IMM_MAX_ROUNDS], dbg_ry[IMM_MAX_ROUNDS], dbg_r[IMM_MAX_ROUNDS];
@@ -313,9 +317,10 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job) {
     // a2: eq vectors for both points
     if ((rc = build_eq(ctx, s, job.rx, job.mu, job.ry, job.nu))) return rc;
 
-    // a1 + a3 for A, then a1 + a4 for B: each operand is widened into scratch (skipped for
-    // pre-encoded tables or in narrow-read mode) and reduced right away, so the reduction of A
-    // does not compete with the write stream of the much larger B.
+    // a1 for A and B: each operand is widened into scratch (skipped for pre-encoded tables or in
+    // narrow-read mode).  Then a3 + a4: in narrow-read mode both reductions in one launch where the
+    // operand forms allow it (the small table of A streams alongside B's instead of filling and
+    // draining the machine on its own), else one after the other.
     const void* Ap = ds.A_dev;
     const void* Bp = ds.B_dev;
     int dtA = (int)ds.dtA, dtB = (int)ds.dtB;
@@ -327,8 +332,6 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job) {
         Ap = ctx->encA.p;
         dtA = IMM_F64P;
     }
-    if ((rc = partial_over_rows(ctx, s, IMM_K_REDUCE_A, Ap, dtA, m, d, d, ctx->eqx.u64(), D, ctx->partA, job.a)))
-        return rc;
     if (ctx->widen && dtB != IMM_F64P) {
         if ((rc = ctx->encB.ensure(sizeof(uint64_t) * d * n))) return rc;
         if ((rc = ctx->prof.begin(IMM_K_ENCODE_B, s))) return rc;
@@ -337,8 +340,35 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job) {
         Bp = ctx->encB.p;
         dtB = IMM_F64P;
     }
-    if ((rc = partial_over_cols(ctx, s, IMM_K_REDUCE_B, Bp, dtB, d, n, n, ctx->eqy.u64(), D, ctx->partB, job.b)))
-        return rc;
+    // (only beside the narrow-read reduction of B: beside the widened table, ten times larger, A's
+    // share is within the noise, and the reduction of B keeps a launch and a bandwidth figure of its own)
+    bool both = false;
+    if (ctx->fuse_reductions && dtB == IMM_I8) {
+        const size_t elemA = dtA == IMM_F64P || dtA == IMM_I64 ? 8 : dtA == IMM_I16 ? 2 : 1;
+        const size_t elemB = dtB == IMM_F64P || dtB == IMM_I64 ? 8 : dtB == IMM_I16 ? 2 : 1;
+        const k::Split spA = k::plan_over_rows_beside(m, d, elemA, d * n * elemB), spB = k::plan_over_cols(d, n, dtB);
+        const bool directA = spA.nsplit == 1, directB = spB.nsplit == 1;
+        if (!directA && (rc = ctx->partA.ensure(sizeof(uint64_t) * spA.nsplit * d))) return rc;
+        if (!directB && (rc = ctx->partB.ensure(sizeof(uint64_t) * spB.nsplit * d))) return rc;
+        if ((rc = ctx->prof.begin(IMM_K_REDUCE_B, s))) return rc;
+        IMM_HIP(k::reduce_both(s, Ap, dtA, m, d, d, ctx->eqx.u64(), directA ? job.a : ctx->partA.u64(), spA, Bp, dtB, d, n,
+                               n, ctx->eqy.u64(), directB ? job.b : ctx->partB.u64(), spB, &both));
+        if (both) {
+            if ((rc = ctx->prof.end(IMM_K_REDUCE_B, s))) return rc;
+        } else {
+            ctx->prof.cancel(IMM_K_REDUCE_B);
+        }
+        if (both) {
+            if ((rc = finish_partial(ctx, s, directA, ctx->partA, spA.nsplit, d, D, job.a))) return rc;
+            if ((rc = finish_partial(ctx, s, directB, ctx->partB, spB.nsplit, d, D, job.b))) return rc;
+        }
+    }
+    if (!both) {
+        if ((rc = partial_over_rows(ctx, s, IMM_K_REDUCE_A, Ap, dtA, m, d, d, ctx->eqx.u64(), D, ctx->partA, job.a)))
+            return rc;
+        if ((rc = partial_over_cols(ctx, s, IMM_K_REDUCE_B, Bp, dtB, d, n, n, ctx->eqy.u64(), D, ctx->partB, job.b)))
+            return rc;
+    }
 
     std::memset(job.out, 0, sizeof(*job.out));
     job.out->version = IMM_PROOF_VERSION;
@@ -650,6 +680,7 @@ extern "C" int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value) {
     switch (option) {
     case IMM_OPT_DEBUG_SNAPSHOTS: ctx->debug = value != 0; return IMM_OK;
     case IMM_OPT_WIDEN: ctx->widen = value != 0; return IMM_OK;
+    case IMM_OPT_FUSE_REDUCTIONS: ctx->fuse_reductions = value != 0; return IMM_OK;
     case IMM_OPT_REPLY_IN_DEVICE_MEMORY: ctx->reply_in_device_memory = value != 0; return IMM_OK;
     case IMM_OPT_TRANSCRIPT:
         if (value != IMM_TRANSCRIPT_DEVICE && value != IMM_TRANSCRIPT_HOST) return IMM_E_SHAPE;

@@ -430,18 +430,52 @@ def test_profiling_counts_launches(torch, ctx, oracle_fast):
     A, B = workloads.tiny()
     com = imm.imm_commit_matmul(A, B, oracle_fast.matmul(A, B), 64, 64, 64)
     Ad, Bd = dev(torch, A), dev(torch, B)
-    ctx.imm_ctx_reset_profiling()
-    ctx.imm_ctx_set_profiling((1 << imm.IMM_K_COUNT) - 1)
-    for _ in range(3):
-        ctx.imm_sumcheck_matmul_prove(Ad, Bd, com, ref.FS_INIT)
-    ctx.imm_ctx_set_profiling(0)
-    counts = {imm.KERNEL_NAMES[k]: ctx.imm_ctx_kernel_time(k) for k in range(imm.IMM_K_COUNT)}
-    assert counts["encode_A"][0] == 3 and counts["encode_B"][0] == 3 and counts["eq_build"][0] == 3
-    assert counts["reduce_A"][0] == 3 and counts["reduce_B"][0] == 3 and counts["combine"][0] <= 6
-    assert counts["round"][0] == 3       # all rounds of a proof run in one launch
-    assert all(ms > 0 for (n, ms) in counts.values() if n)
+    try:
+        for widen, fused in ((1, 1), (0, 1), (0, 0)):
+            ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, widen)
+            ctx.imm_ctx_set_option(imm.IMM_OPT_FUSE_REDUCTIONS, fused)
+            ctx.imm_ctx_reset_profiling()
+            ctx.imm_ctx_set_profiling((1 << imm.IMM_K_COUNT) - 1)
+            for _ in range(3):
+                ctx.imm_sumcheck_matmul_prove(Ad, Bd, com, ref.FS_INIT)
+            ctx.imm_ctx_set_profiling(0)
+            counts = {imm.KERNEL_NAMES[k]: ctx.imm_ctx_kernel_time(k) for k in range(imm.IMM_K_COUNT)}
+            enc = 3 if widen else 0
+            assert counts["encode_A"][0] == enc and counts["encode_B"][0] == enc and counts["eq_build"][0] == 3
+            # in narrow-read mode one launch covers both reductions unless that is switched off
+            assert counts["reduce_A"][0] == (0 if (fused and not widen) else 3) and counts["reduce_B"][0] == 3
+            assert counts["combine"][0] <= 6
+            assert counts["round"][0] == 3       # all rounds of a proof run in one launch
+            assert all(ms > 0 for (n, ms) in counts.values() if n)
+    finally:
+        ctx.imm_ctx_set_option(imm.IMM_OPT_FUSE_REDUCTIONS, 1)
+        ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
     ctx.imm_ctx_reset_profiling()
     assert ctx.imm_ctx_kernel_time(imm.IMM_K_ROUND) == (0, 0.0)
+
+
+def test_reductions_in_one_launch_or_two(torch, ctx, oracle_fast):
+    """Same proofs whether the partial evaluations of A and B share a launch or not, in the three
+    operand forms the shared launch covers and in one it does not (odd row length)."""
+    rng = np.random.default_rng(123)
+    for (m, d, n) in ((70, 300, 96), (33, 128, 4096), (5, 67, 31)):
+        A = rng.integers(-2**15, 2**15, size=(m, d), dtype=np.int16)
+        B = rng.integers(-128, 128, size=(d, n), dtype=np.int8)
+        C = oracle_fast.matmul(A, B)
+        com = imm.imm_commit_matmul(A, B, C, m, d, n)
+        want, s_want = oracle_fast.prove(A, B, C, com.digests())
+        Ad, Bd = dev(torch, A), dev(torch, B)
+        Be = ctx.imm_encode(Bd)
+        try:
+            for fused in (1, 0):
+                ctx.imm_ctx_set_option(imm.IMM_OPT_FUSE_REDUCTIONS, fused)
+                for widen, Bx in ((1, Bd), (0, Bd), (1, Be)):
+                    ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, widen)
+                    got, s_got = ctx.imm_sumcheck_matmul_prove(Ad, Bx, com, imm.imm_fs_init())
+                    assert got.words() == ref.proof_words(want) and s_got == s_want, (m, d, n, fused, widen)
+        finally:
+            ctx.imm_ctx_set_option(imm.IMM_OPT_FUSE_REDUCTIONS, 1)
+            ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
 
 
 def test_challenges_through_the_mailbox_or_through_device_memory(torch, ctx, oracle_fast):
