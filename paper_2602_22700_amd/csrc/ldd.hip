@@ -2,10 +2,11 @@
 // two softmax distributions (paper section 4.3), the top-K distance (paper appendix on the
 // verification of top-K) and the tail density p(t1) (section 5.3).
 //
-// One workgroup of 1024 threads owns one decision step (one row of the logits).  A row of a
-// 128k vocabulary is 512 KiB per operand, so the kernels are HBM-bound: each row is streamed
-// from HBM once; whatever has to be looked at a second time is re-read right away, in reverse
-// order, while it is still in the caches.
+// A row of a 128k vocabulary is 512 KiB per operand and every logit is needed once, so all of these
+// are streaming reductions bound by HBM.  The softmax distances cut a row into chunks, one workgroup
+// per chunk, which hold their part of both rows in registers until the row's statistics are known;
+// the top-K distance takes one workgroup of 1024 threads per row and finds the few largest logits
+// without a sort.  Each logit is read from memory once.
 #include "ldd.h"
 
 #include <math.h>
