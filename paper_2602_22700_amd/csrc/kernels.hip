@@ -793,9 +793,10 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_kernel(uint64_t* __restri
 }
 
 // ------------------------------------------------------------------ all rounds in one launch, host hashes
-// Same loop as rounds_kernel, but the transcript stays on the host: lane 0 posts g_k into a
-// mailbox in pinned host memory and polls the slot where the host thread (spinning on the same
-// mailbox inside the prove call) deposits r_k.  Slots start as kMailEmpty, a value no canonical
+// Same loop as rounds_kernel, but the transcript stays on the host: the workgroup posts g_k into a
+// mailbox in pinned host memory and lane 0 polls the slot where the host thread (spinning on the same
+// mailbox inside the prove call) deposits r_k: a word of the mailbox, or of a block of device
+// memory that the host can write into.  Slots start as kMailEmpty, a value no canonical
 // field element can take, so one 8-byte access both signals and carries the value.  The wait is
 // bounded: after `spin_limit` polls, or when the host posts kMailAbort, every wave leaves the
 // kernel and status[0] is set.
@@ -809,7 +810,7 @@ __device__ __forceinline__ uint64_t mail_peek(const uint64_t* slot) {
 // While the host hashes g_k, the device already prepares round k+1: after the fold with r_k the
 // entries are x + r_k dx, so each value g_{k+1}(t) is a quadratic c0 + c1 r_k + c2 r_k^2 whose
 // coefficients depend only on the tables as they are now.  The block computes the nine
-// coefficients before r_k arrives; when it does, lane 0 evaluates the three quadratics and posts
+// coefficients before r_k arrives; when it does, three lanes evaluate one quadratic each and post
 // g_{k+1} at once, and the in-place fold runs while the host is busy with g_{k+1}.  The critical
 // path of a round is then one host hash and one PCIe round trip.
 struct Quad3 {
