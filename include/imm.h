@@ -265,6 +265,13 @@ int imm_debug_fetch(imm_ctx* ctx, int which, uint64_t* out_host, uint64_t capaci
                                      mailbox in pinned host memory) */
 #define IMM_OPT_FUSE_REDUCTIONS 7 /* 1 (default): in narrow-read mode the partial evaluations of A and of B run in
                                      one launch where the operand forms allow it; 0: always one launch each */
+#define IMM_OPT_ENCODE_AHEAD 8    /* 1 (default): in a batch proved one proof after the other, the raw operands of
+                                     up to three proofs beyond the current one are widened (IMM_OPT_WIDEN) on a
+                                     second stream of the library's own while the current one runs, into a ring
+                                     of four pairs of scratch tables; that stream starts after everything queued
+                                     on the caller's stream up to that point, so operands only have to be ready
+                                     in the caller's stream order, as without it, and no table outlives the call.
+                                     0: every proof widens its own operands */
 int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value);
 
 /* Per-kernel timing with HIP events on the launch stream.  Kernel ids: */

@@ -21,6 +21,7 @@ IMM_I8, IMM_I16, IMM_I64, IMM_F64P = 1, 2, 3, 4
 IMM_OPT_DEBUG_SNAPSHOTS, IMM_OPT_WIDEN, IMM_OPT_TRANSCRIPT, IMM_OPT_SPIN_LIMIT, IMM_OPT_HOST_WAIT_MS = 1, 2, 3, 4, 5
 IMM_OPT_REPLY_IN_DEVICE_MEMORY = 6
 IMM_OPT_FUSE_REDUCTIONS = 7
+IMM_OPT_ENCODE_AHEAD = 8
 IMM_TRANSCRIPT_DEVICE, IMM_TRANSCRIPT_HOST = 0, 1
 (IMM_K_ENCODE_A, IMM_K_ENCODE_B, IMM_K_EQ, IMM_K_REDUCE_A, IMM_K_REDUCE_B, IMM_K_ROUND,
  IMM_K_COMBINE, IMM_K_LDD, IMM_K_TOPK, IMM_K_COUNT) = range(10)

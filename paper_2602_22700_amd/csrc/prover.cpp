@@ -162,7 +162,7 @@ static inline void reply_store(uint64_t* slot, uint64_t v) {
 
 struct imm_ctx {
     int device = 0;
-    imm::DevBuf encA, encB, eqx, eqy, a, b, partA, partB, round_scratch, words, snapA, snapB, group_tables,
+    imm::DevBuf eqx, eqy, a, b, partA, partB, round_scratch, words, snapA, snapB, group_tables,
         ldd_partial, ldd_post, ldd_sum, ldd_arrive;
     uint64_t* pinned = nullptr;  // host staging, 4 KiB
     imm::k::Mailbox* mailbox = nullptr;  // pinned + coherent, kRoundsMaxJobs of them: g_k out, r_k in
@@ -175,6 +175,22 @@ struct imm_ctx {
     bool debug = false;
     bool widen = true;
     bool fuse_reductions = true;
+    // Widening of the operands of the proofs to come while the current proof runs (sequences of proofs
+    // only): a ring of table pairs, a stream for the encode kernels, one event that lets them start
+    // and one per pair that says its tables are written.
+    static constexpr int kAheadDepth = 3;  // proofs beyond the current one whose tables may be queued
+    static constexpr int kTableSets = kAheadDepth + 1;
+    bool encode_ahead = true;
+    imm::DevBuf encA[kTableSets], encB[kTableSets];
+    int set = 0;                           // the pair the current proof reads
+    hipStream_t ahead_stream = nullptr;
+    hipEvent_t ahead_go = nullptr, ahead_done[kTableSets] = {};
+    struct Ahead {
+        imm_matmul_desc ds;
+        bool hasA, hasB;
+        int set;
+    } ahead[kAheadDepth];                  // in proof order; ahead[0] belongs to the proof after the current one
+    int ahead_count = 0;
     // intermediates of the last single proof (debug)
     int dbg_mu = -1, dbg_delta = -1, dbg_nu = -1;
     uint64_t dbg_rx[IMM_MAX_ROUNDS], dbg_ry[IMM_MAX_ROUNDS], dbg_r[IMM_MAX_ROUNDS];
@@ -302,7 +318,69 @@ static int check_desc(const imm_matmul_desc& ds) {
 
 // a0..a4: transcript head on the host, then eq vectors, encoding and the two streaming partial
 // evaluations on the stream; leaves a[], b[] (zero-padded to D) in job.a / job.b.
-static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job) {
+static bool same_operands(const imm_matmul_desc& p, const imm_matmul_desc& q) {
+    return p.A_dev == q.A_dev && p.B_dev == q.B_dev && p.dtA == q.dtA && p.dtB == q.dtB && p.m == q.m && p.d == q.d &&
+           p.n == q.n;
+}
+
+// Forgets the tables queued ahead of time: the stream that writes them drains first, so that
+// whatever uses the buffers next finds them idle.  Every sequence ends with this, also when it ends
+// early: tables never outlive the call they were queued in, whose operands may change afterwards.
+static int ahead_drop(imm_ctx* ctx) {
+    if (!ctx->ahead_count) return IMM_OK;
+    ctx->ahead_count = 0;
+    IMM_HIP(hipStreamSynchronize(ctx->ahead_stream));
+    return IMM_OK;
+}
+
+// Queues the widening of the raw operands of the proofs that follow the current one (look[0] is the
+// next), as far as the ring reaches, each into a pair of tables that neither the current proof nor
+// a queued one uses: the proofs that read those pairs before have returned.  The encode kernels run
+// on a stream of their own, which starts once everything queued on s so far (the current proof's
+// streaming kernels) is done: they share the machine with round loops, which leave the memory
+// system idle, and with the streaming kernels of later proofs only as far as they fall behind.
+static int ahead_queue(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc* look, int count) {
+    if (count > imm_ctx::kAheadDepth) count = imm_ctx::kAheadDepth;
+    if (ctx->ahead_count >= count) return IMM_OK;
+    int rc;
+    if (!ctx->ahead_stream) {
+        IMM_HIP(hipStreamCreateWithFlags(&ctx->ahead_stream, hipStreamNonBlocking));
+        IMM_HIP(hipEventCreateWithFlags(&ctx->ahead_go, hipEventDisableTiming));
+        for (hipEvent_t& e : ctx->ahead_done) IMM_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    }
+    hipStream_t t = ctx->ahead_stream;
+    IMM_HIP(hipEventRecord(ctx->ahead_go, s));
+    IMM_HIP(hipStreamWaitEvent(t, ctx->ahead_go, 0));
+    for (int i = ctx->ahead_count; i < count; ++i) {
+        const imm_matmul_desc& next = look[i];
+        imm_ctx::Ahead& q = ctx->ahead[i];
+        q.ds = next;
+        q.hasA = next.dtA != IMM_F64P;
+        q.hasB = next.dtB != IMM_F64P;
+        q.set = (ctx->set + 1 + i) % imm_ctx::kTableSets;
+        const uint64_t m = next.m, d = next.d, n = next.n;
+        if (q.hasA) {
+            if ((rc = ctx->encA[q.set].ensure(sizeof(uint64_t) * m * d))) return rc;
+            if ((rc = ctx->prof.begin(IMM_K_ENCODE_A, t))) return rc;
+            IMM_HIP(k::encode(t, next.A_dev, (int)next.dtA, m * d, ctx->encA[q.set].u64()));
+            if ((rc = ctx->prof.end(IMM_K_ENCODE_A, t))) return rc;
+        }
+        if (q.hasB) {
+            if ((rc = ctx->encB[q.set].ensure(sizeof(uint64_t) * d * n))) return rc;
+            if ((rc = ctx->prof.begin(IMM_K_ENCODE_B, t))) return rc;
+            IMM_HIP(k::encode(t, next.B_dev, (int)next.dtB, d * n, ctx->encB[q.set].u64()));
+            if ((rc = ctx->prof.end(IMM_K_ENCODE_B, t))) return rc;
+        }
+        IMM_HIP(hipEventRecord(ctx->ahead_done[q.set], t));
+        ctx->ahead_count = i + 1;
+    }
+    return IMM_OK;
+}
+
+// look[0..look_count) are the proofs that follow this one on the same context in the same call:
+// their raw operands are widened while this proof and the ones between run.
+static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_desc* look = nullptr,
+                        int look_count = 0) {
     const imm_matmul_desc& ds = *job.ds;
     const uint64_t m = ds.m, d = ds.d, n = ds.n;
     job.mu = hf::ceil_log2(m);
@@ -324,20 +402,42 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job) {
     const void* Ap = ds.A_dev;
     const void* Bp = ds.B_dev;
     int dtA = (int)ds.dtA, dtB = (int)ds.dtB;
+    if (ctx->ahead_count) {
+        if (ctx->widen && same_operands(ctx->ahead[0].ds, ds)) {
+            // the tables were queued while the proofs before this one ran: take them over
+            const imm_ctx::Ahead q = ctx->ahead[0];
+            for (int i = 1; i < ctx->ahead_count; ++i) ctx->ahead[i - 1] = ctx->ahead[i];
+            ctx->ahead_count -= 1;
+            ctx->set = q.set;
+            IMM_HIP(hipStreamWaitEvent(s, ctx->ahead_done[q.set], 0));
+            if (q.hasA) {
+                Ap = ctx->encA[q.set].p;
+                dtA = IMM_F64P;
+            }
+            if (q.hasB) {
+                Bp = ctx->encB[q.set].p;
+                dtB = IMM_F64P;
+            }
+        } else if ((rc = ahead_drop(ctx))) {
+            return rc;
+        }
+    }
+    imm::DevBuf& encA = ctx->encA[ctx->set];
+    imm::DevBuf& encB = ctx->encB[ctx->set];
     if (ctx->widen && dtA != IMM_F64P) {
-        if ((rc = ctx->encA.ensure(sizeof(uint64_t) * m * d))) return rc;
+        if ((rc = encA.ensure(sizeof(uint64_t) * m * d))) return rc;
         if ((rc = ctx->prof.begin(IMM_K_ENCODE_A, s))) return rc;
-        IMM_HIP(k::encode(s, Ap, dtA, m * d, ctx->encA.u64()));
+        IMM_HIP(k::encode(s, Ap, dtA, m * d, encA.u64()));
         if ((rc = ctx->prof.end(IMM_K_ENCODE_A, s))) return rc;
-        Ap = ctx->encA.p;
+        Ap = encA.p;
         dtA = IMM_F64P;
     }
     if (ctx->widen && dtB != IMM_F64P) {
-        if ((rc = ctx->encB.ensure(sizeof(uint64_t) * d * n))) return rc;
+        if ((rc = encB.ensure(sizeof(uint64_t) * d * n))) return rc;
         if ((rc = ctx->prof.begin(IMM_K_ENCODE_B, s))) return rc;
-        IMM_HIP(k::encode(s, Bp, dtB, d * n, ctx->encB.u64()));
+        IMM_HIP(k::encode(s, Bp, dtB, d * n, encB.u64()));
         if ((rc = ctx->prof.end(IMM_K_ENCODE_B, s))) return rc;
-        Bp = ctx->encB.p;
+        Bp = encB.p;
         dtB = IMM_F64P;
     }
     // (only beside the narrow-read reduction of B: beside the widened table, ten times larger, A's
@@ -369,6 +469,7 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job) {
         if ((rc = partial_over_cols(ctx, s, IMM_K_REDUCE_B, Bp, dtB, d, n, n, ctx->eqy.u64(), D, ctx->partB, job.b)))
             return rc;
     }
+    if (look_count > 0 && ctx->widen && ctx->encode_ahead && (rc = ahead_queue(ctx, s, look, look_count))) return rc;
 
     std::memset(job.out, 0, sizeof(*job.out));
     job.out->version = IMM_PROOF_VERSION;
@@ -542,7 +643,8 @@ static int finish_one(imm_ctx* ctx, hipStream_t s, Job& job) {
     return rounds_with_device_transcript(ctx, s, job);
 }
 
-static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uint8_t state[32], imm_proof* out) {
+static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uint8_t state[32], imm_proof* out,
+                     const imm_matmul_desc* look = nullptr, int look_count = 0) {
     if (!state || !out) return IMM_E_NULL;
     int rc;
     if ((rc = check_desc(ds))) return rc;
@@ -555,7 +657,7 @@ static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uin
     if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
     job.a = ctx->a.u64();
     job.b = ctx->b.u64();
-    if ((rc = stream_phase(ctx, s, job))) return rc;
+    if ((rc = stream_phase(ctx, s, job, look, look_count))) return rc;
     if (ctx->debug) {
         if ((rc = ctx->snapA.ensure(sizeof(uint64_t) * D))) return rc;
         if ((rc = ctx->snapB.ensure(sizeof(uint64_t) * D))) return rc;
@@ -647,7 +749,7 @@ extern "C" int imm_ctx_create(imm_ctx** out, int device, size_t scratch_bytes) {
     ctx->replies = reply_block_take(device);  // may be null: then the mailbox carries the challenges
     if (scratch_bytes) {
         // the hint goes to the widened weight table, by far the largest scratch buffer
-        int rc = ctx->encB.ensure(scratch_bytes);
+        int rc = ctx->encB[0].ensure(scratch_bytes);
         if (rc) {
             (void)hipHostFree(ctx->pinned);
             (void)hipHostFree(ctx->mailbox);
@@ -663,7 +765,14 @@ extern "C" int imm_ctx_destroy(imm_ctx* ctx) {
     if (!ctx) return IMM_E_NULL;
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
-    for (DevBuf* bf : {&ctx->encA, &ctx->encB, &ctx->eqx, &ctx->eqy, &ctx->a, &ctx->b, &ctx->partA, &ctx->partB,
+    if (ctx->ahead_stream) {
+        (void)hipEventDestroy(ctx->ahead_go);
+        for (hipEvent_t e : ctx->ahead_done) (void)hipEventDestroy(e);
+        (void)hipStreamDestroy(ctx->ahead_stream);
+    }
+    for (DevBuf& bf : ctx->encA) bf.release();
+    for (DevBuf& bf : ctx->encB) bf.release();
+    for (DevBuf* bf : {&ctx->eqx, &ctx->eqy, &ctx->a, &ctx->b, &ctx->partA, &ctx->partB,
                        &ctx->round_scratch, &ctx->words, &ctx->snapA, &ctx->snapB, &ctx->group_tables,
                        &ctx->ldd_partial, &ctx->ldd_post, &ctx->ldd_sum, &ctx->ldd_arrive})
         bf->release();
@@ -681,6 +790,7 @@ extern "C" int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value) {
     case IMM_OPT_DEBUG_SNAPSHOTS: ctx->debug = value != 0; return IMM_OK;
     case IMM_OPT_WIDEN: ctx->widen = value != 0; return IMM_OK;
     case IMM_OPT_FUSE_REDUCTIONS: ctx->fuse_reductions = value != 0; return IMM_OK;
+    case IMM_OPT_ENCODE_AHEAD: ctx->encode_ahead = value != 0; return IMM_OK;
     case IMM_OPT_REPLY_IN_DEVICE_MEMORY: ctx->reply_in_device_memory = value != 0; return IMM_OK;
     case IMM_OPT_TRANSCRIPT:
         if (value != IMM_TRANSCRIPT_DEVICE && value != IMM_TRANSCRIPT_HOST) return IMM_E_SHAPE;
@@ -813,8 +923,11 @@ extern "C" int imm_sumcheck_matmul_prove_batch(imm_ctx* ctx, void* stream, int c
     }
     for (int t = 0; t < count; ++t) {
         if (!chained) std::memcpy(cur, start, 32);
-        int rc = prove_one(ctx, s, descs[t], cur, &outs_host[t]);
-        if (rc) return rc;
+        int rc = prove_one(ctx, s, descs[t], cur, &outs_host[t], descs + t + 1, count - t - 1);
+        if (rc) {
+            (void)ahead_drop(ctx);
+            return rc;
+        }
         if (states_out) std::memcpy(states_out + 32 * (size_t)t, cur, 32);
     }
     std::memcpy(transcript_state, cur, 32);

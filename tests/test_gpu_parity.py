@@ -392,6 +392,65 @@ def test_host_transcript_bounded_waits(torch, oracle_fast):
     c.close()
 
 
+def test_operands_of_the_next_proof_widened_ahead_or_not(torch, oracle_fast):
+    """In a sequence of proofs the next proof's raw operands are widened on a second stream while the
+    current proof's rounds run.  Same proofs and states with that switched off; with operands that
+    repeat (the activations shared by consecutive statements), that are pre-encoded, or that change
+    size from one proof to the next; and after a call that failed with tables queued that nobody takes."""
+    rng = np.random.default_rng(2024)
+    c = imm.Context(0)
+    shapes = [(40, 300, 64), (40, 300, 17), (40, 300, 64), (3, 5000, 129), (64, 64, 2048), (1, 2, 3), (9, 1, 4)]
+    A_shared = rng.integers(-2**15, 2**15, size=(40, 300), dtype=np.int16)
+    items, oracle_items = [], []
+    for t, (m, d, n) in enumerate(shapes):
+        A = A_shared if (m, d) == (40, 300) else rng.integers(-2**15, 2**15, size=(m, d), dtype=np.int16)
+        B = rng.integers(-128, 128, size=(d, n), dtype=np.int8)
+        C = oracle_fast.matmul(A, B)
+        com = imm.imm_commit_matmul(A, B, C, m, d, n)
+        oracle_items.append((A, B, C, com.digests()))
+        items.append([dev(torch, A), dev(torch, B), com])
+    shared = items[0][0]
+    for it in items[1:3]:
+        it[0] = shared                                   # the same device buffer, not a copy
+    items[4][1] = c.imm_encode(items[4][1])              # one weight table comes pre-encoded
+    items = [tuple(it) for it in items]
+    want, want_states = oracle_fast.prove_chain(oracle_items, chained=True)
+    try:
+        for ahead in (1, 0, 1):
+            c.imm_ctx_set_option(imm.IMM_OPT_ENCODE_AHEAD, ahead)
+            got, states, final = c.imm_sumcheck_matmul_prove_batch(items, True, ref.FS_INIT)
+            assert [p.words() for p in got] == [ref.proof_words(p) for p in want], ahead
+            assert states == want_states and final == want_states[-1]
+        # profiling sees the encode launches wherever they ran: 7 of A, 6 of B
+        c.imm_ctx_reset_profiling()
+        c.imm_ctx_set_profiling((1 << imm.IMM_K_COUNT) - 1)
+        c.imm_sumcheck_matmul_prove_batch(items, True, ref.FS_INIT)
+        c.imm_ctx_set_profiling(0)
+        assert c.imm_ctx_kernel_time(imm.IMM_K_ENCODE_A)[0] == 7 and c.imm_ctx_kernel_time(imm.IMM_K_ENCODE_B)[0] == 6
+        # a sequence that stops at its first proof (the round kernel gives up at once) leaves the second
+        # proof's tables queued; the next calls, for those operands or for others, are not disturbed
+        c.imm_ctx_set_option(imm.IMM_OPT_SPIN_LIMIT, 0)
+        c.imm_ctx_set_option(imm.IMM_OPT_HOST_WAIT_MS, 50)
+        with pytest.raises(imm.ImmError):
+            c.imm_sumcheck_matmul_prove_batch(items[3:5], True, ref.FS_INIT)
+        torch.cuda.synchronize()
+        c.imm_ctx_set_option(imm.IMM_OPT_SPIN_LIMIT, 1 << 21)
+        c.imm_ctx_set_option(imm.IMM_OPT_HOST_WAIT_MS, 30000)
+        got, s_got = c.imm_sumcheck_matmul_prove(items[0][0], items[0][1], items[0][2], ref.FS_INIT)
+        assert got.words() == ref.proof_words(want[0]) and s_got == want_states[0]
+        c.imm_ctx_set_option(imm.IMM_OPT_SPIN_LIMIT, 0)
+        c.imm_ctx_set_option(imm.IMM_OPT_HOST_WAIT_MS, 50)
+        with pytest.raises(imm.ImmError):
+            c.imm_sumcheck_matmul_prove_batch(items[0:2], True, ref.FS_INIT)
+        torch.cuda.synchronize()
+        c.imm_ctx_set_option(imm.IMM_OPT_SPIN_LIMIT, 1 << 21)
+        c.imm_ctx_set_option(imm.IMM_OPT_HOST_WAIT_MS, 30000)
+        got, states, final = c.imm_sumcheck_matmul_prove_batch(items[1:], True, want_states[0])
+        assert [p.words() for p in got] == [ref.proof_words(p) for p in want[1:]] and final == want_states[-1]
+    finally:
+        c.close()
+
+
 def test_argument_errors(torch, ctx):
     L = imm.load()
     A = torch.zeros((2, 2), dtype=torch.int16, device="cuda")
