@@ -68,7 +68,7 @@ struct Profiler {
     static constexpr size_t kPool = 1024;  // event pairs
     uint32_t mask = 0;
     std::vector<hipEvent_t> ev;
-    struct Rec { int id; size_t first; };
+    struct Rec { int id; size_t first; bool closed; };  // closed: the second event of the pair is recorded
     std::vector<Rec> recs;
     double total_ms[IMM_K_COUNT] = {};
     uint64_t launches[IMM_K_COUNT] = {};
@@ -85,27 +85,40 @@ struct Profiler {
             if (rc) return rc;
         }
         size_t first = 2 * recs.size();
-        recs.push_back({id, first});
+        recs.push_back({id, first, false});
         IMM_HIP(hipEventRecord(ev[first], s));
         return IMM_OK;
     }
     int end(int id, hipStream_t s) {
-        if (!wants(id) || recs.empty()) return IMM_OK;
+        if (!wants(id) || recs.empty() || recs.back().id != id) return IMM_OK;
         IMM_HIP(hipEventRecord(ev[recs.back().first + 1], s));
+        recs.back().closed = true;
         return IMM_OK;
     }
     void cancel(int id) {  // drops the pair opened by the last begin(id): nothing was launched after all
         if (wants(id) && !recs.empty()) recs.pop_back();
     }
+    // Adds up the pairs recorded so far and empties the list, whatever happens: a pair that a failed
+    // call left open, or whose events the runtime will not read, is dropped, not kept for the next flush.
     int flush() {
+        hipError_t bad = hipSuccess;
         for (const Rec& r : recs) {
-            IMM_HIP(hipEventSynchronize(ev[r.first + 1]));
+            if (!r.closed) continue;
             float ms = 0.f;
-            IMM_HIP(hipEventElapsedTime(&ms, ev[r.first], ev[r.first + 1]));
+            hipError_t e = hipEventSynchronize(ev[r.first + 1]);
+            if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev[r.first], ev[r.first + 1]);
+            if (e != hipSuccess) {
+                bad = e;
+                continue;
+            }
             total_ms[r.id] += ms;
             launches[r.id] += 1;
         }
         recs.clear();
+        if (bad != hipSuccess) {
+            (void)hipGetLastError();
+            return fail_hip(bad, "reading the profiling events");
+        }
         return IMM_OK;
     }
     void reset() {
