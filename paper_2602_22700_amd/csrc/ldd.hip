@@ -16,7 +16,6 @@ namespace k {
 namespace {
 
 constexpr int kLddBlock = 1024;
-constexpr int kLddWaves = kLddBlock / 64;
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -419,38 +418,56 @@ __global__ void fill_u32_kernel(uint32_t* p, uint64_t count, uint32_t v) {
 // a share is scattered over the row, so reading it again touches a cache line per four logits).
 constexpr int kTopkCap = 1024;  // candidate list capacity; beyond it the slow exact path is taken
 
-struct Cand {
-    float v;
-    int idx;
-};
+// A logit and its place as one sortable word: of two keys the larger comes first (the larger logit;
+// of equal logits the one with the smaller index; any fixed rule works, values decide the cost).
+// The upper half is monotone in v for every v that is not a NaN, and never zero; key 0 is "nothing".
+__device__ __forceinline__ uint64_t cand_key(float v, uint32_t idx) {
+    const uint32_t u = __float_as_uint(v);
+    const uint32_t ord = u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+    return (uint64_t)ord << 32 | (uint32_t)~idx;
+}
+__device__ __forceinline__ float key_value(uint64_t key) {
+    const uint32_t ord = (uint32_t)(key >> 32);
+    return __uint_as_float(ord ^ ((ord >> 31) ? 0x80000000u : 0xFFFFFFFFu));
+}
 
-// larger value first; equal values: smaller index first (any fixed rule works, values decide the cost)
+// the slow path's order: larger value first; equal values: smaller index first
 __device__ __forceinline__ bool cand_before(float va, int ia, float vb, int ib) {
     return va > vb || (va == vb && ia < ib);
 }
 
+// Workgroup shape of the top-K kernel: one row per workgroup, two workgroups per compute unit (while
+// one ranks its candidates the other streams).
+constexpr int kTopkBlock = 1024;
+constexpr int kTopkWaves = kTopkBlock / 64;
+constexpr int kTopkLoads = 8;           // 16-byte loads in flight per thread
+constexpr int kTopkWavesPerSimd = 8;    // at most 64 registers
+
 template <bool VEC>
-__global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* __restrict__ X, uint64_t n, uint64_t ld,
-                                                                  const int32_t* __restrict__ idx_all, uint32_t K,
-                                                                  double* __restrict__ out) {
-    __shared__ float ldsf[kLddWaves];
+__global__ __launch_bounds__(kTopkBlock, kTopkWavesPerSimd) void topk_distance_kernel(
+    const float* __restrict__ X, uint64_t n, uint64_t ld, const int32_t* __restrict__ idx_all, uint32_t K,
+    double* __restrict__ out) {
+    __shared__ float ldsf[kTopkWaves];
     __shared__ int member_idx[IMM_TOPK_MAX];
     __shared__ float member_val[IMM_TOPK_MAX];
-    __shared__ float top_out[IMM_TOPK_MAX];  // K largest non-members
-    __shared__ Cand cand[kTopkCap];
-    __shared__ unsigned char cand_member[kTopkCap];
-    __shared__ unsigned short hot[kLddBlock];  // threads whose share reaches tau
+    __shared__ uint64_t member_key[IMM_TOPK_MAX];  // key of a member on the candidate list, else 0
+    __shared__ float top_out[IMM_TOPK_MAX];        // K largest non-members
+    __shared__ uint64_t cand[kTopkCap];            // keys of the logits >= tau
+    __shared__ unsigned short hot[kTopkBlock];      // threads whose share holds more than one of them
     __shared__ int hot_count;
     __shared__ int cand_count;
     __shared__ int bad_row;
-    __shared__ double cost[2 * IMM_TOPK_MAX];
-    const float* x = X + (uint64_t)blockIdx.x * ld;
-    const int32_t* idx = idx_all + (uint64_t)blockIdx.x * K;
-    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    __shared__ double wave_best[kTopkWaves];
+    __shared__ float slow_v[kTopkWaves];
+    __shared__ int slow_i[kTopkWaves];
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint64_t n4 = VEC ? n >> 2 : 0;
     // a row with fewer than 2K entries has fewer than K non-members: then every entry is accounted for
     const uint32_t Kn = (n - K < K) ? (uint32_t)(n - K) : K;
 
+    const uint64_t row = blockIdx.x;
+    const float* x = X + row * ld;
+    const int32_t* idx = idx_all + row * K;
     if (tid == 0) { cand_count = 0; hot_count = 0; bad_row = 0; }
     __syncthreads();
     if (tid < K) {
@@ -469,8 +486,8 @@ __global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* _
             if (member_idx[j] == member_idx[tid]) bad_row = 1;
 
     // pass 1 (HBM): the two largest logits of the thread's share and where the largest one sits,
-    // eight loads in flight per thread.  A position is a group of four (VEC), one of the up to three
-    // logits after the last whole group (VEC, numbered from n4 on), or a single logit.
+    // kTopkLoads loads in flight per thread.  A position is a group of four (VEC), one of the up to
+    // three logits after the last whole group (VEC, numbered from n4 on), or a single logit.
     float tmax = -INFINITY, second = -INFINITY;
     uint32_t at = 0;
     auto take = [&](float v) { second = __builtin_amdgcn_fmed3f(tmax, second, v); tmax = fmaxf(tmax, v); };
@@ -480,24 +497,24 @@ __global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* _
         at = tmax > before ? (uint32_t)pos : at;
     };
     uint64_t g = tid;
-    for (; g + 7 * (uint64_t)kLddBlock < n4; g += 8 * (uint64_t)kLddBlock) {
-        v4f q[8];
+    for (; g + (kTopkLoads - 1) * (uint64_t)kTopkBlock < n4; g += kTopkLoads * (uint64_t)kTopkBlock) {
+        v4f q[kTopkLoads];
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            q[j] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(x + 4 * (g + (uint64_t)kLddBlock * j)));
+        for (int j = 0; j < kTopkLoads; ++j)
+            q[j] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(x + 4 * (g + (uint64_t)kTopkBlock * j)));
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) take4(q[j], g + (uint64_t)kLddBlock * j);
+        for (int j = 0; j < kTopkLoads; ++j) take4(q[j], g + (uint64_t)kTopkBlock * j);
     }
-    for (; g < n4; g += kLddBlock) take4(*reinterpret_cast<const v4f*>(x + 4 * g), g);
-    for (uint64_t i = 4 * n4 + tid; i < n; i += kLddBlock) {
+    for (; g < n4; g += kTopkBlock) take4(*reinterpret_cast<const v4f*>(x + 4 * g), g);
+    for (uint64_t i = 4 * n4 + tid; i < n; i += kTopkBlock) {
         const float before = tmax;
         take(x[i]);
         at = tmax > before ? (uint32_t)(VEC ? n4 + (i - 4 * n4) : i) : at;
     }
 
     // r-th largest thread maximum of this wave (ties between lanes broken by lane number)
-    const uint32_t r = (2 * K + kLddWaves - 1) / kLddWaves;
+    const uint32_t r = (2 * K + kTopkWaves - 1) / kTopkWaves;
     float cur = tmax;     // candidates still in play in this lane
     float rth = -INFINITY;
     for (uint32_t it = 0; it < r; ++it) {
@@ -510,92 +527,95 @@ __global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* _
         const uint32_t first = (uint32_t)__builtin_ctzll(holders);
         if (lane == first) cur = -INFINITY;
     }
-    if (lane == 0) ldsf[tid >> 6] = rth;
+    if (lane == 0) ldsf[wave] = rth;
     __syncthreads();
     float tau = ldsf[0];
 #pragma unroll
-    for (int w = 1; w < kLddWaves; ++w) tau = fminf(tau, ldsf[w]);
+    for (int w = 1; w < kTopkWaves; ++w) tau = fminf(tau, ldsf[w]);
 
     // pass 2: only threads whose maximum reaches tau can own a logit >= tau.  Most of them own just
-    // that one (their second largest is below tau) and know where it sits.  The few that own more put
-    // their names on a list, and the whole workgroup goes through the shares of the listed threads
-    // together, one (owner, position) pair per thread at a time, so that this re-read costs one
-    // round trip, not one per position of a share.
-    if (tmax >= tau) {
-        if (second >= tau) {
-            hot[atomicAdd(&hot_count, 1)] = (unsigned short)tid;
-        } else {
-            uint64_t where = at;
-            if (VEC) {
-                if (at < n4) {
-                    const v4f q = *reinterpret_cast<const v4f*>(x + 4 * (uint64_t)at);
-                    where = 4 * (uint64_t)at + (q.x == tmax ? 0 : q.y == tmax ? 1 : q.z == tmax ? 2 : 3);
-                } else {
-                    where = 4 * n4 + (at - n4);
-                }
-            }
-            const int slot = atomicAdd(&cand_count, 1);
-            if (slot < kTopkCap) { cand[slot].v = tmax; cand[slot].idx = (int)where; }
-        }
-    }
+    // that one (their second largest is below tau) and know where it sits, up to its place in a group
+    // of four.  The few that own more put their names on a list, and the whole workgroup goes through
+    // the shares of the listed threads together, one (owner, position) pair per thread at a time.  All
+    // these reads are in flight together: the second look at the row costs one round trip.
+    auto push = [&](float v, uint64_t where) {
+        const int slot = atomicAdd(&cand_count, 1);
+        if (slot < kTopkCap) cand[slot] = cand_key(v, (uint32_t)where);
+    };
+    const bool reaches = tmax >= tau;
+    const bool crowded = reaches && second >= tau;
+    if (crowded) hot[atomicAdd(&hot_count, 1)] = (unsigned short)tid;
+    // a member is on the candidate list exactly when its logit reaches tau
+    if (tid < K) member_key[tid] = member_val[tid] >= tau ? cand_key(member_val[tid], (uint32_t)member_idx[tid]) : 0;
     __syncthreads();
+    const bool alone = reaches && !crowded;
     if constexpr (VEC) {
-        const uint64_t per_owner = (n4 + kLddBlock - 1) / kLddBlock;
+        v4f own = {};
+        if (alone && at < n4) own = *reinterpret_cast<const v4f*>(x + 4 * (uint64_t)at);
+        const uint64_t tail_i = 4 * n4 + tid;  // the up to three logits after the last whole group
+        const float tail_v = tail_i < n && hot_count ? x[tail_i] : -INFINITY;
+        const uint64_t per_owner = (n4 + kTopkBlock - 1) / kTopkBlock;
         const uint64_t items = (uint64_t)hot_count * per_owner;
-        for (uint64_t w = tid; w < items; w += kLddBlock) {
-            const uint64_t u = hot[w / per_owner] + (uint64_t)kLddBlock * (w % per_owner);
+        for (uint64_t w = tid; w < items; w += kTopkBlock) {
+            const uint32_t owner = hot[w / per_owner];
+            const uint64_t u = owner + (uint64_t)kTopkBlock * (w % per_owner);
             if (u >= n4) continue;
             const v4f q = *reinterpret_cast<const v4f*>(x + 4 * u);
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (q[j] >= tau) {
-                    const int slot = atomicAdd(&cand_count, 1);
-                    if (slot < kTopkCap) { cand[slot].v = q[j]; cand[slot].idx = (int)(4 * u + j); }
-                }
+                if (q[j] >= tau) push(q[j], 4 * u + j);
         }
-        const uint64_t i = 4 * n4 + tid;  // the up to three logits after the last whole group
-        if (i < n && x[i] >= tau) {
-            const int slot = atomicAdd(&cand_count, 1);
-            if (slot < kTopkCap) { cand[slot].v = x[i]; cand[slot].idx = (int)i; }
+        // a listed thread's share of the last logits (a thread not listed knows where its only one sits)
+        if (tail_v >= tau) {
+            bool listed = false;
+            for (int h = 0; h < hot_count; ++h) listed |= hot[h] == tid;
+            if (listed) push(tail_v, tail_i);
+        }
+        if (alone) {
+            if (at < n4)
+                push(tmax, 4 * (uint64_t)at + (own.x == tmax ? 0 : own.y == tmax ? 1 : own.z == tmax ? 2 : 3));
+            else
+                push(tmax, 4 * n4 + (at - n4));
         }
     } else {
-        const uint64_t per_owner = (n + kLddBlock - 1) / kLddBlock;
+        const uint64_t per_owner = (n + kTopkBlock - 1) / kTopkBlock;
         const uint64_t items = (uint64_t)hot_count * per_owner;
-        for (uint64_t w = tid; w < items; w += kLddBlock) {
-            const uint64_t i = hot[w / per_owner] + (uint64_t)kLddBlock * (w % per_owner);
+        for (uint64_t w = tid; w < items; w += kTopkBlock) {
+            const uint64_t i = hot[w / per_owner] + (uint64_t)kTopkBlock * (w % per_owner);
             if (i >= n) continue;
             const float v = x[i];
-            if (v >= tau) {
-                const int slot = atomicAdd(&cand_count, 1);
-                if (slot < kTopkCap) { cand[slot].v = v; cand[slot].idx = (int)i; }
-            }
+            if (v >= tau) push(v, i);
         }
+        if (alone) push(tmax, at);
     }
     __syncthreads();
     const int c = cand_count;
 
     if (c <= kTopkCap) {
-        for (int i = tid; i < c; i += kLddBlock) {
-            bool is_member = false;
-            for (uint32_t j = 0; j < K; ++j) is_member |= (member_idx[j] == cand[i].idx);
-            cand_member[i] = is_member ? 1 : 0;
-        }
-        __syncthreads();
-        // Rank of every non-member candidate among the non-member candidates; ranks < Kn are the answer.
+        // Rank of every candidate among the candidates that are not members: the number of keys ahead of
+        // its own on the list, less the number of members' keys ahead of it; ranks < Kn are the answer.
         // `per` neighbouring lanes share the comparisons of one candidate.
         uint32_t per = 1;
-        while (per < 64 && 2 * per * (uint32_t)c <= (uint32_t)kLddBlock) per *= 2;
-        for (uint32_t base = 0; base < (uint32_t)c; base += kLddBlock / per) {
+        while (per < 64 && 2 * per * (uint32_t)c <= (uint32_t)kTopkBlock) per *= 2;
+        for (uint32_t base = 0; base < (uint32_t)c; base += kTopkBlock / per) {
             const uint32_t i = base + tid / per, sub = tid % per;
-            const bool mine = i < (uint32_t)c && !cand_member[i];
-            const float v = mine ? cand[i].v : 0.f;
-            const int id = mine ? cand[i].idx : 0;
-            uint32_t rank = 0;
-            if (mine)
-                for (uint32_t j = sub; j < (uint32_t)c; j += per)
-                    rank += (!cand_member[j] && cand_before(cand[j].v, cand[j].idx, v, id)) ? 1u : 0u;
-            for (uint32_t off = per >> 1; off > 0; off >>= 1) rank += __shfl_xor(rank, off, 64);
-            if (mine && sub == 0 && rank < Kn) top_out[rank] = v;
+            const uint64_t mine = i < (uint32_t)c ? cand[i] : 0;
+            uint32_t ahead = 0, members_ahead = 0, is_member = 0;
+#pragma unroll 4
+            for (uint32_t j = sub; j < (uint32_t)c; j += per) ahead += cand[j] > mine ? 1u : 0u;
+#pragma unroll 4
+            for (uint32_t j = sub; j < K; j += per) {
+                const uint64_t mk = member_key[j];
+                members_ahead += mk > mine ? 1u : 0u;
+                is_member |= mk == mine ? 1u : 0u;
+            }
+            for (uint32_t off = per >> 1; off > 0; off >>= 1) {
+                ahead += __shfl_xor(ahead, off, 64);
+                members_ahead += __shfl_xor(members_ahead, off, 64);
+                is_member |= __shfl_xor(is_member, off, 64);
+            }
+            const uint32_t rank = ahead - members_ahead;
+            if (i < (uint32_t)c && sub == 0 && !is_member && rank < Kn) top_out[rank] = key_value(mine);
         }
     } else {
         // More logits tie at (or crowd above) tau than the list holds: exact but slow path, K rounds
@@ -605,7 +625,7 @@ __global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* _
         for (uint32_t pick = 0; pick < Kn; ++pick) {
             float bv = -INFINITY;
             int bi = 0x7FFFFFFF;
-            for (uint64_t i = tid; i < n; i += kLddBlock) {
+            for (uint64_t i = tid; i < n; i += kTopkBlock) {
                 const float v = x[i];
                 if (!cand_before(last_v, last_i, v, (int)i)) continue;       // already picked or before it
                 bool is_member = false;
@@ -619,12 +639,12 @@ __global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* _
                 const int oi = __shfl_xor(bi, off, 64);
                 if (cand_before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
             }
-            __syncthreads();  // cand[] is free to be reused as per-wave scratch
-            if (lane == 0) { cand[tid >> 6].v = bv; cand[tid >> 6].idx = bi; }
+            __syncthreads();  // the previous pick's scratch has been read by everyone
+            if (lane == 0) { slow_v[wave] = bv; slow_i[wave] = bi; }
             __syncthreads();
-            bv = cand[0].v; bi = cand[0].idx;
-            for (int w = 1; w < kLddWaves; ++w)
-                if (cand_before(cand[w].v, cand[w].idx, bv, bi)) { bv = cand[w].v; bi = cand[w].idx; }
+            bv = slow_v[0]; bi = slow_i[0];
+            for (int w = 1; w < kTopkWaves; ++w)
+                if (cand_before(slow_v[w], slow_i[w], bv, bi)) { bv = slow_v[w]; bi = slow_i[w]; }
             if (tid == 0) top_out[pick] = bv;
             last_v = bv;
             last_i = bi;
@@ -632,23 +652,26 @@ __global__ __launch_bounds__(kLddBlock) void topk_distance_kernel(const float* _
     }
     __syncthreads();
 
-    // cost of each candidate threshold (with K non-members in hand, thresholds below v_K are never better)
-    if (tid < 2 * K) {
-        const bool usable = tid < K ? tid < Kn : true;
-        const float t = tid < K ? (usable ? top_out[tid] : 0.f) : member_val[tid - K];
-        double f = INFINITY;
-        if (usable && (Kn < K || t >= top_out[K - 1])) {
-            f = 0;
-            for (uint32_t j = 0; j < Kn; ++j) f += fmax((double)top_out[j] - (double)t, 0.0);
-            for (uint32_t j = 0; j < K; ++j) f += fmax((double)t - (double)member_val[j], 0.0);
-        }
-        cost[tid] = f;
+    // Cost of each candidate threshold (with K non-members in hand, thresholds below v_K are never
+    // better).  Lane l holds v_l and w_l; the waves share out the 2K thresholds, each a sum over the lanes.
+    const bool has_v = lane < Kn, has_w = lane < K;
+    const double v_l = has_v ? (double)top_out[lane] : 0.0;
+    const double w_l = has_w ? (double)member_val[lane] : 0.0;
+    double best = INFINITY;
+    for (uint32_t t_ix = wave; t_ix < 2 * K; t_ix += kTopkWaves) {
+        if (t_ix < K && t_ix >= Kn) continue;
+        const float t = t_ix < K ? top_out[t_ix] : member_val[t_ix - K];
+        if (Kn == K && t < top_out[K - 1]) continue;
+        const double f = (has_v ? fmax(v_l - (double)t, 0.0) : 0.0) + (has_w ? fmax((double)t - w_l, 0.0) : 0.0);
+        best = fmin(best, wave_all_sum(f));
     }
+    if (lane == 0) wave_best[wave] = best;
     __syncthreads();
-    if (tid == 0) {
-        double best = cost[0];
-        for (uint32_t j = 1; j < 2 * K; ++j) best = fmin(best, cost[j]);
-        out[blockIdx.x] = bad_row ? (double)NAN : best;
+    if (wave == 0) {
+        best = lane < kTopkWaves ? wave_best[lane] : INFINITY;
+#pragma unroll
+        for (int off = kTopkWaves / 2; off > 0; off >>= 1) best = fmin(best, __shfl_xor(best, off, 64));
+        if (lane == 0) out[row] = bad_row ? (double)NAN : best;
     }
 }
 
@@ -711,11 +734,12 @@ hipError_t ldd_tv_kl(hipStream_t stream, const float* X, const float* Y, uint64_
 
 hipError_t topk_distance(hipStream_t stream, const float* X, uint64_t T, uint64_t n, uint64_t ld, const int32_t* idx,
                          uint32_t K, double* out) {
+    if (T == 0) return hipSuccess;
     if (n >= 4 && vec_ok(X, ld))
-        hipLaunchKernelGGL((topk_distance_kernel<true>), dim3((unsigned)T), dim3(kLddBlock), 0, stream, X, n, ld, idx, K,
+        hipLaunchKernelGGL((topk_distance_kernel<true>), dim3((unsigned)T), dim3(kTopkBlock), 0, stream, X, n, ld, idx, K,
                            out);
     else
-        hipLaunchKernelGGL((topk_distance_kernel<false>), dim3((unsigned)T), dim3(kLddBlock), 0, stream, X, n, ld, idx,
+        hipLaunchKernelGGL((topk_distance_kernel<false>), dim3((unsigned)T), dim3(kTopkBlock), 0, stream, X, n, ld, idx,
                            K, out);
     return hipGetLastError();
 }

@@ -219,6 +219,33 @@ def test_topk_distance_ties_beyond_the_candidate_list(torch, ctx):
     assert got[0] == 0.0 and got[3] == 0.0
 
 
+def test_topk_distance_row_ends_that_are_not_a_whole_group_of_four(torch, ctx):
+    """Aligned storage, row length not a multiple of four: the vector path with up to three logits
+    after the last whole group, which here are among the largest of the row, members or not, alone in
+    their thread's share above the cut or not."""
+    rng = np.random.default_rng(31)
+    for n in (131, 4097, 4098, 4099, 70003):
+        K = 20
+        ld = (n + 3) // 4 * 4 + 4
+        x = (4 * rng.standard_normal((8, n))).astype(np.float32)
+        x[0, n - 1] = 40.0                                   # the largest, at the very end
+        x[1, n - 3:] = (41.0, 39.0, 42.0)
+        x[2, n - 2] = 40.0
+        t = (n - 2) - 4 * (n // 4)                           # the thread that owns that logit, if it is past the groups
+        if t >= 0:
+            x[2, 4 * t] = 39.0                               # the same thread's share also holds a large one
+        x[3, n - 1] = x[3].max()                             # a tie with the row's maximum
+        x[4, n - 3:] = -50.0                                 # and the smallest
+        idx = perturbed_sets(x, K, seed=n)
+        idx[5] = workloads.topk_indices(x[5:6], K)[0]
+        idx[0] = workloads.topk_indices(x[0:1], K)[0]        # the end is a member ...
+        idx[1] = np.setdiff1d(np.arange(n), [n - 1, n - 2, n - 3])[rng.choice(n - 3, size=K, replace=False)]  # ... or not
+        wide = torch.zeros((8, ld), dtype=torch.float32, device="cuda")
+        wide[:, :n] = torch.from_numpy(x).cuda()
+        got = check_topk(torch, ctx, x, idx, x_dev=wide[:, :n])
+        assert got[0] == 0.0 and got[5] == 0.0
+
+
 def test_topk_distance_unaligned_rows(torch, ctx):
     dep, _ = workloads.logits_pair(5, 3001, seed=12)
     wide = torch.zeros((5, 3003), dtype=torch.float32, device="cuda")
