@@ -129,6 +129,27 @@ int imm_fs_init(uint8_t state[32]);
 int imm_commit_matmul(const int16_t* A, const int8_t* B, const int64_t* C,
                       uint64_t m, uint64_t d, uint64_t n, imm_commit* out);
 
+/* One table to commit from device memory: rows x cols raw integers of type dtype (IMM_I8, IMM_I16
+ * or IMM_I64), row-major without gaps between rows, at a 4-byte aligned DEVICE address. */
+typedef struct imm_table_desc {
+    const void* table_dev;
+    uint32_t dtype;
+    uint32_t _pad;
+    uint64_t rows, cols;
+} imm_table_desc;
+
+/* The same commitments as imm_commit_matmul (paper section 2.1; same bytes), for `count` tables that
+ * live in device memory: every 1 MiB leaf of every table is hashed by one GPU lane, all in one
+ * launch on `stream`; the leaf digests come back to the host, which hashes each table's header and
+ * leaf digests into out_host[t] (HOST, count entries).  A hash chain is sequential, so the launch
+ * takes about 28 ms however few leaves there are, and as long as they fit the chip's 65536 lanes:
+ * it pays from roughly five hundred leaves (half a GiB) on, e.g. the activations and products of
+ * all statements of a request at once; for single matrices imm_commit_matmul on the host is faster.
+ * Synchronises `stream`.  Errors: IMM_E_NULL, IMM_E_SHAPE (count < 0, a zero or too large
+ * dimension, a misaligned address, more than 2^22 leaves in all), IMM_E_DTYPE, IMM_E_NOMEM, IMM_E_HIP. */
+int imm_commit_tables_device(imm_ctx* ctx, void* stream, int count, const imm_table_desc* tables,
+                             imm_commit1* out_host);
+
 /* Field-encoding pass: dst[i] = src[i] mod p for `count` elements.
  * src: DEVICE, dtype IMM_I8 / IMM_I16 / IMM_I64.  dst: DEVICE, count x uint64_t.
  * Asynchronous on `stream`.  Used to widen weights once at deployment so that
@@ -284,7 +305,8 @@ int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value);
 #define IMM_K_COMBINE 6    /* sum of per-split partial vectors */
 #define IMM_K_LDD 7        /* TV / KL distances of the logits */
 #define IMM_K_TOPK 8       /* top-K distance */
-#define IMM_K_COUNT 9
+#define IMM_K_COMMIT 9     /* leaf hashing of imm_commit_tables_device */
+#define IMM_K_COUNT 10
 /* mask: bit k set = time kernel id k (0 = profiling off). */
 int imm_ctx_set_profiling(imm_ctx* ctx, uint32_t mask);
 /* Sum of durations (ms) and number of launches since the last reset. */

@@ -24,17 +24,18 @@ IMM_OPT_FUSE_REDUCTIONS = 7
 IMM_OPT_ENCODE_AHEAD = 8
 IMM_TRANSCRIPT_DEVICE, IMM_TRANSCRIPT_HOST = 0, 1
 (IMM_K_ENCODE_A, IMM_K_ENCODE_B, IMM_K_EQ, IMM_K_REDUCE_A, IMM_K_REDUCE_B, IMM_K_ROUND,
- IMM_K_COMBINE, IMM_K_LDD, IMM_K_TOPK, IMM_K_COUNT) = range(10)
+ IMM_K_COMBINE, IMM_K_LDD, IMM_K_TOPK, IMM_K_COMMIT, IMM_K_COUNT) = range(11)
 IMM_TOPK_MAX = 64
 IMM_OK, IMM_E_NULL, IMM_E_SHAPE, IMM_E_DTYPE, IMM_E_NOMEM, IMM_E_HIP, IMM_E_STATE = 0, -1, -2, -3, -4, -5, -6
 KERNEL_NAMES = ["encode_A", "encode_B", "eq_build", "reduce_A", "reduce_B", "round", "combine", "ldd_tv_kl",
-                "topk_distance"]
+                "topk_distance", "commit_leaves"]
 
 EXPORTS = [
     "imm_ctx_create", "imm_ctx_destroy", "imm_last_error", "imm_fs_init", "imm_commit_matmul", "imm_encode",
     "imm_mle_eval", "imm_sumcheck_matmul_prove", "imm_sumcheck_matmul_prove_batch", "imm_round_fold_eval",
     "imm_verify", "imm_debug_fetch", "imm_ctx_set_option", "imm_ctx_set_profiling", "imm_ctx_kernel_time",
     "imm_ctx_reset_profiling", "imm_ldd_tv_kl", "imm_topk_distance", "imm_tail_density",
+    "imm_commit_tables_device",
 ]
 
 
@@ -47,6 +48,11 @@ class ImmError(RuntimeError):
 class Commit1(ctypes.Structure):
     _fields_ = [("digest", ctypes.c_uint8 * 32), ("rows", ctypes.c_uint64), ("cols", ctypes.c_uint64),
                 ("dtype", ctypes.c_uint32), ("_pad", ctypes.c_uint32)]
+
+
+class TableDesc(ctypes.Structure):
+    _fields_ = [("table_dev", ctypes.c_void_p), ("dtype", ctypes.c_uint32), ("_pad", ctypes.c_uint32),
+                ("rows", ctypes.c_uint64), ("cols", ctypes.c_uint64)]
 
 
 class Commit(ctypes.Structure):
@@ -113,6 +119,7 @@ def load() -> ctypes.CDLL:
     L.imm_ldd_tv_kl.argtypes = [vp, vp, vp, vp, u64, u64, u64, vp, vp]
     L.imm_topk_distance.argtypes = [vp, vp, vp, u64, u64, u64, vp, u32, vp]
     L.imm_tail_density.argtypes = [vp, vp, vp, u64, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
+    L.imm_commit_tables_device.argtypes = [vp, vp, i32, ctypes.POINTER(TableDesc), ctypes.POINTER(Commit1)]
     for name in EXPORTS:
         if name != "imm_last_error":
             getattr(L, name).restype = i32
@@ -316,6 +323,24 @@ class Context:
                                      ctypes.byref(out))
         _check(rc, "imm_tail_density")
         return out.value
+
+    def imm_commit_tables_device(self, tables, stream=None) -> List[Commit1]:
+        """tables: contiguous 2-D device tensors of int8 / int16 / int64.  Returns one Commit1 per table."""
+        count = len(tables)
+        descs = (TableDesc * max(count, 1))()
+        for t, tab in enumerate(tables):
+            assert tab.is_cuda and tab.dim() == 2 and tab.is_contiguous()
+            descs[t].table_dev, descs[t].dtype = tab.data_ptr(), _tensor_dtype(tab)
+            descs[t].rows, descs[t].cols = tab.shape
+        out = (Commit1 * max(count, 1))()
+        rc = load().imm_commit_tables_device(self._h, _stream_handle(stream), count, descs, out)
+        _check(rc, "imm_commit_tables_device")
+        res = []
+        for t in range(count):
+            c = Commit1()
+            ctypes.memmove(ctypes.byref(c), ctypes.byref(out[t]), ctypes.sizeof(Commit1))
+            res.append(c)
+        return res
 
     def prepare_batch(self, items, chained: bool, state: bytes, stream=None) -> "PreparedBatch":
         """Marshal a batch once; PreparedBatch.run() then only performs the C call."""

@@ -5,6 +5,7 @@
 #include <mutex>
 #include <emmintrin.h>
 
+#include <algorithm>
 #include <atomic>
 #include <chrono>
 #include <cstdio>
@@ -15,7 +16,9 @@
 #include "../../include/imm.h"
 #include "host_field.h"
 #include "kernels.h"
+#include "commit_leaves.h"
 #include "ldd.h"
+#include "sha256.h"
 #include "transcript.h"
 
 namespace imm {
@@ -176,7 +179,7 @@ static inline void reply_store(uint64_t* slot, uint64_t v) {
 struct imm_ctx {
     int device = 0;
     imm::DevBuf eqx, eqy, a, b, partA, partB, round_scratch, words, snapA, snapB, group_tables,
-        ldd_partial, ldd_post, ldd_sum, ldd_arrive;
+        ldd_partial, ldd_post, ldd_sum, ldd_arrive, commit_leaves, commit_digests;
     uint64_t* pinned = nullptr;  // host staging, 4 KiB
     imm::k::Mailbox* mailbox = nullptr;  // pinned + coherent, kRoundsMaxJobs of them: g_k out, r_k in
     uint64_t* replies = nullptr;         // host-writable device memory for r_k, or null (then the mailbox carries them)
@@ -787,7 +790,8 @@ extern "C" int imm_ctx_destroy(imm_ctx* ctx) {
     for (DevBuf& bf : ctx->encB) bf.release();
     for (DevBuf* bf : {&ctx->eqx, &ctx->eqy, &ctx->a, &ctx->b, &ctx->partA, &ctx->partB,
                        &ctx->round_scratch, &ctx->words, &ctx->snapA, &ctx->snapB, &ctx->group_tables,
-                       &ctx->ldd_partial, &ctx->ldd_post, &ctx->ldd_sum, &ctx->ldd_arrive})
+                       &ctx->ldd_partial, &ctx->ldd_post, &ctx->ldd_sum, &ctx->ldd_arrive, &ctx->commit_leaves,
+                       &ctx->commit_digests})
         bf->release();
     ctx->prof.destroy();
     reply_block_give(ctx->device, ctx->replies);
@@ -1043,4 +1047,67 @@ extern "C" int imm_tail_density(imm_ctx* ctx, void* stream, const double* dist_d
     if ((rc = fetch_words(ctx, s, ctx->words.u64(), 1, &count))) return rc;
     *out_host = (double)count / (double)T;
     return IMM_OK;
+}
+
+// ------------------------------------------------------------------ commitments from device memory
+extern "C" int imm_commit_tables_device(imm_ctx* ctx, void* stream, int count, const imm_table_desc* tables,
+                                        imm_commit1* out_host) {
+    using namespace imm;
+    if (!ctx || (count > 0 && (!tables || !out_host))) return IMM_E_NULL;
+    if (count < 0) return IMM_E_SHAPE;
+    if (count == 0) return IMM_OK;
+    constexpr uint64_t kLeafBytes = 1ull << 20, kMaxLeaves = 1ull << 22;
+    const uint64_t lim = 1ull << IMM_MAX_ROUNDS;
+    std::vector<k::LeafDesc> leaves;
+    std::vector<uint64_t> first(count + 1, 0);  // first[t]: index of table t's first leaf
+    bool aligned16 = true;
+    for (int t = 0; t < count; ++t) {
+        const imm_table_desc& d = tables[t];
+        if (!d.table_dev) return IMM_E_NULL;
+        if (d.rows == 0 || d.cols == 0 || d.rows > lim || d.cols > lim) return IMM_E_SHAPE;
+        const uint64_t elem = d.dtype == IMM_I8 ? 1 : d.dtype == IMM_I16 ? 2 : d.dtype == IMM_I64 ? 8 : 0;
+        if (!elem) return IMM_E_DTYPE;
+        const uintptr_t addr = reinterpret_cast<uintptr_t>(d.table_dev);
+        if (addr % 4) return IMM_E_SHAPE;
+        aligned16 = aligned16 && addr % 16 == 0;
+        const uint64_t bytes = d.rows * d.cols * elem;  // < 2^53
+        const uint64_t n = (bytes + kLeafBytes - 1) / kLeafBytes;
+        first[t + 1] = first[t] + n;
+        if (first[t + 1] > kMaxLeaves) return IMM_E_SHAPE;
+        for (uint64_t i = 0; i < n; ++i)
+            leaves.push_back({static_cast<const uint8_t*>(d.table_dev) + i * kLeafBytes,
+                              std::min(kLeafBytes, bytes - i * kLeafBytes)});
+    }
+    IMM_HIP(hipSetDevice(ctx->device));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc;
+    const size_t total = leaves.size();
+    if ((rc = ctx->commit_leaves.ensure(sizeof(k::LeafDesc) * total))) return rc;
+    if ((rc = ctx->commit_digests.ensure(32 * total))) return rc;
+    // (the descriptors are in pageable memory: the copy has left `leaves` when the call returns)
+    IMM_HIP(hipMemcpyAsync(ctx->commit_leaves.p, leaves.data(), sizeof(k::LeafDesc) * total, hipMemcpyHostToDevice, s));
+    if ((rc = ctx->prof.begin(IMM_K_COMMIT, s))) return rc;
+    IMM_HIP(k::commit_leaves(s, static_cast<const k::LeafDesc*>(ctx->commit_leaves.p), (uint32_t)total, aligned16,
+                             static_cast<uint8_t*>(ctx->commit_digests.p)));
+    if ((rc = ctx->prof.end(IMM_K_COMMIT, s))) return rc;
+    std::vector<uint8_t> digests(32 * total);
+    IMM_HIP(hipMemcpyAsync(digests.data(), ctx->commit_digests.p, digests.size(), hipMemcpyDeviceToHost, s));
+    IMM_HIP(hipStreamSynchronize(s));
+    for (int t = 0; t < count; ++t) {
+        const imm_table_desc& d = tables[t];
+        Sha256 top;
+        uint8_t hdr[13 + 4 + 8 + 8];
+        std::memcpy(hdr, "IMM-COMMIT-v1", 13);
+        for (int i = 0; i < 4; ++i) hdr[13 + i] = (uint8_t)(d.dtype >> (8 * i));
+        for (int i = 0; i < 8; ++i) hdr[17 + i] = (uint8_t)(d.rows >> (8 * i));
+        for (int i = 0; i < 8; ++i) hdr[25 + i] = (uint8_t)(d.cols >> (8 * i));
+        top.update(hdr, sizeof(hdr));
+        top.update(digests.data() + 32 * first[t], 32 * (size_t)(first[t + 1] - first[t]));
+        top.finish(out_host[t].digest);
+        out_host[t].rows = d.rows;
+        out_host[t].cols = d.cols;
+        out_host[t].dtype = d.dtype;
+        out_host[t]._pad = 0;
+    }
+    return ctx->prof.mask ? ctx->prof.flush() : IMM_OK;
 }

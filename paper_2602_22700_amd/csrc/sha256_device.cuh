@@ -46,10 +46,10 @@ __device__ __noinline__ State compress_fn(State st, Block bl) {
             w[t & 15] = w[t & 15] + s0 + w[(t - 7) & 15] + s1;
         }
         uint32_t S1 = xor3(rotr(e, 6), rotr(e, 11), rotr(e, 25));
-        uint32_t ch = (e & f) ^ (~e & g);
+        uint32_t ch = __builtin_amdgcn_bitop3_b32(e, f, g, 0xCA);   // e ? f : g
         uint32_t t1 = hh + S1 + ch + K[t] + w[t & 15];
         uint32_t S0 = xor3(rotr(a, 2), rotr(a, 13), rotr(a, 22));
-        uint32_t mj = (a & b) ^ (a & c) ^ (b & c);
+        uint32_t mj = __builtin_amdgcn_bitop3_b32(a, b, c, 0xE8);   // majority
         uint32_t t2 = S0 + mj;
         hh = g; g = f; f = e; e = d + t1; d = c; c = b; b = a; a = t1 + t2;
     }
@@ -67,6 +67,39 @@ __device__ __forceinline__ void compress(uint32_t (&h)[8], uint32_t (&w)[16]) {
     st = compress_fn(st, bl);
 #pragma unroll
     for (int i = 0; i < 8; ++i) h[i] = st.h[i];
+}
+
+// The two halves of a compression for callers that let different waves do them: the message
+// schedule with the round constants already added (it does not depend on the hash state), and the
+// 64 rounds on such a schedule.
+__device__ __forceinline__ void schedule_plus_k(const uint32_t (&m)[16], uint32_t (&wk)[64]) {
+    uint32_t w[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) w[t] = m[t];
+#pragma unroll
+    for (int t = 0; t < 64; ++t) {
+        if (t >= 16) {
+            uint32_t w15 = w[(t - 15) & 15], w2 = w[(t - 2) & 15];
+            uint32_t s0 = xor3(rotr(w15, 7), rotr(w15, 18), w15 >> 3);
+            uint32_t s1 = xor3(rotr(w2, 17), rotr(w2, 19), w2 >> 10);
+            w[t & 15] = w[t & 15] + s0 + w[(t - 7) & 15] + s1;
+        }
+        wk[t] = w[t & 15] + K[t];
+    }
+}
+__device__ __forceinline__ void rounds_on_schedule(uint32_t (&h)[8], const uint32_t (&wk)[64]) {
+    uint32_t a = h[0], b = h[1], c = h[2], d = h[3], e = h[4], f = h[5], g = h[6], hh = h[7];
+#pragma unroll
+    for (int t = 0; t < 64; ++t) {
+        uint32_t S1 = xor3(rotr(e, 6), rotr(e, 11), rotr(e, 25));
+        uint32_t ch = __builtin_amdgcn_bitop3_b32(e, f, g, 0xCA);
+        uint32_t t1 = hh + S1 + ch + wk[t];
+        uint32_t S0 = xor3(rotr(a, 2), rotr(a, 13), rotr(a, 22));
+        uint32_t mj = __builtin_amdgcn_bitop3_b32(a, b, c, 0xE8);
+        uint32_t t2 = S0 + mj;
+        hh = g; g = f; f = e; e = d + t1; d = c; c = b; b = a; a = t1 + t2;
+    }
+    h[0] += a; h[1] += b; h[2] += c; h[3] += d; h[4] += e; h[5] += f; h[6] += g; h[7] += hh;
 }
 
 __device__ __forceinline__ void init_h(uint32_t (&h)[8]) {
