@@ -57,6 +57,18 @@ def test_device_commitments_match_the_oracle(torch, ctx, oracle_fast):
     assert ctx.imm_commit_tables_device([]) == []
 
 
+def test_device_commitments_over_many_workgroups(torch, ctx, oracle_fast):
+    """More leaves than one workgroup hashes (64), of different lengths side by side in a wave."""
+    rng = np.random.default_rng(11)
+    arrays = [rng.integers(-2**62, 2**62, size=(2048, 6400), dtype=np.int64),      # 100 leaves
+              rng.integers(-128, 128, size=(3, 5), dtype=np.int8),
+              rng.integers(-2**15, 2**15, size=(1500, 1400), dtype=np.int16),       # 5 leaves, the last one short
+              rng.integers(-128, 128, size=(40, MIB), dtype=np.int8),               # 40 whole leaves
+              rng.integers(-2**62, 2**62, size=(9, 1), dtype=np.int64)]
+    got = ctx.imm_commit_tables_device([torch.from_numpy(a).cuda() for a in arrays])
+    assert [bytes(c.digest) for c in got] == [oracle_fast.commit_array(a) for a in arrays]
+
+
 def test_device_commitments_of_tables_that_are_only_4_byte_aligned(torch, ctx, oracle_fast):
     rng = np.random.default_rng(7)
     A, B, C = statement(rng, 3, 700001, 2)
