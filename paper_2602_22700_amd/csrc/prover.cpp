@@ -81,7 +81,9 @@ struct Profiler {
         if (!wants(id)) return IMM_OK;
         if (ev.empty()) {
             ev.resize(2 * kPool);
-            for (auto& e : ev) IMM_HIP(hipEventCreate(&e));
+            // timing only: nothing on the host reads what the kernels wrote when it reads these events, so
+            // recording one need not push the caches out to system scope
+            for (auto& e : ev) IMM_HIP(hipEventCreateWithFlags(&e, hipEventDisableSystemFence));
         }
         if (recs.size() >= kPool) {
             int rc = flush();
