@@ -408,18 +408,14 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
     job.L = job.D;
     const uint64_t D = job.D;
     int rc;
-    job.tr.head(m, d, n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, job.mu, job.nu, job.rx, job.ry);
-
-    // a2: eq vectors for both points
-    if ((rc = build_eq(ctx, s, job.rx, job.mu, job.ry, job.nu))) return rc;
-
-    // a1 for A and B: each operand is widened into scratch (skipped for pre-encoded tables or in
-    // narrow-read mode).  Then a3 + a4: in narrow-read mode both reductions in one launch where the
-    // operand forms allow it (the small table of A streams alongside B's instead of filling and
-    // draining the machine on its own), else one after the other.
+    // a1 for A and B comes first: each operand is widened into scratch (skipped for pre-encoded tables
+    // or in narrow-read mode).  The widening does not depend on the transcript, so its launches go
+    // out before the host hashes the head of the transcript, and everything else is queued behind
+    // them while they run.
     const void* Ap = ds.A_dev;
     const void* Bp = ds.B_dev;
     int dtA = (int)ds.dtA, dtB = (int)ds.dtB;
+    bool taken_over = false;
     if (ctx->ahead_count) {
         if (ctx->widen && same_operands(ctx->ahead[0].ds, ds)) {
             // the tables were queued while the proofs before this one ran: take them over
@@ -427,7 +423,7 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
             for (int i = 1; i < ctx->ahead_count; ++i) ctx->ahead[i - 1] = ctx->ahead[i];
             ctx->ahead_count -= 1;
             ctx->set = q.set;
-            IMM_HIP(hipStreamWaitEvent(s, ctx->ahead_done[q.set], 0));
+            taken_over = true;
             if (q.hasA) {
                 Ap = ctx->encA[q.set].p;
                 dtA = IMM_F64P;
@@ -458,6 +454,14 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
         Bp = encB.p;
         dtB = IMM_F64P;
     }
+    // a0 + a2: the points from the transcript, and their eq vectors
+    job.tr.head(m, d, n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, job.mu, job.nu, job.rx, job.ry);
+    if ((rc = build_eq(ctx, s, job.rx, job.mu, job.ry, job.nu))) return rc;
+    if (taken_over) IMM_HIP(hipStreamWaitEvent(s, ctx->ahead_done[ctx->set], 0));  // the tables are written
+
+    // a3 + a4: in narrow-read mode both reductions in one launch where the operand forms allow it
+    // (the small table of A streams alongside B's instead of filling and draining the machine on
+    // its own), else one after the other.
     // (only beside the narrow-read reduction of B: beside the widened table, ten times larger, A's
     // share is within the noise, and the reduction of B keeps a launch and a bandwidth figure of its own)
     bool both = false;
