@@ -410,9 +410,9 @@ __global__ void fill_u32_kernel(uint32_t* p, uint64_t count, uint32_t v) {
 // cannot decrease (at least K non-members lie above t, at most K members below), and f is piecewise
 // linear, so the minimum is attained at one of the 2K values.  The K largest non-members are among
 // the 2K largest logits of the row.  Those are found without sorting the row: every thread keeps
-// the maximum of its own (strided) share while the row streams in from HBM; if tau is the smallest,
-// over the 16 waves, of the r-th largest thread maximum of the wave (16 r >= 2K), then at least 2K
-// logits are >= tau, and only threads whose maximum reaches tau can hold such logits.  A thread
+// the maximum of its own (strided) share while the row streams in from HBM; if tau is the 2K-th
+// largest of the 16 r thread maxima that are the r largest of each of the 16 waves (16 r >= 2K), then
+// at least 2K logits are >= tau, and only threads whose maximum reaches tau can hold such logits.  A thread
 // also keeps its second largest logit and the place of the largest, so that it can tell whether it
 // holds one such logit (then it knows which) or more (then its share is read again, which is rare:
 // a share is scattered over the row, so reading it again touches a cache line per four logits).
@@ -447,7 +447,7 @@ template <bool VEC>
 __global__ __launch_bounds__(kTopkBlock, kTopkWavesPerSimd) void topk_distance_kernel(
     const float* __restrict__ X, uint64_t n, uint64_t ld, const int32_t* __restrict__ idx_all, uint32_t K,
     double* __restrict__ out) {
-    __shared__ float ldsf[kTopkWaves];
+    __shared__ uint64_t tops[2 * IMM_TOPK_MAX + kTopkWaves];  // the r largest thread maxima of every wave, as keys
     __shared__ int member_idx[IMM_TOPK_MAX];
     __shared__ float member_val[IMM_TOPK_MAX];
     __shared__ uint64_t member_key[IMM_TOPK_MAX];  // key of a member on the candidate list, else 0
@@ -513,25 +513,36 @@ __global__ __launch_bounds__(kTopkBlock, kTopkWavesPerSimd) void topk_distance_k
         at = tmax > before ? (uint32_t)(VEC ? n4 + (i - 4 * n4) : i) : at;
     }
 
-    // r-th largest thread maximum of this wave (ties between lanes broken by lane number)
+    // the r largest thread maxima of this wave (ties between lanes broken by lane number), 16 r >= 2K
     const uint32_t r = (2 * K + kTopkWaves - 1) / kTopkWaves;
     float cur = tmax;     // candidates still in play in this lane
-    float rth = -INFINITY;
     for (uint32_t it = 0; it < r; ++it) {
         float m = cur;
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
-        rth = m;
+        if (lane == 0) tops[wave * r + it] = cand_key(m, wave * r + it);
         // retire exactly one lane holding m
         const uint64_t holders = __ballot(cur == m);
         const uint32_t first = (uint32_t)__builtin_ctzll(holders);
         if (lane == first) cur = -INFINITY;
     }
-    if (lane == 0) ldsf[wave] = rth;
     __syncthreads();
-    float tau = ldsf[0];
-#pragma unroll
-    for (int w = 1; w < kTopkWaves; ++w) tau = fminf(tau, ldsf[w]);
+    // tau = the 2K-th largest of these 16 r thread maxima (every wave works it out for itself: a lane
+    // counts how many of them come before its own one or two)
+    const uint32_t V = kTopkWaves * r;
+    const uint64_t mine0 = lane < V ? tops[lane] : 0, mine1 = lane + 64 < V ? tops[lane + 64] : 0;
+    uint32_t before0 = 0, before1 = 0;
+#pragma unroll 8
+    for (uint32_t j = 0; j < V; ++j) {
+        const uint64_t other = tops[j];
+        before0 += other > mine0 ? 1u : 0u;
+        before1 += other > mine1 ? 1u : 0u;
+    }
+    const uint64_t hit0 = __ballot(lane < V && before0 == 2 * K - 1);
+    const uint64_t hit1 = __ballot(lane + 64 < V && before1 == 2 * K - 1);
+    const uint64_t tau_key = hit0 ? __shfl(mine0, (int)__builtin_ctzll(hit0), 64)
+                                  : __shfl(mine1, (int)__builtin_ctzll(hit1 | (1ull << 63)), 64);
+    const float tau = key_value(tau_key);
 
     // pass 2: only threads whose maximum reaches tau can own a logit >= tau.  Most of them own just
     // that one (their second largest is below tau) and know where it sits, up to its place in a group
