@@ -202,7 +202,9 @@ def main():
         "kernels": kernels,
         "roofline": {"bound": "hbm",
                      "kernel": ("reduce_A+B (partial MLEs of A over its rows and of B over its columns, one launch)" if fused
-                                else "reduce_B (partial MLE of B over its columns)"),
+                                else "reduce_B (partial MLE of B over its columns)" +
+                                ("; the launch also sums the partial vectors of A's reduction, whose bytes are not counted"
+                                 if kernels["combine"]["launches_per_step"] == 0 else "")),
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": recorded_traffic() if args.workload == "ffn_up" else None,

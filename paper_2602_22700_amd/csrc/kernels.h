@@ -49,6 +49,12 @@ hipError_t reduce_both(hipStream_t stream, const void* A, int dtA, uint64_t rows
                        uint64_t colsB, uint64_t ldB, const uint64_t* eq_cols, uint64_t* partB, Split spB, bool* done);
 
 // out[j] = sum_s partial[s][j] for j < len, 0 for len <= j < padded
+// reduce_over_cols of a table of field elements with a single column split (out_rows[i] for i < rows),
+// and in the same launch combine(cpartial, cnsplit, clen, cpadded, cout) of an earlier reduction.
+hipError_t reduce_over_cols_and_combine(hipStream_t stream, const uint64_t* T, uint64_t rows, uint64_t cols, uint64_t ld,
+                                        const uint64_t* eq_cols, uint64_t* out_rows, const uint64_t* cpartial,
+                                        uint32_t cnsplit, uint64_t clen, uint64_t cpadded, uint64_t* cout);
+
 hipError_t combine(hipStream_t stream, const uint64_t* partial, uint32_t nsplit, uint64_t len, uint64_t padded,
                    uint64_t* out);
 

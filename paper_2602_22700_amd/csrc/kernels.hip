@@ -145,6 +145,27 @@ __global__ __launch_bounds__(kBlock) void eq_build2_kernel(Point ptA, int tA, ui
     out[idx] = w;
 }
 
+// ------------------------------------------------------------------ sum of per-split partial vectors
+// 64 outputs per block; the four waves take the splits s = w, w + 4, ... and meet in LDS.
+__device__ __forceinline__ void combine_block(const uint64_t* __restrict__ partial, uint32_t nsplit, uint64_t len,
+                                              uint64_t padded, uint64_t* __restrict__ out, uint32_t block,
+                                              uint64_t (*lds)[64]) {
+    const uint32_t lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const uint64_t j = (uint64_t)block * 64 + lane;
+    uint64_t v = 0;
+    if (j < len) {
+#pragma unroll 8
+        for (uint32_t s = w; s < nsplit; s += kWaves) v = gl::add(v, partial[(uint64_t)s * len + j]);
+    }
+    lds[w][lane] = v;
+    __syncthreads();
+    if (w == 0 && j < padded) {
+#pragma unroll
+        for (int k = 1; k < kWaves; ++k) v = gl::add(v, lds[k][lane]);
+        out[j] = v;
+    }
+}
+
 // ------------------------------------------------------------------ reduction over the columns (row-wise)
 // Block = R consecutive rows x one column split.  A lane owns the column pairs
 // (2*tid, 2*tid+1) + 512*u of the split, so one wave load covers 1 KiB of a row and the
@@ -233,6 +254,29 @@ __global__ __launch_bounds__(kBlock) void reduce_over_cols_kernel(const S* __res
                                                                   uint64_t cols_per_split) {
     __shared__ uint64_t lds[kWaves];
     reduce_over_cols_block<S, R, U, VEC>(T, ld, rows, cols, eq, partial, cols_per_split, blockIdx.x, blockIdx.y, lds);
+}
+
+// The same reduction (single column split) with the sum of another reduction's partial vectors riding
+// in the same launch: the first `cblocks` workgroups do that sum, a few microseconds of work that
+// would otherwise hold a launch slot of its own between two long kernels (placed last in the grid
+// they made the launch half a microsecond longer).
+struct CombineArgs {
+    const uint64_t* partial;
+    uint32_t nsplit;
+    uint64_t len, padded;
+    uint64_t* out;
+};
+template <typename S, int R, int U, bool VEC>
+__global__ __launch_bounds__(kBlock) void reduce_over_cols_and_combine_kernel(const S* __restrict__ T, uint64_t ld,
+                                                                              uint64_t rows, uint64_t cols,
+                                                                              const uint64_t* __restrict__ eq,
+                                                                              uint64_t* __restrict__ partial,
+                                                                              CombineArgs c, uint32_t cblocks) {
+    __shared__ uint64_t lds[kWaves][64];
+    if (blockIdx.x < cblocks)
+        combine_block(c.partial, c.nsplit, c.len, c.padded, c.out, blockIdx.x, lds);
+    else
+        reduce_over_cols_block<S, R, U, VEC>(T, ld, rows, cols, eq, partial, cols, blockIdx.x - cblocks, 0, &lds[0][0]);
 }
 
 constexpr int kRowsPerBlock = 2;
@@ -497,22 +541,10 @@ hipError_t launch_over_rows(hipStream_t stream, const void* T, uint64_t rows, ui
 }
 
 // ------------------------------------------------------------------ combine / dot
-// 64 outputs per block; the four waves take the splits s = w, w + 4, ... and meet in LDS.
 __global__ __launch_bounds__(kBlock) void combine_kernel(const uint64_t* __restrict__ partial, uint32_t nsplit,
                                                          uint64_t len, uint64_t padded, uint64_t* __restrict__ out) {
     __shared__ uint64_t lds[kWaves][64];
-    const uint32_t lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const uint64_t j = (uint64_t)blockIdx.x * 64 + lane;
-    uint64_t v = 0;
-    if (j < len)
-        for (uint32_t s = w; s < nsplit; s += kWaves) v = gl::add(v, partial[(uint64_t)s * len + j]);
-    lds[w][lane] = v;
-    __syncthreads();
-    if (w == 0 && j < padded) {
-#pragma unroll
-        for (int k = 1; k < kWaves; ++k) v = gl::add(v, lds[k][lane]);
-        out[j] = v;
-    }
+    combine_block(partial, nsplit, len, padded, out, blockIdx.x, lds);
 }
 
 __global__ __launch_bounds__(kBlock) void dot_kernel(const uint64_t* __restrict__ x, const uint64_t* __restrict__ y,
@@ -1302,6 +1334,23 @@ hipError_t reduce_both(hipStream_t stream, const void* A, int dtA, uint64_t rows
     else
         hipLaunchKernelGGL((reduce_both_kernel<int16_t, uint64_t, false>), grid, dim3(kBlock), 0, stream, a, b);
     *done = true;
+    return hipGetLastError();
+}
+
+hipError_t reduce_over_cols_and_combine(hipStream_t stream, const uint64_t* T, uint64_t rows, uint64_t cols, uint64_t ld,
+                                        const uint64_t* eq_cols, uint64_t* out_rows, const uint64_t* cpartial,
+                                        uint32_t cnsplit, uint64_t clen, uint64_t cpadded, uint64_t* cout) {
+    const bool vec = (reinterpret_cast<uintptr_t>(T) % 16 == 0) && (ld % 2 == 0) && (cols % 2 == 0) &&
+                     (reinterpret_cast<uintptr_t>(eq_cols) % 16 == 0);
+    const uint32_t cblocks = (uint32_t)((cpadded + 63) / 64);
+    const CombineArgs c{cpartial, cnsplit, clen, cpadded, cout};
+    dim3 grid((unsigned)((rows + kRowsPerBlock - 1) / kRowsPerBlock) + cblocks);
+    if (vec)
+        hipLaunchKernelGGL((reduce_over_cols_and_combine_kernel<uint64_t, kRowsPerBlock, kColsUnroll, true>), grid,
+                           dim3(kBlock), 0, stream, T, ld, rows, cols, eq_cols, out_rows, c, cblocks);
+    else
+        hipLaunchKernelGGL((reduce_over_cols_and_combine_kernel<uint64_t, kRowsPerBlock, kColsUnroll, false>), grid,
+                           dim3(kBlock), 0, stream, T, ld, rows, cols, eq_cols, out_rows, c, cblocks);
     return hipGetLastError();
 }
 

@@ -486,10 +486,30 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
         }
     }
     if (!both) {
-        if ((rc = partial_over_rows(ctx, s, IMM_K_REDUCE_A, Ap, dtA, m, d, d, ctx->eqx.u64(), D, ctx->partA, job.a)))
-            return rc;
-        if ((rc = partial_over_cols(ctx, s, IMM_K_REDUCE_B, Bp, dtB, d, n, n, ctx->eqy.u64(), D, ctx->partB, job.b)))
-            return rc;
+        // Widened tables: when B's reduction writes b itself (a single column split), the sum of A's
+        // partial vectors rides in its launch instead of taking one of its own between the two.
+        const k::Split spA = k::plan_over_rows(m, d), spB = k::plan_over_cols(d, n, dtB);
+        const bool directA = spA.nsplit == 1;
+        if (ctx->fuse_reductions && dtB == IMM_F64P && spB.nsplit == 1 && !(directA && d == D)) {
+            if (!directA && (rc = ctx->partA.ensure(sizeof(uint64_t) * spA.nsplit * d))) return rc;
+            if ((rc = ctx->prof.begin(IMM_K_REDUCE_A, s))) return rc;
+            IMM_HIP(k::reduce_over_rows(s, Ap, dtA, m, d, d, ctx->eqx.u64(), directA ? job.a : ctx->partA.u64(), spA));
+            if ((rc = ctx->prof.end(IMM_K_REDUCE_A, s))) return rc;
+            if ((rc = ctx->prof.begin(IMM_K_REDUCE_B, s))) return rc;
+            if (directA)  // only the padding of a is left
+                IMM_HIP(k::reduce_over_cols_and_combine(s, static_cast<const uint64_t*>(Bp), d, n, n, ctx->eqy.u64(), job.b,
+                                                        nullptr, 0, 0, D - d, job.a + d));
+            else
+                IMM_HIP(k::reduce_over_cols_and_combine(s, static_cast<const uint64_t*>(Bp), d, n, n, ctx->eqy.u64(), job.b,
+                                                        ctx->partA.u64(), spA.nsplit, d, D, job.a));
+            if ((rc = ctx->prof.end(IMM_K_REDUCE_B, s))) return rc;
+            if ((rc = finish_partial(ctx, s, true, ctx->partB, 1, d, D, job.b))) return rc;
+        } else {
+            if ((rc = partial_over_rows(ctx, s, IMM_K_REDUCE_A, Ap, dtA, m, d, d, ctx->eqx.u64(), D, ctx->partA, job.a)))
+                return rc;
+            if ((rc = partial_over_cols(ctx, s, IMM_K_REDUCE_B, Bp, dtB, d, n, n, ctx->eqy.u64(), D, ctx->partB, job.b)))
+                return rc;
+        }
     }
     if (look_count > 0 && ctx->widen && ctx->encode_ahead && (rc = ahead_queue(ctx, s, look, look_count))) return rc;
 
