@@ -286,7 +286,8 @@ int imm_debug_fetch(imm_ctx* ctx, int which, uint64_t* out_host, uint64_t capaci
                                      mailbox in pinned host memory) */
 #define IMM_OPT_FUSE_REDUCTIONS 7 /* 1 (default): in narrow-read mode the partial evaluations of A and of B run in
                                      one launch where the operand forms allow it, and with widened tables the sum
-                                     of A's partial vectors rides in the launch of B's reduction; 0: one launch each */
+                                     of A's partial vectors rides in the launch of B's reduction and the widening
+                                     of two raw operands shares a launch with the eq vectors; 0: one launch each */
 #define IMM_OPT_ENCODE_AHEAD 8    /* 1 (default): in a batch proved one proof after the other, the raw operands of
                                      up to three proofs beyond the current one are widened (IMM_OPT_WIDEN) on a
                                      second stream of the library's own while the current one runs, into a ring

@@ -78,11 +78,12 @@ __device__ __forceinline__ uint64_t block_sum(uint64_t v, uint64_t* lds) {
 }
 
 // ------------------------------------------------------------------ encode
+// The work of workgroup `block` out of `nblocks` that share the array.
 template <typename S, bool VEC>
-__global__ __launch_bounds__(kBlock) void encode_kernel(const S* __restrict__ src, uint64_t* __restrict__ dst,
-                                                        uint64_t count) {
-    const uint64_t stride = (uint64_t)gridDim.x * kBlock;
-    const uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+__device__ __forceinline__ void encode_block(const S* __restrict__ src, uint64_t* __restrict__ dst, uint64_t count,
+                                             uint32_t block, uint32_t nblocks) {
+    const uint64_t stride = (uint64_t)nblocks * kBlock;
+    const uint64_t t = (uint64_t)block * kBlock + threadIdx.x;
     if (VEC) {
         // one wave reads 64 adjacent pairs and writes 1 KiB of contiguous field elements
         const uint64_t pairs = count >> 1;
@@ -101,14 +102,27 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(const S* __restrict__ sr
     }
 }
 
+template <typename S, bool VEC>
+__global__ __launch_bounds__(kBlock) void encode_kernel(const S* __restrict__ src, uint64_t* __restrict__ dst,
+                                                        uint64_t count) {
+    encode_block<S, VEC>(src, dst, count, blockIdx.x, gridDim.x);
+}
+
+// workgroups that encode `count` entries, and whether the two-entries-per-thread form applies
+template <typename S>
+uint32_t encode_blocks(const void* src, const uint64_t* dst, uint64_t count, bool* vec) {
+    *vec = (reinterpret_cast<uintptr_t>(src) % (2 * sizeof(S)) == 0) && (reinterpret_cast<uintptr_t>(dst) % 16 == 0);
+    const uint64_t items = *vec ? (count + 1) / 2 : count;
+    uint64_t blocks = (items + kBlock - 1) / kBlock;  // one item per thread: many small blocks stream best
+    if (blocks > (1u << 22)) blocks = 1u << 22;
+    return (uint32_t)blocks;
+}
+
 template <typename S>
 hipError_t launch_encode(hipStream_t stream, const void* src, uint64_t count, uint64_t* dst) {
     if (count == 0) return hipSuccess;
-    const bool vec = (reinterpret_cast<uintptr_t>(src) % (2 * sizeof(S)) == 0) &&
-                     (reinterpret_cast<uintptr_t>(dst) % 16 == 0);
-    const uint64_t items = vec ? (count + 1) / 2 : count;
-    uint64_t blocks = (items + kBlock - 1) / kBlock;  // one item per thread: many small blocks stream best
-    if (blocks > (1u << 22)) blocks = 1u << 22;
+    bool vec;
+    const uint32_t blocks = encode_blocks<S>(src, dst, count, &vec);
     if (vec)
         hipLaunchKernelGGL((encode_kernel<S, true>), dim3((unsigned)blocks), dim3(kBlock), 0, stream,
                            static_cast<const S*>(src), dst, count);
@@ -122,27 +136,60 @@ hipError_t launch_encode(hipStream_t stream, const void* src, uint64_t count, ui
 // out[i] = prod_k (bit_k(i) ? r_k : 1 - r_k), bit_1 = most significant bit of i.
 // Each entry is an independent product of t factors: no synchronisation, and the
 // result is the same canonical value the doubling recurrence gives.
+// The points are kernel arguments.  The body below is expanded inside the kernels, not called: as
+// long as a kernel reads its own struct arguments with constant indices they come straight from
+// the argument segment, while handing them to a function, even an inlined one, makes every thread
+// of the launch keep a private 512-byte copy.
+#define IMM_EQ_BUILD2_BODY(ptA, tA, outA, ptB, tB, outB, block)                                   \
+    do {                                                                                          \
+        uint64_t idx_ = (uint64_t)(block) * kBlock + threadIdx.x;                                 \
+        const uint64_t nA_ = 1ull << (tA), nB_ = 1ull << (tB);                                    \
+        const bool second_ = idx_ >= nA_;                                                         \
+        if (second_) idx_ -= nA_;                                                                 \
+        const int t_ = second_ ? (tB) : (tA);                                                     \
+        uint64_t w_ = 1;                                                                          \
+        _Pragma("unroll") for (int kk_ = 0; kk_ < IMM_MAX_ROUNDS; ++kk_) {                        \
+            if (kk_ < t_) {                                                                       \
+                const uint64_t r_ = second_ ? (ptB).v[kk_] : (ptA).v[kk_];                        \
+                const uint64_t f_ = ((idx_ >> (t_ - 1 - kk_)) & 1) ? r_ : gl::sub(1, r_);         \
+                w_ = gl::mul(w_, f_);                                                             \
+            }                                                                                     \
+        }                                                                                         \
+        if (!second_ || idx_ < nB_) (second_ ? (outB) : (outA))[idx_] = w_;                       \
+    } while (0)
+
 __global__ __launch_bounds__(kBlock) void eq_build2_kernel(Point ptA, int tA, uint64_t* __restrict__ outA, Point ptB,
                                                            int tB, uint64_t* __restrict__ outB) {
-    uint64_t idx = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    const uint64_t nA = 1ull << tA, nB = 1ull << tB;
-    const Point* pt;
-    uint64_t* out;
-    int t;
-    if (idx < nA) {
-        pt = &ptA; out = outA; t = tA;
-    } else {
-        idx -= nA;
-        if (idx >= nB) return;
-        pt = &ptB; out = outB; t = tB;
+    IMM_EQ_BUILD2_BODY(ptA, tA, outA, ptB, tB, outB, blockIdx.x);
+}
+
+// Everything a proof launches before its reductions, in one grid: the eq vectors of both points
+// (first workgroups), the widening of A from int16 and the widening of B from int8.  The three are
+// independent of one another; as launches of their own the two short ones cost their ramp and a gap.
+struct FrontArgs {
+    const int16_t* srcA;
+    uint64_t* dstA;
+    uint64_t countA;
+    const int8_t* srcB;
+    uint64_t* dstB;
+    uint64_t countB;
+    uint64_t* eqA;
+    uint64_t* eqB;
+    int tA, tB;
+    uint32_t blocks_eq, blocks_A, blocks_B;
+};
+template <bool VA, bool VB>
+__global__ __launch_bounds__(kBlock) void front_kernel(FrontArgs f, Point ptA, Point ptB) {
+    uint32_t b = blockIdx.x;
+    if (b < f.blocks_eq) {
+        IMM_EQ_BUILD2_BODY(ptA, f.tA, f.eqA, ptB, f.tB, f.eqB, b);
+        return;
     }
-    uint64_t w = 1;
-    for (int kk = 0; kk < t; ++kk) {
-        uint64_t r = pt->v[kk];
-        uint64_t f = ((idx >> (t - 1 - kk)) & 1) ? r : gl::sub(1, r);
-        w = gl::mul(w, f);
-    }
-    out[idx] = w;
+    b -= f.blocks_eq;
+    if (b < f.blocks_A)
+        encode_block<int16_t, VA>(f.srcA, f.dstA, f.countA, b, f.blocks_A);
+    else
+        encode_block<int8_t, VB>(f.srcB, f.dstB, f.countB, b - f.blocks_A, f.blocks_B);
 }
 
 // ------------------------------------------------------------------ sum of per-split partial vectors
@@ -1211,6 +1258,24 @@ hipError_t encode(hipStream_t stream, const void* src, int dtype, uint64_t count
     case IMM_I64: return launch_encode<int64_t>(stream, src, count, dst);
     default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t front(hipStream_t stream, const int16_t* A, uint64_t countA, uint64_t* dstA, const int8_t* B, uint64_t countB,
+                 uint64_t* dstB, const Point& ptA, int tA, uint64_t* eqA, const Point& ptB, int tB, uint64_t* eqB) {
+    FrontArgs f{};
+    bool va, vb;
+    f.srcA = A; f.dstA = dstA; f.countA = countA;
+    f.srcB = B; f.dstB = dstB; f.countB = countB;
+    f.eqA = eqA; f.eqB = eqB; f.tA = tA; f.tB = tB;
+    f.blocks_eq = (uint32_t)(((1ull << tA) + (1ull << tB) + kBlock - 1) / kBlock);
+    f.blocks_A = encode_blocks<int16_t>(A, dstA, countA, &va);
+    f.blocks_B = encode_blocks<int8_t>(B, dstB, countB, &vb);
+    const dim3 grid(f.blocks_eq + f.blocks_A + f.blocks_B);
+    if (va && vb) hipLaunchKernelGGL((front_kernel<true, true>), grid, dim3(kBlock), 0, stream, f, ptA, ptB);
+    else if (va) hipLaunchKernelGGL((front_kernel<true, false>), grid, dim3(kBlock), 0, stream, f, ptA, ptB);
+    else if (vb) hipLaunchKernelGGL((front_kernel<false, true>), grid, dim3(kBlock), 0, stream, f, ptA, ptB);
+    else hipLaunchKernelGGL((front_kernel<false, false>), grid, dim3(kBlock), 0, stream, f, ptA, ptB);
+    return hipGetLastError();
 }
 
 hipError_t eq_build2(hipStream_t stream, const Point& ptA, int tA, uint64_t* outA, const Point& ptB, int tB,

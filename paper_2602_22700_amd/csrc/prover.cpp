@@ -409,9 +409,9 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
     const uint64_t D = job.D;
     int rc;
     // a1 for A and B comes first: each operand is widened into scratch (skipped for pre-encoded tables
-    // or in narrow-read mode).  The widening does not depend on the transcript, so its launches go
-    // out before the host hashes the head of the transcript, and everything else is queued behind
-    // them while they run.
+    // or in narrow-read mode).  The widening does not depend on the transcript: where it has launches
+    // of its own they go out before the host hashes the head of the transcript, and everything else
+    // is queued behind them while they run.
     const void* Ap = ds.A_dev;
     const void* Bp = ds.B_dev;
     int dtA = (int)ds.dtA, dtB = (int)ds.dtB;
@@ -438,6 +438,26 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
     }
     imm::DevBuf& encA = ctx->encA[ctx->set];
     imm::DevBuf& encB = ctx->encB[ctx->set];
+    bool eq_done = false;
+    if (ctx->widen && ctx->fuse_reductions && !taken_over && dtA == IMM_I16 && dtB == IMM_I8) {
+        // both operands raw: their widening and the eq vectors (a0 + a1 + a2) go out as one launch
+        job.tr.head(m, d, n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, job.mu, job.nu, job.rx, job.ry);
+        if ((rc = ctx->eqx.ensure(sizeof(uint64_t) << job.mu))) return rc;
+        if ((rc = ctx->eqy.ensure(sizeof(uint64_t) << job.nu))) return rc;
+        if ((rc = encA.ensure(sizeof(uint64_t) * m * d))) return rc;
+        if ((rc = encB.ensure(sizeof(uint64_t) * d * n))) return rc;
+        k::Point px{}, py{};
+        for (int i = 0; i < job.mu; ++i) px.v[i] = job.rx[i];
+        for (int i = 0; i < job.nu; ++i) py.v[i] = job.ry[i];
+        if ((rc = ctx->prof.begin(IMM_K_ENCODE_B, s))) return rc;
+        IMM_HIP(k::front(s, static_cast<const int16_t*>(Ap), m * d, encA.u64(), static_cast<const int8_t*>(Bp), d * n,
+                         encB.u64(), px, job.mu, ctx->eqx.u64(), py, job.nu, ctx->eqy.u64()));
+        if ((rc = ctx->prof.end(IMM_K_ENCODE_B, s))) return rc;
+        Ap = encA.p;
+        Bp = encB.p;
+        dtA = dtB = IMM_F64P;
+        eq_done = true;
+    }
     if (ctx->widen && dtA != IMM_F64P) {
         if ((rc = encA.ensure(sizeof(uint64_t) * m * d))) return rc;
         if ((rc = ctx->prof.begin(IMM_K_ENCODE_A, s))) return rc;
@@ -455,8 +475,10 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
         dtB = IMM_F64P;
     }
     // a0 + a2: the points from the transcript, and their eq vectors
-    job.tr.head(m, d, n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, job.mu, job.nu, job.rx, job.ry);
-    if ((rc = build_eq(ctx, s, job.rx, job.mu, job.ry, job.nu))) return rc;
+    if (!eq_done) {
+        job.tr.head(m, d, n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, job.mu, job.nu, job.rx, job.ry);
+        if ((rc = build_eq(ctx, s, job.rx, job.mu, job.ry, job.nu))) return rc;
+    }
     if (taken_over) IMM_HIP(hipStreamWaitEvent(s, ctx->ahead_done[ctx->set], 0));  // the tables are written
 
     // a3 + a4: in narrow-read mode both reductions in one launch where the operand forms allow it
