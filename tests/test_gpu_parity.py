@@ -220,6 +220,33 @@ def test_prove_extreme_values(torch, ctx, oracle_fast):
         check_proof(torch, ctx, oracle_fast, A, B)
 
 
+def test_prove_operands_at_odd_addresses(torch, ctx, oracle_fast):
+    """Raw operands that start one element into a buffer (2-byte aligned int16, odd-address int8): the
+    widening, alone or sharing a launch, and the reductions take their element-wise forms."""
+    rng = np.random.default_rng(404)
+    for (m, d, n) in ((7, 33, 19), (16, 256, 130), (3, 1000, 257)):
+        A = rng.integers(-2**15, 2**15, size=(m, d), dtype=np.int16)
+        B = rng.integers(-128, 128, size=(d, n), dtype=np.int8)
+        C = oracle_fast.matmul(A, B)
+        com = imm.imm_commit_matmul(A, B, C, m, d, n)
+        want, s_want = oracle_fast.prove(A, B, C, com.digests())
+        bufA = torch.zeros(m * d + 8, dtype=torch.int16, device="cuda")
+        bufB = torch.zeros(d * n + 8, dtype=torch.int8, device="cuda")
+        for offA, offB in ((1, 1), (0, 3), (1, 0)):
+            bufA[offA:offA + m * d] = torch.from_numpy(A.reshape(-1)).cuda()
+            bufB[offB:offB + d * n] = torch.from_numpy(B.reshape(-1)).cuda()
+            Ad, Bd = bufA[offA:offA + m * d].view(m, d), bufB[offB:offB + d * n].view(d, n)
+            try:
+                for widen, fused in ((1, 1), (1, 0), (0, 1)):
+                    ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, widen)
+                    ctx.imm_ctx_set_option(imm.IMM_OPT_FUSE_REDUCTIONS, fused)
+                    got, s_got = ctx.imm_sumcheck_matmul_prove(Ad, Bd, com, imm.imm_fs_init())
+                    assert got.words() == ref.proof_words(want) and s_got == s_want, (m, d, n, offA, offB, widen, fused)
+            finally:
+                ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
+                ctx.imm_ctx_set_option(imm.IMM_OPT_FUSE_REDUCTIONS, 1)
+
+
 def test_config1_tiny(torch, ctx, oracle_fast):
     A, B = workloads.tiny()
     got, _ = check_proof(torch, ctx, oracle_fast, A, B)
