@@ -19,7 +19,7 @@ hipError_t encode(hipStream_t stream, const void* src, int dtype, uint64_t count
 
 // eq vectors of two points in one launch: outA has 2^tA entries, outB has 2^tB.
 // Either count may be 0 (vector [1]).  First coordinate = most significant bit.
-// eq_build2(ptA .. eqB), encode(A -> dstA) and encode(B -> dstB) in one launch (countA, countB >= 1).
+// eq_build2(ptA .. eqB), encode(A -> dstA) and, unless countB is 0, encode(B -> dstB) in one launch (countA >= 1).
 hipError_t front(hipStream_t stream, const int16_t* A, uint64_t countA, uint64_t* dstA, const int8_t* B, uint64_t countB,
                  uint64_t* dstB, const Point& ptA, int tA, uint64_t* eqA, const Point& ptB, int tB, uint64_t* eqB);
 

@@ -1269,7 +1269,8 @@ hipError_t front(hipStream_t stream, const int16_t* A, uint64_t countA, uint64_t
     f.eqA = eqA; f.eqB = eqB; f.tA = tA; f.tB = tB;
     f.blocks_eq = (uint32_t)(((1ull << tA) + (1ull << tB) + kBlock - 1) / kBlock);
     f.blocks_A = encode_blocks<int16_t>(A, dstA, countA, &va);
-    f.blocks_B = encode_blocks<int8_t>(B, dstB, countB, &vb);
+    f.blocks_B = countB ? encode_blocks<int8_t>(B, dstB, countB, &vb) : 0;
+    if (!countB) vb = true;
     const dim3 grid(f.blocks_eq + f.blocks_A + f.blocks_B);
     if (va && vb) hipLaunchKernelGGL((front_kernel<true, true>), grid, dim3(kBlock), 0, stream, f, ptA, ptB);
     else if (va) hipLaunchKernelGGL((front_kernel<true, false>), grid, dim3(kBlock), 0, stream, f, ptA, ptB);

@@ -439,22 +439,24 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
     imm::DevBuf& encA = ctx->encA[ctx->set];
     imm::DevBuf& encB = ctx->encB[ctx->set];
     bool eq_done = false;
-    if (ctx->widen && ctx->fuse_reductions && !taken_over && dtA == IMM_I16 && dtB == IMM_I8) {
-        // both operands raw: their widening and the eq vectors (a0 + a1 + a2) go out as one launch
+    if (ctx->widen && ctx->fuse_reductions && !taken_over && dtA == IMM_I16 && (dtB == IMM_I8 || dtB == IMM_F64P)) {
+        // A raw, B raw or widened beforehand: the widening and the eq vectors (a0 + a1 + a2) go out as one launch
+        const bool rawB = dtB == IMM_I8;
         job.tr.head(m, d, n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, job.mu, job.nu, job.rx, job.ry);
         if ((rc = ctx->eqx.ensure(sizeof(uint64_t) << job.mu))) return rc;
         if ((rc = ctx->eqy.ensure(sizeof(uint64_t) << job.nu))) return rc;
         if ((rc = encA.ensure(sizeof(uint64_t) * m * d))) return rc;
-        if ((rc = encB.ensure(sizeof(uint64_t) * d * n))) return rc;
+        if (rawB && (rc = encB.ensure(sizeof(uint64_t) * d * n))) return rc;
         k::Point px{}, py{};
         for (int i = 0; i < job.mu; ++i) px.v[i] = job.rx[i];
         for (int i = 0; i < job.nu; ++i) py.v[i] = job.ry[i];
         if ((rc = ctx->prof.begin(IMM_K_ENCODE_B, s))) return rc;
-        IMM_HIP(k::front(s, static_cast<const int16_t*>(Ap), m * d, encA.u64(), static_cast<const int8_t*>(Bp), d * n,
-                         encB.u64(), px, job.mu, ctx->eqx.u64(), py, job.nu, ctx->eqy.u64()));
+        IMM_HIP(k::front(s, static_cast<const int16_t*>(Ap), m * d, encA.u64(), rawB ? static_cast<const int8_t*>(Bp) : nullptr,
+                         rawB ? d * n : 0, rawB ? encB.u64() : nullptr, px, job.mu, ctx->eqx.u64(), py, job.nu,
+                         ctx->eqy.u64()));
         if ((rc = ctx->prof.end(IMM_K_ENCODE_B, s))) return rc;
         Ap = encA.p;
-        Bp = encB.p;
+        if (rawB) Bp = encB.p;
         dtA = dtB = IMM_F64P;
         eq_done = true;
     }
