@@ -167,6 +167,25 @@ int imm_mle_eval(imm_ctx* ctx, void* stream, const void* table_dev, imm_dtype dt
                  uint64_t rows, uint64_t cols, uint64_t ld,
                  const uint64_t* pt_rows, const uint64_t* pt_cols, uint64_t* out_host);
 
+/* imm_mle_eval for callers that cannot allocate device memory: code under HIP stream capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same value, but no context and no allocation of
+ * any kind: the working memory (both eq vectors, the partial evaluations, the per-split partial
+ * vectors) is an array of IMM_STATIC_SCRATCH_BYTES that is part of the library's device image, one
+ * copy per device, held until the process ends.  Runs on the calling thread's current HIP device,
+ * asynchronously on `stream`; the result goes to *out_dev (DEVICE, one word) in stream order and
+ * nothing is synchronised.  pt_rows, pt_cols: HOST, read before the call returns.
+ * A table whose working memory exceeds the array -- roughly 8 bytes x (2^ceil(log2 rows) +
+ * 2^ceil(log2 cols) + 3 x the longer dimension) -- is refused with IMM_E_SHAPE and a text in
+ * imm_last_error(); imm_mle_eval takes any size.  All calls on one device share the array: two
+ * calls that overlap in time on the same device (different streams or threads) race and must be
+ * ordered by the caller.  The array's address is looked up when a context is created on the
+ * device, or else by the first call there (which should then come before any stream capture).
+ * Errors: IMM_E_NULL, IMM_E_SHAPE, IMM_E_DTYPE, IMM_E_HIP. */
+#define IMM_STATIC_SCRATCH_BYTES (8u << 20)
+int imm_mle_eval_static(void* stream, const void* table_dev, imm_dtype dt,
+                        uint64_t rows, uint64_t cols, uint64_t ld,
+                        const uint64_t* pt_rows, const uint64_t* pt_cols, uint64_t* out_dev);
+
 /* Prove C = A.B for one statement (the schedule at the top of this file).
  * A_dev: DEVICE m x d, IMM_I16 or IMM_F64P.  B_dev: DEVICE d x n, IMM_I8 or
  * IMM_F64P.  Raw integer operands are widened into context scratch by the

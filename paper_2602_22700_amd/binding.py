@@ -35,7 +35,7 @@ EXPORTS = [
     "imm_mle_eval", "imm_sumcheck_matmul_prove", "imm_sumcheck_matmul_prove_batch", "imm_round_fold_eval",
     "imm_verify", "imm_debug_fetch", "imm_ctx_set_option", "imm_ctx_set_profiling", "imm_ctx_kernel_time",
     "imm_ctx_reset_profiling", "imm_ldd_tv_kl", "imm_topk_distance", "imm_tail_density",
-    "imm_commit_tables_device",
+    "imm_commit_tables_device", "imm_mle_eval_static",
 ]
 
 
@@ -120,6 +120,7 @@ def load() -> ctypes.CDLL:
     L.imm_topk_distance.argtypes = [vp, vp, vp, u64, u64, u64, vp, u32, vp]
     L.imm_tail_density.argtypes = [vp, vp, vp, u64, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
     L.imm_commit_tables_device.argtypes = [vp, vp, i32, ctypes.POINTER(TableDesc), ctypes.POINTER(Commit1)]
+    L.imm_mle_eval_static.argtypes = [vp, vp, i32, u64, u64, u64, vp, vp, vp]
     for name in EXPORTS:
         if name != "imm_last_error":
             getattr(L, name).restype = i32
@@ -186,6 +187,27 @@ def imm_verify(com: Commit, transcript_in: bytes, proof: Proof, A: Optional[np.n
 
 
 # ----------------------------------------------------------------------------- device calls
+IMM_STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def imm_mle_eval_static(table, pt_rows: Sequence[int], pt_cols: Sequence[int], out, stream=None,
+                        rows: Optional[int] = None, cols: Optional[int] = None, ld: Optional[int] = None) -> None:
+    """The allocation-free form of imm_mle_eval: no context; the value lands in out[0] (a device uint64
+    tensor the caller owns) in stream order.  Nothing is synchronised."""
+    import torch
+    assert table.is_cuda and out.is_cuda and out.dtype == torch.uint64 and out.numel() >= 1
+    if rows is None:
+        assert table.dim() == 2 and table.is_contiguous()
+        rows, cols = table.shape
+        ld = cols
+    pr = np.array([int(v) for v in pt_rows], dtype=np.uint64)
+    pc = np.array([int(v) for v in pt_cols], dtype=np.uint64)
+    rc = load().imm_mle_eval_static(_stream_handle(stream), table.data_ptr(), _tensor_dtype(table), rows, cols, ld,
+                                    pr.ctypes.data if pr.size else None, pc.ctypes.data if pc.size else None,
+                                    out.data_ptr())
+    _check(rc, "imm_mle_eval_static")
+
+
 class Context:
     """Owns an imm_ctx.  Methods carry the names of the C entry points."""
 

@@ -15,6 +15,7 @@
 
 #include "../../include/imm.h"
 #include "host_field.h"
+#include "internal.h"
 #include "kernels.h"
 #include "commit_leaves.h"
 #include "ldd.h"
@@ -25,7 +26,9 @@ namespace imm {
 
 static thread_local std::string g_last_error;
 
-static int fail_hip(hipError_t e, const char* what) {
+void set_last_error(const char* text) { g_last_error = text; }
+
+int fail_hip(hipError_t e, const char* what) {
     g_last_error = std::string(what) + ": " + hipGetErrorString(e);
     return IMM_E_HIP;
 }
@@ -813,6 +816,13 @@ extern "C" int imm_ctx_create(imm_ctx** out, int device, size_t scratch_bytes) {
         return fail_hip(e, "hipHostMalloc(mailbox)");
     }
     ctx->replies = reply_block_take(device);  // may be null: then the mailbox carries the challenges
+    if (int rc = static_scratch_prepare(device)) {
+        (void)hipHostFree(ctx->pinned);
+        (void)hipHostFree(ctx->mailbox);
+        reply_block_give(device, ctx->replies);
+        delete ctx;
+        return rc;
+    }
     if (scratch_bytes) {
         // the hint goes to the widened weight table, by far the largest scratch buffer
         int rc = ctx->encB[0].ensure(scratch_bytes);
