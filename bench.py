@@ -26,7 +26,7 @@ def recorded_traffic():
     try:
         kv = dict(line.split(" = ", 1) for line in open(path).read().splitlines() if " = " in line and not line.startswith(" "))
         h = hashlib.sha256()
-        for fn in ("kernels.hip", "goldilocks.cuh"):
+        for fn in ("kernels.hip", "goldilocks_device.h", "kernels.h", "prover.cpp"):   # kernels and launch geometry
             h.update(open(os.path.join(ROOT, "paper_2602_22700_amd", "csrc", fn), "rb").read())
         if h.hexdigest() != kv["kernel_sources_sha256"].strip():
             return None
@@ -62,6 +62,74 @@ def make_workload(name, torch, imm, workloads):
     return out
 
 
+def timed_runs(torch, batch, steps, warmup):
+    """Milliseconds per call of batch.run(), wall clock around `steps` calls bracketed by device syncs."""
+    for _ in range(warmup):
+        batch.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        batch.run()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def other_workload(name, torch, imm, workloads, ctx, steps, cpu_seconds):
+    """A multi-statement workload measured in the same run: the seven chained statements of one decoder
+    layer (`dense_layer`) or the eight independent experts (`moe`), in the three execution modes, with
+    the bandwidth of the dominant kernel (the reduction over B's columns, all statements together),
+    the oracle timed on the same statements and the proofs of all modes compared with the oracle's."""
+    import numpy as np
+    stmts = make_workload(name, torch, imm, workloads)
+    items = [(Ad, Bd, com) for (_, _, Ad, Bd, com) in stmts]
+    chained = name != "moe"
+    s0 = imm.imm_fs_init()
+    batch = ctx.prepare_batch(items, chained, s0)
+    timed_runs(torch, batch, 2, 1)
+    ctx.imm_ctx_reset_profiling()
+    ctx.imm_ctx_set_profiling(1 << imm.IMM_K_REDUCE_B)
+    ms = timed_runs(torch, batch, steps, 0)
+    ctx.imm_ctx_set_profiling(0)
+    n_dom, ms_dom = ctx.imm_ctx_kernel_time(imm.IMM_K_REDUCE_B)
+    ctx.imm_ctx_reset_profiling()
+    proofs = [p.words() for p in batch.proofs]
+    b_bytes = 8.0 * sum(B.shape[0] * B.shape[1] for (_, B, _, _, _) in stmts)
+    pre = [(Ad, ctx.imm_encode(Bd), com) for (Ad, Bd, com) in items]
+    batch_pre = ctx.prepare_batch(pre, chained, s0)
+    ms_pre = timed_runs(torch, batch_pre, steps, 2)
+    proofs_pre = [p.words() for p in batch_pre.proofs]
+    del pre, batch_pre
+    ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 0)
+    ms_narrow = timed_runs(torch, batch, steps, 2)
+    proofs_narrow = [p.words() for p in batch.proofs]
+    ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
+    out = {"statements": [{"m": A.shape[0], "d": A.shape[1], "n": B.shape[1]} for (A, B, _, _, _) in stmts],
+           "transcript": "one chained transcript" if chained else "independent (each from the initial state)",
+           "prove_ms": round(ms, 4), "prove_ms_weights_preencoded": round(ms_pre, 4),
+           "prove_ms_narrow_read": round(ms_narrow, 4),
+           "reduce_B": {"launches_per_step": n_dom / steps, "us_per_step": round(ms_dom * 1e3 / steps, 1),
+                        "algorithmic_MB": b_bytes / 1e6,
+                        "frac_of_8TBps": round(b_bytes * steps / (ms_dom * 1e-3) / 1e9 / HBM_PEAK_GBS, 3) if ms_dom else None}}
+    if cpu_seconds > 0:
+        from oracle import fast as oracle_fast
+        from oracle import reference as ref
+        oracle_items = [(A, B, None, com.digests()) for (A, B, _, _, com) in stmts]
+        want, _ = oracle_fast.prove_chain(oracle_items, chained, check=False)
+        want = [ref.proof_words(p) for p in want]
+        n_cpu, t0 = 0, time.perf_counter()
+        while n_cpu == 0 or time.perf_counter() - t0 < cpu_seconds:
+            oracle_fast.prove_chain(oracle_items, chained, check=False)
+            n_cpu += 1
+        out["cpu_baseline"] = {"value": round((time.perf_counter() - t0) * 1e3 / n_cpu, 2), "unit": "ms",
+                               "cores": oracle_fast.threads(), "kind": "oracle", "sample": ORACLE_FORM % n_cpu}
+        out["proof_bytes_equal"] = bool(proofs == want and proofs_pre == want and proofs_narrow == want)
+    return out
+
+
+ORACLE_FORM = ("the full workload (same statements), %d repetitions; the oracle's prove with c0 taken as sum_j a[j] b[j] "
+               "like the prover's (C=None, check=False: the product matrix is not read, no direct openings)")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -71,6 +139,8 @@ def main():
                     help="dense_request (224 chained proofs) wants --steps 3 --warmup 1")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="time budget of the CPU-oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the decoder-layer and expert-batch workloads that the default run (ffn_up) also measures")
     ap.add_argument("--fold-log2", type=int, default=26,
                     help="log2 of the table length of the stand-alone fold-kernel measurement (0 = skip)")
     ap.add_argument("--ldd-steps", type=int, default=2048,
@@ -197,6 +267,9 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u64 (Goldilocks field)",
         "data": "synthetic",
+        "value_is": ("ms for the proofs of this workload's statements (%d matrix product%s = %d linear layer%s of the model)"
+                     % (len(stmts), "" if len(stmts) == 1 else "s", len(stmts), "" if len(stmts) == 1 else "s")
+                     + ("; a decoder layer of seven is other_workloads.dense_layer" if args.workload == "ffn_up" else "")),
         "config": {"workload": args.workload,
                    "statements": ([{"m": A.shape[0], "d": A.shape[1], "n": B.shape[1]} for (A, B, _, _, _) in stmts]
                                   if len(stmts) <= 8 else "%d chained statements: 32 decoder layers x (Wq, Wk, Wv, Wo, "
@@ -215,6 +288,8 @@ def main():
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": recorded_traffic() if args.workload == "ffn_up" else None,
+                     "traffic_source": "profiles/reduce_B_ffn_up_hbm_counters.txt (recorded with rocprofv3 --pmc in an earlier "
+                                       "run of this command, not measured in this run; null once the kernel sources differ)",
                      "avg_launch_us": round(avg_ms * 1e3, 2), "algorithmic_bytes_per_launch": dom_bytes / max(launches_per_step, 1)},
     }
 
@@ -400,9 +475,16 @@ def main():
                 break
         cpu_ms = (time.perf_counter() - t_cpu0) * 1e3 / n_cpu
         result["cpu_baseline"] = {"value": round(cpu_ms, 2), "unit": "ms", "cores": oracle_fast.threads(),
-                                  "kind": "oracle",
-                                  "sample": "the full workload (same statements), %d repetitions" % n_cpu}
+                                  "kind": "oracle", "sample": ORACLE_FORM % n_cpu}
         result["proof_bytes_equal"] = bool(same)
+
+    # The multi-statement workloads of the metric (ms per layer): one decoder layer and the expert batch.
+    if args.workload == "ffn_up" and not args.no_other_workloads:
+        del stmts, items, batch, step
+        torch.cuda.empty_cache()
+        result["other_workloads"] = {
+            name: other_workload(name, torch, imm, workloads, ctx, 10, 0.0 if args.no_cpu_baseline else 3.0)
+            for name in ("dense_layer", "moe")}
     print(json.dumps(result))
 
 

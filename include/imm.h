@@ -72,6 +72,8 @@ typedef enum imm_dtype {
 #define IMM_REJ_OPEN_C 5     /* c0 != C~(rx || ry) */
 #define IMM_REJ_COMMIT 6     /* a supplied matrix does not hash to its committed digest */
 #define IMM_REJ_FORMAT 7     /* header does not match the shapes, or a word >= p */
+#define IMM_REJ_UNOPENED 8   /* no check failed, but A, B or C was not supplied: c0, vA and vB are then not
+                                tied to the commitments and a prover could have chosen them freely */
 
 /* Hash commitment of one matrix (paper section 2.1: c = Hash(m); no blinding salt).
  * digest = SHA256("IMM-COMMIT-v1" || u32le(dtype) || u64le(rows) || u64le(cols)
@@ -226,16 +228,33 @@ int imm_sumcheck_matmul_prove_batch(imm_ctx* ctx, void* stream, int count,
 int imm_round_fold_eval(imm_ctx* ctx, void* stream, uint64_t* a_dev, uint64_t* b_dev,
                         uint64_t L, const uint64_t* fold_r, uint64_t g_host[3]);
 
-/* Verify one proof -- CPU only (the paper's Vrfy; a REJECT is its "bottom").
- * com: HOST.  transcript_in: HOST 32 bytes.  A, B, C: HOST raw matrices or NULL.
- * With matrices the digests are recomputed and the three openings c0, vA, vB are
- * checked by direct evaluation (this stands in for a polynomial-commitment
- * opening, which hash commitments do not provide); with NULL only the transcript
- * consistency is checked.  transcript_out (HOST, nullable) receives the state
- * after the proof on ACCEPT; *fail_round (nullable) the failing round. */
+/* Verify one proof -- CPU only (the paper's Vrfy; anything but 0 is its "bottom").
+ * com: HOST; the shapes m, d, n are taken from it.  transcript_in: HOST 32 bytes.
+ * A, B, C: HOST raw matrices.  The digests are recomputed and the three openings c0 = C~(rx || ry),
+ * vA = A~(rx || r), vB = B~(r || ry) are checked by direct evaluation (this stands in for a
+ * polynomial-commitment opening, which hash commitments do not provide).  Returns IMM_OK (ACCEPT) only
+ * when all three matrices were supplied and every check passed.  A matrix may be NULL: its digest and
+ * opening are then skipped, and when nothing else fails the call returns IMM_REJ_UNOPENED, not
+ * ACCEPT -- the sumcheck transcript is consistent, but the skipped openings have to be established by
+ * other means (e.g. imm_mle_eval on the device at the points that imm_verify_points returns) before
+ * the proof means anything.  transcript_out (HOST, nullable) receives the state after the proof on
+ * IMM_OK and on IMM_REJ_UNOPENED; *fail_round (nullable) the failing round of IMM_REJ_ROUND_SUM.
+ * Errors: IMM_E_NULL, IMM_E_SHAPE / IMM_E_DTYPE (commitments that do not describe an int16 x int8 ->
+ * int64 statement), IMM_E_NOMEM. */
 int imm_verify(const imm_commit* com, const uint8_t transcript_in[32], const imm_proof* proof,
                const int16_t* A, const int8_t* B, const int64_t* C,
                uint8_t transcript_out[32], int* fail_round);
+
+/* The points at which a proof's three values are openings, replayed from the transcript (no check
+ * of the proof's arithmetic): rx[mu], ry[nu], r[delta] (HOST, IMM_MAX_ROUNDS words each, any may be
+ * NULL).  c0 = C~(rx || ry), vA = A~(rx || r), vB = B~(r || ry).  Errors: as imm_verify; a proof whose
+ * header or words are malformed gives IMM_REJ_FORMAT. */
+int imm_verify_points(const imm_commit* com, const uint8_t transcript_in[32], const imm_proof* proof,
+                      uint64_t* rx, uint64_t* ry, uint64_t* r);
+
+/* One challenge squeezed from a transcript state (the rule at the top of this file): state (HOST,
+ * 32 bytes) is replaced by the accepted hash, *out (HOST) receives the canonical value. */
+int imm_transcript_challenge(uint8_t state[32], uint64_t* out);
 
 /* ---- Logit distances of the audited decision steps ------------------------------------------
  * Beside the matrix products, the audit proof reports how far the deployed logits l_i of each
@@ -279,6 +298,11 @@ int imm_tail_density(imm_ctx* ctx, void* stream, const double* dist_dev, uint64_
  * a and b are snapshots taken before the first fold.  Needs IMM_OPT_DEBUG_SNAPSHOTS
  * set before the proof; IMM_E_STATE otherwise. */
 int imm_debug_fetch(imm_ctx* ctx, int which, uint64_t* out_host, uint64_t capacity, uint64_t* count);
+
+/* Test/diagnostic: the same challenge derivation as imm_transcript_challenge, run by one lane of the
+ * device (the routine the round kernel uses when the device hashes the transcript).  state: HOST, 32
+ * bytes, in/out; *out_host the value.  Synchronises `stream`. */
+int imm_debug_device_challenge(imm_ctx* ctx, void* stream, uint8_t state[32], uint64_t* out_host);
 
 /* Context options. */
 #define IMM_OPT_DEBUG_SNAPSHOTS 1 /* value != 0: keep the intermediates imm_debug_fetch serves (default 0) */

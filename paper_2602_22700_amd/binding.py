@@ -27,6 +27,7 @@ IMM_TRANSCRIPT_DEVICE, IMM_TRANSCRIPT_HOST = 0, 1
  IMM_K_COMBINE, IMM_K_LDD, IMM_K_TOPK, IMM_K_COMMIT, IMM_K_COUNT) = range(11)
 IMM_TOPK_MAX = 64
 IMM_OK, IMM_E_NULL, IMM_E_SHAPE, IMM_E_DTYPE, IMM_E_NOMEM, IMM_E_HIP, IMM_E_STATE = 0, -1, -2, -3, -4, -5, -6
+IMM_REJ_UNOPENED = 8
 KERNEL_NAMES = ["encode_A", "encode_B", "eq_build", "reduce_A", "reduce_B", "round", "combine", "ldd_tv_kl",
                 "topk_distance", "commit_leaves"]
 
@@ -35,7 +36,8 @@ EXPORTS = [
     "imm_mle_eval", "imm_sumcheck_matmul_prove", "imm_sumcheck_matmul_prove_batch", "imm_round_fold_eval",
     "imm_verify", "imm_debug_fetch", "imm_ctx_set_option", "imm_ctx_set_profiling", "imm_ctx_kernel_time",
     "imm_ctx_reset_profiling", "imm_ldd_tv_kl", "imm_topk_distance", "imm_tail_density",
-    "imm_commit_tables_device", "imm_mle_eval_static",
+    "imm_commit_tables_device", "imm_mle_eval_static", "imm_verify_points", "imm_transcript_challenge",
+    "imm_debug_device_challenge",
 ]
 
 
@@ -121,6 +123,9 @@ def load() -> ctypes.CDLL:
     L.imm_tail_density.argtypes = [vp, vp, vp, u64, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
     L.imm_commit_tables_device.argtypes = [vp, vp, i32, ctypes.POINTER(TableDesc), ctypes.POINTER(Commit1)]
     L.imm_mle_eval_static.argtypes = [vp, vp, i32, u64, u64, u64, vp, vp, vp]
+    L.imm_verify_points.argtypes = [ctypes.POINTER(Commit), vp, ctypes.POINTER(Proof), vp, vp, vp]
+    L.imm_transcript_challenge.argtypes = [vp, ctypes.POINTER(u64)]
+    L.imm_debug_device_challenge.argtypes = [vp, vp, vp, ctypes.POINTER(u64)]
     for name in EXPORTS:
         if name != "imm_last_error":
             getattr(L, name).restype = i32
@@ -175,7 +180,8 @@ def imm_commit_matmul(A: Optional[np.ndarray], B: Optional[np.ndarray], C: Optio
 
 def imm_verify(com: Commit, transcript_in: bytes, proof: Proof, A: Optional[np.ndarray] = None,
                B: Optional[np.ndarray] = None, C: Optional[np.ndarray] = None) -> Tuple[int, Optional[bytes], int]:
-    """Returns (code, state_out or None, fail_round); code 0 = ACCEPT, > 0 = reject reason."""
+    """Returns (code, state_out or None, fail_round); code 0 = ACCEPT (all three openings checked),
+    > 0 = reject reason; IMM_REJ_UNOPENED: nothing failed but a matrix was not supplied."""
     assert len(transcript_in) == 32
     sin = (ctypes.c_uint8 * 32).from_buffer_copy(transcript_in)
     sout = (ctypes.c_uint8 * 32)()
@@ -183,7 +189,26 @@ def imm_verify(com: Commit, transcript_in: bytes, proof: Proof, A: Optional[np.n
     rc = load().imm_verify(ctypes.byref(com), sin, ctypes.byref(proof), _host_ptr(A, np.int16),
                            _host_ptr(B, np.int8), _host_ptr(C, np.int64), sout, ctypes.byref(fr))
     _check(rc, "imm_verify")
-    return rc, (bytes(sout) if rc == 0 else None), fr.value
+    return rc, (bytes(sout) if rc in (0, IMM_REJ_UNOPENED) else None), fr.value
+
+
+def imm_verify_points(com: Commit, transcript_in: bytes, proof: Proof) -> Tuple[List[int], List[int], List[int]]:
+    """(rx, ry, r): the points at which c0, vA, vB of the proof are openings of C, A, B."""
+    sin = (ctypes.c_uint8 * 32).from_buffer_copy(transcript_in)
+    bufs = [(ctypes.c_uint64 * IMM_MAX_ROUNDS)() for _ in range(3)]
+    rc = load().imm_verify_points(ctypes.byref(com), sin, ctypes.byref(proof), *bufs)
+    if rc:
+        raise ImmError(rc, "imm_verify_points", load().imm_last_error().decode(errors="replace") if rc < 0 else "")
+    return ([int(v) for v in bufs[0][:proof.mu]], [int(v) for v in bufs[1][:proof.nu]],
+            [int(v) for v in bufs[2][:proof.delta]])
+
+
+def imm_transcript_challenge(state: bytes) -> Tuple[int, bytes]:
+    """(challenge, next state) squeezed from a 32-byte transcript state on the host."""
+    st = (ctypes.c_uint8 * 32).from_buffer_copy(state)
+    out = ctypes.c_uint64(0)
+    _check(load().imm_transcript_challenge(st, ctypes.byref(out)), "imm_transcript_challenge")
+    return out.value, bytes(st)
 
 
 # ----------------------------------------------------------------------------- device calls
@@ -378,6 +403,13 @@ class Context:
                                         ctypes.byref(r) if r is not None else None, g)
         _check(rc, "imm_round_fold_eval")
         return [int(v) for v in g]
+
+    def imm_debug_device_challenge(self, state: bytes, stream=None) -> Tuple[int, bytes]:
+        st = (ctypes.c_uint8 * 32).from_buffer_copy(state)
+        out = ctypes.c_uint64(0)
+        _check(load().imm_debug_device_challenge(self._h, _stream_handle(stream), st, ctypes.byref(out)),
+               "imm_debug_device_challenge")
+        return out.value, bytes(st)
 
     def imm_debug_fetch(self, which: int) -> np.ndarray:
         cnt = ctypes.c_uint64(0)

@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libimm.so")
 
 SOURCES = ["kernels.hip", "ldd.hip", "commit_leaves.hip", "static_eval.hip", "prover.cpp", "verify.cpp", "commit.cpp", "transcript.cpp", "sha256.cpp"]
-HEADERS = ["goldilocks.cuh", "sha256_device.cuh", "kernels.h", "internal.h", "ldd.h", "commit_leaves.h", "host_field.h", "transcript.h", "sha256.h", "../../include/imm.h"]
+HEADERS = ["goldilocks_device.h", "sha256_device.h", "kernels.h", "internal.h", "ldd.h", "commit_leaves.h", "host_field.h", "transcript.h", "sha256.h", "../../include/imm.h"]
 
 # -packed-fp32-ops off: keep the compiler from forming packed-FP32 instructions
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

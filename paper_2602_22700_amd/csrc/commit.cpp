@@ -1,6 +1,7 @@
 // Hash commitments of the statement's matrices (host only).
 #include <algorithm>
 #include <cstring>
+#include <new>
 #include <thread>
 #include <vector>
 
@@ -59,9 +60,23 @@ extern "C" int imm_commit_matmul(const int16_t* A, const int8_t* B, const int64_
     if (!out) return IMM_E_NULL;
     const uint64_t lim = 1ull << IMM_MAX_ROUNDS;
     if (m == 0 || d == 0 || n == 0 || m > lim || d > lim || n > lim) return IMM_E_SHAPE;
-    if (A) imm::fill(&out->A, A, 2, IMM_I16, m, d);
-    if (B) imm::fill(&out->B, B, 1, IMM_I8, d, n);
-    if (C) imm::fill(&out->C, C, 8, IMM_I64, m, n);
+    try {
+        if (A) imm::fill(&out->A, A, 2, IMM_I16, m, d);
+        if (B) imm::fill(&out->B, B, 1, IMM_I8, d, n);
+        if (C) imm::fill(&out->C, C, 8, IMM_I64, m, n);
+    } catch (const std::bad_alloc&) {
+        return IMM_E_NOMEM;
+    } catch (...) {  // a worker thread could not be started
+        return IMM_E_STATE;
+    }
+    return IMM_OK;
+}
+
+extern "C" int imm_transcript_challenge(uint8_t state[32], uint64_t* out) {
+    if (!state || !out) return IMM_E_NULL;
+    imm::Transcript tr(state);
+    *out = tr.challenge();
+    std::memcpy(state, tr.s, 32);
     return IMM_OK;
 }
 

@@ -11,7 +11,7 @@
 // below what HBM gives.
 #include "commit_leaves.h"
 
-#include "sha256_device.cuh"
+#include "sha256_device.h"
 
 namespace imm {
 namespace k {

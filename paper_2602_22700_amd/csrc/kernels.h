@@ -90,6 +90,9 @@ constexpr uint64_t kRoundsMaxL = 1ull << 15;  // longest table the single-workgr
 hipError_t rounds(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, int nrounds, int first_k, bool absorb_claim,
                   const uint32_t state_in[8], uint64_t* words, uint32_t* state_out);
 
+// One transcript challenge on the device: value[0] and state_out[0..8) (big-endian words) from state_in.
+hipError_t challenge_once(hipStream_t stream, const uint32_t state_in[8], uint64_t* value, uint32_t* state_out);
+
 // Mailbox in pinned, coherent host memory shared by rounds_mailbox() and the host thread that
 // hashes the transcript.  Every slot holds kMailEmpty until its owner writes it.
 constexpr uint64_t kMailEmpty = 0xFFFFFFFFFFFFFFFFull;  // not a canonical field element

@@ -6,8 +6,8 @@
 // for C = A.B over Goldilocks) and all conventions are stated in include/imm.h.
 #include "kernels.h"
 
-#include "goldilocks.cuh"
-#include "sha256_device.cuh"
+#include "goldilocks_device.h"
+#include "sha256_device.h"
 
 namespace imm {
 namespace k {
@@ -871,6 +871,17 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_kernel(uint64_t* __restri
     }
 }
 
+// One challenge from a given state, by the routine the loop above uses (for tests of its rare branch).
+__global__ void challenge_kernel(sha::State st_in, uint64_t* __restrict__ value, uint32_t* __restrict__ state_out) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    uint32_t s[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s[i] = st_in.h[i];
+    value[0] = sha::challenge(s);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) state_out[i] = s[i];
+}
+
 // ------------------------------------------------------------------ all rounds in one launch, host hashes
 // Same loop as rounds_kernel, but the transcript stays on the host: the workgroup posts g_k into a
 // mailbox in pinned host memory and lane 0 polls the slot where the host thread (spinning on the same
@@ -1470,6 +1481,13 @@ hipError_t rounds(hipStream_t stream, uint64_t* a, uint64_t* b, uint64_t L, int 
     for (int i = 0; i < 8; ++i) st.h[i] = state_in[i];
     hipLaunchKernelGGL(rounds_kernel, dim3(1), dim3(kRoundsBlock), 0, stream, a, b, L, nrounds, first_k,
                        absorb_claim ? 1 : 0, st, words, state_out);
+    return hipGetLastError();
+}
+
+hipError_t challenge_once(hipStream_t stream, const uint32_t state_in[8], uint64_t* value, uint32_t* state_out) {
+    sha::State st;
+    for (int i = 0; i < 8; ++i) st.h[i] = state_in[i];
+    hipLaunchKernelGGL(challenge_kernel, dim3(1), dim3(64), 0, stream, st, value, state_out);
     return hipGetLastError();
 }
 

@@ -3,6 +3,8 @@
 // host only hashes and moves a few words per round.
 #include <hip/hip_runtime.h>
 #include <mutex>
+#include <new>
+#include <stdexcept>
 #include <emmintrin.h>
 
 #include <algorithm>
@@ -334,6 +336,17 @@ static int check_desc(const imm_matmul_desc& ds) {
     if (!dim_ok(ds.m) || !dim_ok(ds.d) || !dim_ok(ds.n)) return IMM_E_SHAPE;
     if (ds.dtA != IMM_I16 && ds.dtA != IMM_F64P) return IMM_E_DTYPE;
     if (ds.dtB != IMM_I8 && ds.dtB != IMM_F64P) return IMM_E_DTYPE;
+    // the commitments must be those of this statement: the verifier takes the shapes from them
+    const imm_commit& c = *ds.com;
+    if (c.A.rows != ds.m || c.A.cols != ds.d || c.B.rows != ds.d || c.B.cols != ds.n || c.C.rows != ds.m ||
+        c.C.cols != ds.n) {
+        g_last_error = "the shapes recorded in the commitments differ from m, d, n";
+        return IMM_E_SHAPE;
+    }
+    if (c.A.dtype != IMM_I16 || c.B.dtype != IMM_I8 || c.C.dtype != IMM_I64) {
+        g_last_error = "the commitments are not those of an int16 x int8 -> int64 statement";
+        return IMM_E_DTYPE;
+    }
     return IMM_OK;
 }
 
@@ -788,53 +801,73 @@ static int prove_independent(imm_ctx* ctx, hipStream_t s, int count, const imm_m
 
 using namespace imm;
 
+// No exception crosses the C ABI: host allocations that fail (vectors of jobs, leaves, events) and
+// anything else the standard library throws become error codes.
+template <typename F>
+static int guarded(F&& body) {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        g_last_error = "host allocation failed";
+        return IMM_E_NOMEM;
+    } catch (const std::exception& e) {
+        g_last_error = e.what();
+        return IMM_E_STATE;
+    } catch (...) {
+        g_last_error = "unknown exception";
+        return IMM_E_STATE;
+    }
+}
+
 extern "C" const char* imm_last_error(void) { return g_last_error.c_str(); }
 
 extern "C" int imm_ctx_create(imm_ctx** out, int device, size_t scratch_bytes) {
-    if (!out) return IMM_E_NULL;
-    *out = nullptr;
-    int count = 0;
-    IMM_HIP(hipGetDeviceCount(&count));
-    if (device < 0 || device >= count) {
-        g_last_error = "no such HIP device";
-        return IMM_E_HIP;
-    }
-    IMM_HIP(hipSetDevice(device));
-    imm_ctx* ctx = new (std::nothrow) imm_ctx();
-    if (!ctx) return IMM_E_NOMEM;
-    ctx->device = device;
-    hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), 4096, hipHostMallocDefault);
-    if (e != hipSuccess) {
-        delete ctx;
-        return fail_hip(e, "hipHostMalloc");
-    }
-    e = hipHostMalloc(reinterpret_cast<void**>(&ctx->mailbox), sizeof(k::Mailbox) * k::kRoundsMaxJobs,
-                      hipHostMallocMapped | hipHostMallocCoherent);
-    if (e != hipSuccess) {
-        (void)hipHostFree(ctx->pinned);
-        delete ctx;
-        return fail_hip(e, "hipHostMalloc(mailbox)");
-    }
-    ctx->replies = reply_block_take(device);  // may be null: then the mailbox carries the challenges
-    if (int rc = static_scratch_prepare(device)) {
-        (void)hipHostFree(ctx->pinned);
-        (void)hipHostFree(ctx->mailbox);
-        reply_block_give(device, ctx->replies);
-        delete ctx;
-        return rc;
-    }
-    if (scratch_bytes) {
-        // the hint goes to the widened weight table, by far the largest scratch buffer
-        int rc = ctx->encB[0].ensure(scratch_bytes);
-        if (rc) {
+    return guarded([&]() -> int {
+        if (!out) return IMM_E_NULL;
+        *out = nullptr;
+        int count = 0;
+        IMM_HIP(hipGetDeviceCount(&count));
+        if (device < 0 || device >= count) {
+            g_last_error = "no such HIP device";
+            return IMM_E_HIP;
+        }
+        IMM_HIP(hipSetDevice(device));
+        imm_ctx* ctx = new (std::nothrow) imm_ctx();
+        if (!ctx) return IMM_E_NOMEM;
+        ctx->device = device;
+        hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), 4096, hipHostMallocDefault);
+        if (e != hipSuccess) {
+            delete ctx;
+            return fail_hip(e, "hipHostMalloc");
+        }
+        e = hipHostMalloc(reinterpret_cast<void**>(&ctx->mailbox), sizeof(k::Mailbox) * k::kRoundsMaxJobs,
+                          hipHostMallocMapped | hipHostMallocCoherent);
+        if (e != hipSuccess) {
+            (void)hipHostFree(ctx->pinned);
+            delete ctx;
+            return fail_hip(e, "hipHostMalloc(mailbox)");
+        }
+        ctx->replies = reply_block_take(device);  // may be null: then the mailbox carries the challenges
+        if (int rc = static_scratch_prepare(device)) {
             (void)hipHostFree(ctx->pinned);
             (void)hipHostFree(ctx->mailbox);
+            reply_block_give(device, ctx->replies);
             delete ctx;
             return rc;
         }
-    }
-    *out = ctx;
-    return IMM_OK;
+        if (scratch_bytes) {
+            // the hint goes to the widened weight table, by far the largest scratch buffer
+            int rc = ctx->encB[0].ensure(scratch_bytes);
+            if (rc) {
+                (void)hipHostFree(ctx->pinned);
+                (void)hipHostFree(ctx->mailbox);
+                delete ctx;
+                return rc;
+            }
+        }
+        *out = ctx;
+        return IMM_OK;
+    });
 }
 
 extern "C" int imm_ctx_destroy(imm_ctx* ctx) {
@@ -886,288 +919,341 @@ extern "C" int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value) {
 }
 
 extern "C" int imm_ctx_set_profiling(imm_ctx* ctx, uint32_t mask) {
-    if (!ctx) return IMM_E_NULL;
-    IMM_HIP(hipSetDevice(ctx->device));
-    if (ctx->prof.mask) {
-        int rc = ctx->prof.flush();
-        if (rc) return rc;
-    }
-    ctx->prof.mask = mask & ((1u << IMM_K_COUNT) - 1);
-    return IMM_OK;
+    return guarded([&]() -> int {
+        if (!ctx) return IMM_E_NULL;
+        IMM_HIP(hipSetDevice(ctx->device));
+        if (ctx->prof.mask) {
+            int rc = ctx->prof.flush();
+            if (rc) return rc;
+        }
+        ctx->prof.mask = mask & ((1u << IMM_K_COUNT) - 1);
+        return IMM_OK;
+    });
 }
 
 extern "C" int imm_ctx_kernel_time(imm_ctx* ctx, int kernel_id, uint64_t* launches, double* total_ms) {
-    if (!ctx) return IMM_E_NULL;
-    if (kernel_id < 0 || kernel_id >= IMM_K_COUNT) return IMM_E_SHAPE;
-    IMM_HIP(hipSetDevice(ctx->device));
-    int rc = ctx->prof.flush();
-    if (rc) return rc;
-    if (launches) *launches = ctx->prof.launches[kernel_id];
-    if (total_ms) *total_ms = ctx->prof.total_ms[kernel_id];
-    return IMM_OK;
+    return guarded([&]() -> int {
+        if (!ctx) return IMM_E_NULL;
+        if (kernel_id < 0 || kernel_id >= IMM_K_COUNT) return IMM_E_SHAPE;
+        IMM_HIP(hipSetDevice(ctx->device));
+        int rc = ctx->prof.flush();
+        if (rc) return rc;
+        if (launches) *launches = ctx->prof.launches[kernel_id];
+        if (total_ms) *total_ms = ctx->prof.total_ms[kernel_id];
+        return IMM_OK;
+    });
 }
 
 extern "C" int imm_ctx_reset_profiling(imm_ctx* ctx) {
-    if (!ctx) return IMM_E_NULL;
-    IMM_HIP(hipSetDevice(ctx->device));
-    int rc = ctx->prof.flush();
-    ctx->prof.reset();
-    return rc;
+    return guarded([&]() -> int {
+        if (!ctx) return IMM_E_NULL;
+        IMM_HIP(hipSetDevice(ctx->device));
+        int rc = ctx->prof.flush();
+        ctx->prof.reset();
+        return rc;
+    });
 }
 
 extern "C" int imm_encode(imm_ctx* ctx, void* stream, const void* src_dev, imm_dtype dtype, uint64_t count,
                           uint64_t* dst_dev) {
-    if (!ctx || (count && (!src_dev || !dst_dev))) return IMM_E_NULL;
-    if (dtype != IMM_I8 && dtype != IMM_I16 && dtype != IMM_I64) return IMM_E_DTYPE;
-    IMM_HIP(hipSetDevice(ctx->device));
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    int rc;
-    if ((rc = ctx->prof.begin(IMM_K_ENCODE_B, s))) return rc;
-    IMM_HIP(k::encode(s, src_dev, dtype, count, dst_dev));
-    return ctx->prof.end(IMM_K_ENCODE_B, s);
+    return guarded([&]() -> int {
+        if (!ctx || (count && (!src_dev || !dst_dev))) return IMM_E_NULL;
+        if (dtype != IMM_I8 && dtype != IMM_I16 && dtype != IMM_I64) return IMM_E_DTYPE;
+        IMM_HIP(hipSetDevice(ctx->device));
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        int rc;
+        if ((rc = ctx->prof.begin(IMM_K_ENCODE_B, s))) return rc;
+        IMM_HIP(k::encode(s, src_dev, dtype, count, dst_dev));
+        return ctx->prof.end(IMM_K_ENCODE_B, s);
+    });
 }
 
 extern "C" int imm_mle_eval(imm_ctx* ctx, void* stream, const void* table_dev, imm_dtype dt, uint64_t rows,
                             uint64_t cols, uint64_t ld, const uint64_t* pt_rows, const uint64_t* pt_cols,
                             uint64_t* out_host) {
-    if (!ctx || !table_dev || !out_host) return IMM_E_NULL;
-    if (!dim_ok(rows) || !dim_ok(cols) || ld < cols) return IMM_E_SHAPE;
-    if (dt < IMM_I8 || dt > IMM_F64P) return IMM_E_DTYPE;
-    const int tR = hf::ceil_log2(rows), tC = hf::ceil_log2(cols);
-    if ((tR && !pt_rows) || (tC && !pt_cols)) return IMM_E_NULL;
-    for (int i = 0; i < tR; ++i)
-        if (pt_rows[i] >= hf::P) return IMM_E_SHAPE;
-    for (int i = 0; i < tC; ++i)
-        if (pt_cols[i] >= hf::P) return IMM_E_SHAPE;
-    IMM_HIP(hipSetDevice(ctx->device));
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    int rc;
-    if ((rc = build_eq(ctx, s, pt_rows, tR, pt_cols, tC))) return rc;
-    if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
-    if (cols >= 256) {
-        // wide table: reduce along the rows first, then one dot product with the row weights
-        if ((rc = ctx->a.ensure(sizeof(uint64_t) * rows))) return rc;
-        if ((rc = partial_over_cols(ctx, s, IMM_K_REDUCE_B, table_dev, dt, rows, cols, ld, ctx->eqy.u64(), rows,
-                                    ctx->partB, ctx->a.u64())))
-            return rc;
-        IMM_HIP(k::dot(s, ctx->a.u64(), ctx->eqx.u64(), rows, ctx->words.u64()));
-    } else {
-        if ((rc = ctx->a.ensure(sizeof(uint64_t) * cols))) return rc;
-        if ((rc = partial_over_rows(ctx, s, IMM_K_REDUCE_A, table_dev, dt, rows, cols, ld, ctx->eqx.u64(), cols,
-                                    ctx->partA, ctx->a.u64())))
-            return rc;
-        IMM_HIP(k::dot(s, ctx->a.u64(), ctx->eqy.u64(), cols, ctx->words.u64()));
-    }
-    if ((rc = fetch_words(ctx, s, ctx->words.u64(), 1, out_host))) return rc;
-    return ctx->prof.mask ? ctx->prof.flush() : IMM_OK;
+    return guarded([&]() -> int {
+        if (!ctx || !table_dev || !out_host) return IMM_E_NULL;
+        if (!dim_ok(rows) || !dim_ok(cols) || ld < cols) return IMM_E_SHAPE;
+        if (dt < IMM_I8 || dt > IMM_F64P) return IMM_E_DTYPE;
+        const int tR = hf::ceil_log2(rows), tC = hf::ceil_log2(cols);
+        if ((tR && !pt_rows) || (tC && !pt_cols)) return IMM_E_NULL;
+        for (int i = 0; i < tR; ++i)
+            if (pt_rows[i] >= hf::P) return IMM_E_SHAPE;
+        for (int i = 0; i < tC; ++i)
+            if (pt_cols[i] >= hf::P) return IMM_E_SHAPE;
+        IMM_HIP(hipSetDevice(ctx->device));
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        int rc;
+        if ((rc = build_eq(ctx, s, pt_rows, tR, pt_cols, tC))) return rc;
+        if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
+        if (cols >= 256) {
+            // wide table: reduce along the rows first, then one dot product with the row weights
+            if ((rc = ctx->a.ensure(sizeof(uint64_t) * rows))) return rc;
+            if ((rc = partial_over_cols(ctx, s, IMM_K_REDUCE_B, table_dev, dt, rows, cols, ld, ctx->eqy.u64(), rows,
+                                        ctx->partB, ctx->a.u64())))
+                return rc;
+            IMM_HIP(k::dot(s, ctx->a.u64(), ctx->eqx.u64(), rows, ctx->words.u64()));
+        } else {
+            if ((rc = ctx->a.ensure(sizeof(uint64_t) * cols))) return rc;
+            if ((rc = partial_over_rows(ctx, s, IMM_K_REDUCE_A, table_dev, dt, rows, cols, ld, ctx->eqx.u64(), cols,
+                                        ctx->partA, ctx->a.u64())))
+                return rc;
+            IMM_HIP(k::dot(s, ctx->a.u64(), ctx->eqy.u64(), cols, ctx->words.u64()));
+        }
+        if ((rc = fetch_words(ctx, s, ctx->words.u64(), 1, out_host))) return rc;
+        return ctx->prof.mask ? ctx->prof.flush() : IMM_OK;
+    });
 }
 
 extern "C" int imm_sumcheck_matmul_prove(imm_ctx* ctx, void* stream, const void* A_dev, imm_dtype dtA,
                                          const void* B_dev, imm_dtype dtB, uint64_t m, uint64_t d, uint64_t n,
                                          const imm_commit* com, uint8_t transcript_state[32], imm_proof* out_host) {
-    if (!ctx) return IMM_E_NULL;
-    IMM_HIP(hipSetDevice(ctx->device));
-    imm_matmul_desc ds;
-    ds.A_dev = A_dev; ds.B_dev = B_dev;
-    ds.dtA = (uint32_t)dtA; ds.dtB = (uint32_t)dtB;
-    ds.m = m; ds.d = d; ds.n = n;
-    ds.com = com;
-    return prove_one(ctx, static_cast<hipStream_t>(stream), ds, transcript_state, out_host);
+    return guarded([&]() -> int {
+        if (!ctx) return IMM_E_NULL;
+        IMM_HIP(hipSetDevice(ctx->device));
+        imm_matmul_desc ds;
+        ds.A_dev = A_dev; ds.B_dev = B_dev;
+        ds.dtA = (uint32_t)dtA; ds.dtB = (uint32_t)dtB;
+        ds.m = m; ds.d = d; ds.n = n;
+        ds.com = com;
+        return prove_one(ctx, static_cast<hipStream_t>(stream), ds, transcript_state, out_host);
+    });
 }
 
 extern "C" int imm_sumcheck_matmul_prove_batch(imm_ctx* ctx, void* stream, int count, const imm_matmul_desc* descs,
                                                int chained, uint8_t transcript_state[32], imm_proof* outs_host,
                                                uint8_t* states_out) {
-    if (!ctx || !transcript_state || (count > 0 && (!descs || !outs_host))) return IMM_E_NULL;
-    if (count < 0) return IMM_E_SHAPE;
-    IMM_HIP(hipSetDevice(ctx->device));
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    // validate everything before the first launch
-    for (int t = 0; t < count; ++t) {
-        int rc = check_desc(descs[t]);
-        if (rc) return rc;
-    }
-    uint8_t start[32], cur[32];
-    std::memcpy(start, transcript_state, 32);
-    std::memcpy(cur, transcript_state, 32);
-    if (!chained && count > 1 && ctx->transcript_mode == IMM_TRANSCRIPT_HOST && !ctx->debug) {
-        std::vector<uint8_t> states((size_t)count * 32);
-        int rc = prove_independent(ctx, s, count, descs, start, outs_host, states.data());
-        if (rc) return rc;
-        if (states_out) std::memcpy(states_out, states.data(), states.size());
-        std::memcpy(transcript_state, states.data() + 32 * (size_t)(count - 1), 32);
-        return IMM_OK;
-    }
-    for (int t = 0; t < count; ++t) {
-        if (!chained) std::memcpy(cur, start, 32);
-        int rc = prove_one(ctx, s, descs[t], cur, &outs_host[t], descs + t + 1, count - t - 1);
-        if (rc) {
-            (void)ahead_drop(ctx);
-            return rc;
+    return guarded([&]() -> int {
+        if (!ctx || !transcript_state || (count > 0 && (!descs || !outs_host))) return IMM_E_NULL;
+        if (count < 0) return IMM_E_SHAPE;
+        IMM_HIP(hipSetDevice(ctx->device));
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        // validate everything before the first launch
+        for (int t = 0; t < count; ++t) {
+            int rc = check_desc(descs[t]);
+            if (rc) return rc;
         }
-        if (states_out) std::memcpy(states_out + 32 * (size_t)t, cur, 32);
-    }
-    std::memcpy(transcript_state, cur, 32);
-    return IMM_OK;
+        uint8_t start[32], cur[32];
+        std::memcpy(start, transcript_state, 32);
+        std::memcpy(cur, transcript_state, 32);
+        if (!chained && count > 1 && ctx->transcript_mode == IMM_TRANSCRIPT_HOST && !ctx->debug) {
+            std::vector<uint8_t> states((size_t)count * 32);
+            int rc = prove_independent(ctx, s, count, descs, start, outs_host, states.data());
+            if (rc) return rc;
+            if (states_out) std::memcpy(states_out, states.data(), states.size());
+            std::memcpy(transcript_state, states.data() + 32 * (size_t)(count - 1), 32);
+            return IMM_OK;
+        }
+        for (int t = 0; t < count; ++t) {
+            if (!chained) std::memcpy(cur, start, 32);
+            int rc = prove_one(ctx, s, descs[t], cur, &outs_host[t], descs + t + 1, count - t - 1);
+            if (rc) {
+                (void)ahead_drop(ctx);
+                return rc;
+            }
+            if (states_out) std::memcpy(states_out + 32 * (size_t)t, cur, 32);
+        }
+        std::memcpy(transcript_state, cur, 32);
+        return IMM_OK;
+    });
 }
 
 extern "C" int imm_round_fold_eval(imm_ctx* ctx, void* stream, uint64_t* a_dev, uint64_t* b_dev, uint64_t L,
                                    const uint64_t* fold_r, uint64_t g_host[3]) {
-    if (!ctx || !a_dev || !b_dev || !g_host) return IMM_E_NULL;
-    if (L < 2 || (L & (L - 1)) || L > (1ull << IMM_MAX_ROUNDS)) return IMM_E_SHAPE;
-    if (fold_r && *fold_r >= hf::P) return IMM_E_SHAPE;
-    IMM_HIP(hipSetDevice(ctx->device));
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    int rc;
-    if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
-    if ((rc = run_round(ctx, s, a_dev, b_dev, L, fold_r != nullptr, fold_r ? *fold_r : 0, ctx->words.u64(), g_host)))
-        return rc;
-    return ctx->prof.mask ? ctx->prof.flush() : IMM_OK;
+    return guarded([&]() -> int {
+        if (!ctx || !a_dev || !b_dev || !g_host) return IMM_E_NULL;
+        if (L < 2 || (L & (L - 1)) || L > (1ull << IMM_MAX_ROUNDS)) return IMM_E_SHAPE;
+        if (fold_r && *fold_r >= hf::P) return IMM_E_SHAPE;
+        IMM_HIP(hipSetDevice(ctx->device));
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        int rc;
+        if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
+        if ((rc = run_round(ctx, s, a_dev, b_dev, L, fold_r != nullptr, fold_r ? *fold_r : 0, ctx->words.u64(), g_host)))
+            return rc;
+        return ctx->prof.mask ? ctx->prof.flush() : IMM_OK;
+    });
 }
 
 extern "C" int imm_debug_fetch(imm_ctx* ctx, int which, uint64_t* out_host, uint64_t capacity, uint64_t* count) {
-    if (!ctx || !count) return IMM_E_NULL;
-    if (!ctx->debug || ctx->dbg_delta < 0) return IMM_E_STATE;
-    IMM_HIP(hipSetDevice(ctx->device));
-    const uint64_t* host_src = nullptr;
-    const void* dev_src = nullptr;
-    uint64_t avail = 0;
-    switch (which) {
-    case 0: dev_src = ctx->eqx.p; avail = 1ull << ctx->dbg_mu; break;
-    case 1: dev_src = ctx->eqy.p; avail = 1ull << ctx->dbg_nu; break;
-    case 2: dev_src = ctx->snapA.p; avail = 1ull << ctx->dbg_delta; break;
-    case 3: dev_src = ctx->snapB.p; avail = 1ull << ctx->dbg_delta; break;
-    case 4: host_src = ctx->dbg_rx; avail = (uint64_t)ctx->dbg_mu; break;
-    case 5: host_src = ctx->dbg_ry; avail = (uint64_t)ctx->dbg_nu; break;
-    case 6: host_src = ctx->dbg_r; avail = (uint64_t)ctx->dbg_delta; break;
-    default: return IMM_E_SHAPE;
-    }
-    *count = avail;
-    uint64_t ncopy = avail < capacity ? avail : capacity;
-    if (!ncopy) return IMM_OK;
-    if (!out_host) return IMM_E_NULL;
-    if (host_src) {
-        std::memcpy(out_host, host_src, ncopy * sizeof(uint64_t));
-    } else {
-        IMM_HIP(hipDeviceSynchronize());
-        IMM_HIP(hipMemcpy(out_host, dev_src, ncopy * sizeof(uint64_t), hipMemcpyDeviceToHost));
-    }
-    return IMM_OK;
+    return guarded([&]() -> int {
+        if (!ctx || !count) return IMM_E_NULL;
+        if (!ctx->debug || ctx->dbg_delta < 0) return IMM_E_STATE;
+        IMM_HIP(hipSetDevice(ctx->device));
+        const uint64_t* host_src = nullptr;
+        const void* dev_src = nullptr;
+        uint64_t avail = 0;
+        switch (which) {
+        case 0: dev_src = ctx->eqx.p; avail = 1ull << ctx->dbg_mu; break;
+        case 1: dev_src = ctx->eqy.p; avail = 1ull << ctx->dbg_nu; break;
+        case 2: dev_src = ctx->snapA.p; avail = 1ull << ctx->dbg_delta; break;
+        case 3: dev_src = ctx->snapB.p; avail = 1ull << ctx->dbg_delta; break;
+        case 4: host_src = ctx->dbg_rx; avail = (uint64_t)ctx->dbg_mu; break;
+        case 5: host_src = ctx->dbg_ry; avail = (uint64_t)ctx->dbg_nu; break;
+        case 6: host_src = ctx->dbg_r; avail = (uint64_t)ctx->dbg_delta; break;
+        default: return IMM_E_SHAPE;
+        }
+        *count = avail;
+        uint64_t ncopy = avail < capacity ? avail : capacity;
+        if (!ncopy) return IMM_OK;
+        if (!out_host) return IMM_E_NULL;
+        if (host_src) {
+            std::memcpy(out_host, host_src, ncopy * sizeof(uint64_t));
+        } else {
+            IMM_HIP(hipDeviceSynchronize());
+            IMM_HIP(hipMemcpy(out_host, dev_src, ncopy * sizeof(uint64_t), hipMemcpyDeviceToHost));
+        }
+        return IMM_OK;
+    });
+}
+
+extern "C" int imm_debug_device_challenge(imm_ctx* ctx, void* stream, uint8_t state[32], uint64_t* out_host) {
+    return guarded([&]() -> int {
+        if (!ctx || !state || !out_host) return IMM_E_NULL;
+        IMM_HIP(hipSetDevice(ctx->device));
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        int rc;
+        if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
+        uint32_t st_in[8];
+        for (int i = 0; i < 8; ++i)
+            st_in[i] = (uint32_t)state[4 * i] << 24 | (uint32_t)state[4 * i + 1] << 16 | (uint32_t)state[4 * i + 2] << 8 |
+                       (uint32_t)state[4 * i + 3];
+        uint64_t* words = ctx->words.u64();
+        IMM_HIP(k::challenge_once(s, st_in, words, reinterpret_cast<uint32_t*>(words + 1)));
+        uint64_t hw[5];
+        if ((rc = fetch_words(ctx, s, words, 5, hw))) return rc;
+        *out_host = hw[0];
+        const uint32_t* st_out = reinterpret_cast<const uint32_t*>(hw + 1);
+        for (int i = 0; i < 8; ++i) {
+            state[4 * i] = (uint8_t)(st_out[i] >> 24);
+            state[4 * i + 1] = (uint8_t)(st_out[i] >> 16);
+            state[4 * i + 2] = (uint8_t)(st_out[i] >> 8);
+            state[4 * i + 3] = (uint8_t)st_out[i];
+        }
+        return IMM_OK;
+    });
 }
 
 extern "C" int imm_ldd_tv_kl(imm_ctx* ctx, void* stream, const float* logits_dev, const float* ref_dev, uint64_t T,
                              uint64_t n, uint64_t ld, double* tv_out_dev, double* kl_out_dev) {
-    if (!ctx || !logits_dev || !ref_dev || (!tv_out_dev && !kl_out_dev)) return IMM_E_NULL;
-    if (T == 0 || n == 0 || ld < n || T > 0x7FFFFFFFull || n > (1ull << 30)) return IMM_E_SHAPE;
-    IMM_HIP(hipSetDevice(ctx->device));
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    int rc;
-    if (ctx->ldd_partial.bytes < k::ldd_slot_bytes(T, n) || ctx->ldd_post.bytes < k::ldd_post_bytes(T) ||
-        ctx->ldd_sum.bytes < k::ldd_sum_bytes(T) || ctx->ldd_arrive.bytes < k::ldd_counter_bytes(T)) {
-        if ((rc = ctx->ldd_partial.ensure(k::ldd_slot_bytes(T, n)))) return rc;
-        if ((rc = ctx->ldd_post.ensure(k::ldd_post_bytes(T)))) return rc;
-        if ((rc = ctx->ldd_sum.ensure(k::ldd_sum_bytes(T)))) return rc;
-        if ((rc = ctx->ldd_arrive.ensure(k::ldd_counter_bytes(T)))) return rc;
-        IMM_HIP(k::ldd_init_sync(s, ctx->ldd_partial.u64(), ctx->ldd_partial.bytes, ctx->ldd_post.u64(),
-                                 ctx->ldd_post.bytes, ctx->ldd_sum.u64(), ctx->ldd_sum.bytes,
-                                 static_cast<uint32_t*>(ctx->ldd_arrive.p), ctx->ldd_arrive.bytes));
-    }
-    // a workgroup whose wait runs out finishes on its own, so the bound can be short: about 50 ms
-    const uint64_t wait_polls = ctx->spin_limit < (1ull << 15) ? ctx->spin_limit : (1ull << 15);
-    if ((rc = ctx->prof.begin(IMM_K_LDD, s))) return rc;
-    IMM_HIP(k::ldd_tv_kl(s, logits_dev, ref_dev, T, n, ld, ctx->ldd_partial.u64(), ctx->ldd_post.u64(),
-                         ctx->ldd_sum.u64(), static_cast<uint32_t*>(ctx->ldd_arrive.p), wait_polls, tv_out_dev, kl_out_dev));
-    return ctx->prof.end(IMM_K_LDD, s);
+    return guarded([&]() -> int {
+        if (!ctx || !logits_dev || !ref_dev || (!tv_out_dev && !kl_out_dev)) return IMM_E_NULL;
+        if (T == 0 || n == 0 || ld < n || T > 0x7FFFFFFFull || n > (1ull << 30)) return IMM_E_SHAPE;
+        IMM_HIP(hipSetDevice(ctx->device));
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        int rc;
+        if (ctx->ldd_partial.bytes < k::ldd_slot_bytes(T, n) || ctx->ldd_post.bytes < k::ldd_post_bytes(T) ||
+            ctx->ldd_sum.bytes < k::ldd_sum_bytes(T) || ctx->ldd_arrive.bytes < k::ldd_counter_bytes(T)) {
+            if ((rc = ctx->ldd_partial.ensure(k::ldd_slot_bytes(T, n)))) return rc;
+            if ((rc = ctx->ldd_post.ensure(k::ldd_post_bytes(T)))) return rc;
+            if ((rc = ctx->ldd_sum.ensure(k::ldd_sum_bytes(T)))) return rc;
+            if ((rc = ctx->ldd_arrive.ensure(k::ldd_counter_bytes(T)))) return rc;
+            IMM_HIP(k::ldd_init_sync(s, ctx->ldd_partial.u64(), ctx->ldd_partial.bytes, ctx->ldd_post.u64(),
+                                     ctx->ldd_post.bytes, ctx->ldd_sum.u64(), ctx->ldd_sum.bytes,
+                                     static_cast<uint32_t*>(ctx->ldd_arrive.p), ctx->ldd_arrive.bytes));
+        }
+        // a workgroup whose wait runs out finishes on its own, so the bound can be short: about 50 ms
+        const uint64_t wait_polls = ctx->spin_limit < (1ull << 15) ? ctx->spin_limit : (1ull << 15);
+        if ((rc = ctx->prof.begin(IMM_K_LDD, s))) return rc;
+        IMM_HIP(k::ldd_tv_kl(s, logits_dev, ref_dev, T, n, ld, ctx->ldd_partial.u64(), ctx->ldd_post.u64(),
+                             ctx->ldd_sum.u64(), static_cast<uint32_t*>(ctx->ldd_arrive.p), wait_polls, tv_out_dev, kl_out_dev));
+        return ctx->prof.end(IMM_K_LDD, s);
+    });
 }
 
 extern "C" int imm_topk_distance(imm_ctx* ctx, void* stream, const float* logits_dev, uint64_t T, uint64_t n,
                                  uint64_t ld, const int32_t* idx_dev, uint32_t K, double* out_dev) {
-    if (!ctx || !logits_dev || !idx_dev || !out_dev) return IMM_E_NULL;
-    if (T == 0 || n == 0 || ld < n || T > 0x7FFFFFFFull || n > 0x7FFFFFFFull) return IMM_E_SHAPE;
-    if (K < 1 || K > IMM_TOPK_MAX || K >= n) return IMM_E_SHAPE;
-    IMM_HIP(hipSetDevice(ctx->device));
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    int rc;
-    if ((rc = ctx->prof.begin(IMM_K_TOPK, s))) return rc;
-    IMM_HIP(k::topk_distance(s, logits_dev, T, n, ld, idx_dev, K, out_dev));
-    return ctx->prof.end(IMM_K_TOPK, s);
+    return guarded([&]() -> int {
+        if (!ctx || !logits_dev || !idx_dev || !out_dev) return IMM_E_NULL;
+        if (T == 0 || n == 0 || ld < n || T > 0x7FFFFFFFull || n > 0x7FFFFFFFull) return IMM_E_SHAPE;
+        if (K < 1 || K > IMM_TOPK_MAX || K >= n) return IMM_E_SHAPE;
+        IMM_HIP(hipSetDevice(ctx->device));
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        int rc;
+        if ((rc = ctx->prof.begin(IMM_K_TOPK, s))) return rc;
+        IMM_HIP(k::topk_distance(s, logits_dev, T, n, ld, idx_dev, K, out_dev));
+        return ctx->prof.end(IMM_K_TOPK, s);
+    });
 }
 
 extern "C" int imm_tail_density(imm_ctx* ctx, void* stream, const double* dist_dev, uint64_t T, double t1,
                                 double* out_host) {
-    if (!ctx || !dist_dev || !out_host) return IMM_E_NULL;
-    if (T == 0) return IMM_E_SHAPE;
-    IMM_HIP(hipSetDevice(ctx->device));
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    int rc;
-    if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
-    unsigned long long* count_dev = reinterpret_cast<unsigned long long*>(ctx->words.u64());
-    IMM_HIP(k::tail_count(s, dist_dev, T, t1, count_dev));
-    uint64_t count = 0;
-    if ((rc = fetch_words(ctx, s, ctx->words.u64(), 1, &count))) return rc;
-    *out_host = (double)count / (double)T;
-    return IMM_OK;
+    return guarded([&]() -> int {
+        if (!ctx || !dist_dev || !out_host) return IMM_E_NULL;
+        if (T == 0) return IMM_E_SHAPE;
+        IMM_HIP(hipSetDevice(ctx->device));
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        int rc;
+        if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
+        unsigned long long* count_dev = reinterpret_cast<unsigned long long*>(ctx->words.u64());
+        IMM_HIP(k::tail_count(s, dist_dev, T, t1, count_dev));
+        uint64_t count = 0;
+        if ((rc = fetch_words(ctx, s, ctx->words.u64(), 1, &count))) return rc;
+        *out_host = (double)count / (double)T;
+        return IMM_OK;
+    });
 }
 
 // ------------------------------------------------------------------ commitments from device memory
 extern "C" int imm_commit_tables_device(imm_ctx* ctx, void* stream, int count, const imm_table_desc* tables,
                                         imm_commit1* out_host) {
-    using namespace imm;
-    if (!ctx || (count > 0 && (!tables || !out_host))) return IMM_E_NULL;
-    if (count < 0) return IMM_E_SHAPE;
-    if (count == 0) return IMM_OK;
-    constexpr uint64_t kLeafBytes = 1ull << 20, kMaxLeaves = 1ull << 22;
-    const uint64_t lim = 1ull << IMM_MAX_ROUNDS;
-    std::vector<k::LeafDesc> leaves;
-    std::vector<uint64_t> first(count + 1, 0);  // first[t]: index of table t's first leaf
-    bool aligned16 = true;
-    for (int t = 0; t < count; ++t) {
-        const imm_table_desc& d = tables[t];
-        if (!d.table_dev) return IMM_E_NULL;
-        if (d.rows == 0 || d.cols == 0 || d.rows > lim || d.cols > lim) return IMM_E_SHAPE;
-        const uint64_t elem = d.dtype == IMM_I8 ? 1 : d.dtype == IMM_I16 ? 2 : d.dtype == IMM_I64 ? 8 : 0;
-        if (!elem) return IMM_E_DTYPE;
-        const uintptr_t addr = reinterpret_cast<uintptr_t>(d.table_dev);
-        if (addr % 4) return IMM_E_SHAPE;
-        aligned16 = aligned16 && addr % 16 == 0;
-        const uint64_t bytes = d.rows * d.cols * elem;  // < 2^53
-        const uint64_t n = (bytes + kLeafBytes - 1) / kLeafBytes;
-        first[t + 1] = first[t] + n;
-        if (first[t + 1] > kMaxLeaves) return IMM_E_SHAPE;
-        for (uint64_t i = 0; i < n; ++i)
-            leaves.push_back({static_cast<const uint8_t*>(d.table_dev) + i * kLeafBytes,
-                              std::min(kLeafBytes, bytes - i * kLeafBytes)});
-    }
-    IMM_HIP(hipSetDevice(ctx->device));
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    int rc;
-    const size_t total = leaves.size();
-    if ((rc = ctx->commit_leaves.ensure(sizeof(k::LeafDesc) * total))) return rc;
-    if ((rc = ctx->commit_digests.ensure(32 * total))) return rc;
-    // (the descriptors are in pageable memory: the copy has left `leaves` when the call returns)
-    IMM_HIP(hipMemcpyAsync(ctx->commit_leaves.p, leaves.data(), sizeof(k::LeafDesc) * total, hipMemcpyHostToDevice, s));
-    if ((rc = ctx->prof.begin(IMM_K_COMMIT, s))) return rc;
-    IMM_HIP(k::commit_leaves(s, static_cast<const k::LeafDesc*>(ctx->commit_leaves.p), (uint32_t)total, aligned16,
-                             static_cast<uint8_t*>(ctx->commit_digests.p)));
-    if ((rc = ctx->prof.end(IMM_K_COMMIT, s))) return rc;
-    std::vector<uint8_t> digests(32 * total);
-    IMM_HIP(hipMemcpyAsync(digests.data(), ctx->commit_digests.p, digests.size(), hipMemcpyDeviceToHost, s));
-    IMM_HIP(hipStreamSynchronize(s));
-    for (int t = 0; t < count; ++t) {
-        const imm_table_desc& d = tables[t];
-        Sha256 top;
-        uint8_t hdr[13 + 4 + 8 + 8];
-        std::memcpy(hdr, "IMM-COMMIT-v1", 13);
-        for (int i = 0; i < 4; ++i) hdr[13 + i] = (uint8_t)(d.dtype >> (8 * i));
-        for (int i = 0; i < 8; ++i) hdr[17 + i] = (uint8_t)(d.rows >> (8 * i));
-        for (int i = 0; i < 8; ++i) hdr[25 + i] = (uint8_t)(d.cols >> (8 * i));
-        top.update(hdr, sizeof(hdr));
-        top.update(digests.data() + 32 * first[t], 32 * (size_t)(first[t + 1] - first[t]));
-        top.finish(out_host[t].digest);
-        out_host[t].rows = d.rows;
-        out_host[t].cols = d.cols;
-        out_host[t].dtype = d.dtype;
-        out_host[t]._pad = 0;
-    }
-    return ctx->prof.mask ? ctx->prof.flush() : IMM_OK;
+    return guarded([&]() -> int {
+        using namespace imm;
+        if (!ctx || (count > 0 && (!tables || !out_host))) return IMM_E_NULL;
+        if (count < 0) return IMM_E_SHAPE;
+        if (count == 0) return IMM_OK;
+        constexpr uint64_t kLeafBytes = 1ull << 20, kMaxLeaves = 1ull << 22;
+        const uint64_t lim = 1ull << IMM_MAX_ROUNDS;
+        std::vector<k::LeafDesc> leaves;
+        std::vector<uint64_t> first(count + 1, 0);  // first[t]: index of table t's first leaf
+        bool aligned16 = true;
+        for (int t = 0; t < count; ++t) {
+            const imm_table_desc& d = tables[t];
+            if (!d.table_dev) return IMM_E_NULL;
+            if (d.rows == 0 || d.cols == 0 || d.rows > lim || d.cols > lim) return IMM_E_SHAPE;
+            const uint64_t elem = d.dtype == IMM_I8 ? 1 : d.dtype == IMM_I16 ? 2 : d.dtype == IMM_I64 ? 8 : 0;
+            if (!elem) return IMM_E_DTYPE;
+            const uintptr_t addr = reinterpret_cast<uintptr_t>(d.table_dev);
+            if (addr % 4) return IMM_E_SHAPE;
+            aligned16 = aligned16 && addr % 16 == 0;
+            const uint64_t bytes = d.rows * d.cols * elem;  // < 2^53
+            const uint64_t n = (bytes + kLeafBytes - 1) / kLeafBytes;
+            first[t + 1] = first[t] + n;
+            if (first[t + 1] > kMaxLeaves) return IMM_E_SHAPE;
+            for (uint64_t i = 0; i < n; ++i)
+                leaves.push_back({static_cast<const uint8_t*>(d.table_dev) + i * kLeafBytes,
+                                  std::min(kLeafBytes, bytes - i * kLeafBytes)});
+        }
+        IMM_HIP(hipSetDevice(ctx->device));
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        int rc;
+        const size_t total = leaves.size();
+        if ((rc = ctx->commit_leaves.ensure(sizeof(k::LeafDesc) * total))) return rc;
+        if ((rc = ctx->commit_digests.ensure(32 * total))) return rc;
+        // (the descriptors are in pageable memory: the copy has left `leaves` when the call returns)
+        IMM_HIP(hipMemcpyAsync(ctx->commit_leaves.p, leaves.data(), sizeof(k::LeafDesc) * total, hipMemcpyHostToDevice, s));
+        if ((rc = ctx->prof.begin(IMM_K_COMMIT, s))) return rc;
+        IMM_HIP(k::commit_leaves(s, static_cast<const k::LeafDesc*>(ctx->commit_leaves.p), (uint32_t)total, aligned16,
+                                 static_cast<uint8_t*>(ctx->commit_digests.p)));
+        if ((rc = ctx->prof.end(IMM_K_COMMIT, s))) return rc;
+        std::vector<uint8_t> digests(32 * total);
+        IMM_HIP(hipMemcpyAsync(digests.data(), ctx->commit_digests.p, digests.size(), hipMemcpyDeviceToHost, s));
+        IMM_HIP(hipStreamSynchronize(s));
+        for (int t = 0; t < count; ++t) {
+            const imm_table_desc& d = tables[t];
+            Sha256 top;
+            uint8_t hdr[13 + 4 + 8 + 8];
+            std::memcpy(hdr, "IMM-COMMIT-v1", 13);
+            for (int i = 0; i < 4; ++i) hdr[13 + i] = (uint8_t)(d.dtype >> (8 * i));
+            for (int i = 0; i < 8; ++i) hdr[17 + i] = (uint8_t)(d.rows >> (8 * i));
+            for (int i = 0; i < 8; ++i) hdr[25 + i] = (uint8_t)(d.cols >> (8 * i));
+            top.update(hdr, sizeof(hdr));
+            top.update(digests.data() + 32 * first[t], 32 * (size_t)(first[t + 1] - first[t]));
+            top.finish(out_host[t].digest);
+            out_host[t].rows = d.rows;
+            out_host[t].cols = d.cols;
+            out_host[t].dtype = d.dtype;
+            out_host[t]._pad = 0;
+        }
+        return ctx->prof.mask ? ctx->prof.flush() : IMM_OK;
+    });
 }

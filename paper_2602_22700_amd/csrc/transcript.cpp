@@ -28,10 +28,18 @@ void Transcript::absorb(const char tag[4], const void* data, size_t len) {
 }
 
 void Transcript::absorb_words(const char tag[4], const uint64_t* words, size_t count) {
-    uint8_t tmp[8 * 8];
-    if (count > 8) count = 8;  // callers absorb at most three words at a time
-    for (size_t i = 0; i < count; ++i) put_u64le(tmp + 8 * i, words[i]);
-    absorb(tag, tmp, 8 * count);
+    Sha256 h;
+    uint8_t hdr[44];
+    std::memcpy(hdr, s, 32);
+    std::memcpy(hdr + 32, tag, 4);
+    put_u64le(hdr + 36, (uint64_t)(8 * count));
+    h.update(hdr, sizeof(hdr));
+    for (size_t i = 0; i < count; ++i) {
+        uint8_t le[8];
+        put_u64le(le, words[i]);
+        h.update(le, 8);
+    }
+    h.finish(s);
 }
 
 uint64_t Transcript::challenge() {

@@ -2,6 +2,7 @@
 // product, and (when the matrices are supplied) the digests and the openings.
 #include <algorithm>
 #include <cstring>
+#include <new>
 #include <thread>
 #include <vector>
 
@@ -70,16 +71,18 @@ bool digest_matches(const void* raw, size_t bytes, uint32_t dtype, uint64_t rows
 }  // namespace
 }  // namespace imm
 
-extern "C" int imm_verify(const imm_commit* com, const uint8_t transcript_in[32], const imm_proof* proof,
-                          const int16_t* A, const int8_t* B, const int64_t* C, uint8_t transcript_out[32],
-                          int* fail_round) {
-    using namespace imm;
+namespace imm {
+namespace {
+
+int verify_body(const imm_commit* com, const uint8_t transcript_in[32], const imm_proof* proof, const int16_t* A,
+                const int8_t* B, const int64_t* C, uint8_t transcript_out[32], int* fail_round) {
     if (fail_round) *fail_round = 0;
     if (!com || !transcript_in || !proof) return IMM_E_NULL;
     const uint64_t m = com->A.rows, d = com->A.cols, n = com->B.cols;
     const uint64_t lim = 1ull << IMM_MAX_ROUNDS;
     if (m == 0 || d == 0 || n == 0 || m > lim || d > lim || n > lim) return IMM_E_SHAPE;
     if (com->B.rows != d || com->C.rows != m || com->C.cols != n) return IMM_E_SHAPE;
+    if (com->A.dtype != IMM_I16 || com->B.dtype != IMM_I8 || com->C.dtype != IMM_I64) return IMM_E_DTYPE;
     const int mu = hf::ceil_log2(m), delta = hf::ceil_log2(d), nu = hf::ceil_log2(n);
 
     if (proof->version != IMM_PROOF_VERSION || (int)proof->mu != mu || (int)proof->delta != delta ||
@@ -121,5 +124,51 @@ extern "C" int imm_verify(const imm_commit* com, const uint8_t transcript_in[32]
         if (C && open_matrix(C, m, n, ex, ey) != proof->c0) return IMM_REJ_OPEN_C;
     }
     if (transcript_out) std::memcpy(transcript_out, tr.s, 32);
+    // Without all three openings c0, vA and vB are not tied to the commitments: a prover is free to
+    // choose c0 and consistent round messages.  That is not an accept.
+    return (A && B && C) ? IMM_OK : IMM_REJ_UNOPENED;
+}
+
+}  // namespace
+}  // namespace imm
+
+extern "C" int imm_verify_points(const imm_commit* com, const uint8_t transcript_in[32], const imm_proof* proof,
+                                 uint64_t* rx_out, uint64_t* ry_out, uint64_t* r_out) {
+    using namespace imm;
+    if (!com || !transcript_in || !proof) return IMM_E_NULL;
+    const uint64_t m = com->A.rows, d = com->A.cols, n = com->B.cols;
+    const uint64_t lim = 1ull << IMM_MAX_ROUNDS;
+    if (m == 0 || d == 0 || n == 0 || m > lim || d > lim || n > lim) return IMM_E_SHAPE;
+    if (com->B.rows != d || com->C.rows != m || com->C.cols != n) return IMM_E_SHAPE;
+    if (com->A.dtype != IMM_I16 || com->B.dtype != IMM_I8 || com->C.dtype != IMM_I64) return IMM_E_DTYPE;
+    const int mu = hf::ceil_log2(m), delta = hf::ceil_log2(d), nu = hf::ceil_log2(n);
+    if (proof->version != IMM_PROOF_VERSION || (int)proof->mu != mu || (int)proof->delta != delta ||
+        (int)proof->nu != nu || proof->c0 >= hf::P)
+        return IMM_REJ_FORMAT;
+    for (int k = 0; k < 3 * delta; ++k)
+        if (proof->g[k] >= hf::P) return IMM_REJ_FORMAT;
+    Transcript tr(transcript_in);
+    uint64_t rx[IMM_MAX_ROUNDS] = {}, ry[IMM_MAX_ROUNDS] = {}, r[IMM_MAX_ROUNDS] = {};
+    tr.head(m, d, n, com->A.digest, com->B.digest, com->C.digest, mu, nu, rx, ry);
+    tr.absorb_words("clmC", &proof->c0, 1);
+    for (int k = 0; k < delta; ++k) {
+        tr.absorb_words("rnd ", &proof->g[3 * k], 3);
+        r[k] = tr.challenge();
+    }
+    if (rx_out) std::memcpy(rx_out, rx, sizeof(rx));
+    if (ry_out) std::memcpy(ry_out, ry, sizeof(ry));
+    if (r_out) std::memcpy(r_out, r, sizeof(r));
     return IMM_OK;
+}
+
+extern "C" int imm_verify(const imm_commit* com, const uint8_t transcript_in[32], const imm_proof* proof,
+                          const int16_t* A, const int8_t* B, const int64_t* C, uint8_t transcript_out[32],
+                          int* fail_round) {
+    try {
+        return imm::verify_body(com, transcript_in, proof, A, B, C, transcript_out, fail_round);
+    } catch (const std::bad_alloc&) {
+        return IMM_E_NOMEM;  // e.g. the eq vector of a 2^32-row statement
+    } catch (...) {
+        return IMM_E_STATE;
+    }
 }

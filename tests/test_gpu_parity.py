@@ -196,7 +196,7 @@ def check_proof(torch, ctx, oracle_fast, A, B, C=None, state=ref.FS_INIT, interm
     if verify_open:
         assert imm.imm_verify(com, state, got, A, B, C) == (0, s_want, 0)
     else:
-        assert imm.imm_verify(com, state, got) == (0, s_want, 0)
+        assert imm.imm_verify(com, state, got) == (imm.IMM_REJ_UNOPENED, s_want, 0)
     return got, s_got
 
 
@@ -279,7 +279,7 @@ def test_config3_ffn_up_projection(torch, ctx, oracle_fast):
     assert imm.imm_verify(com, ref.FS_INIT, got, None, None, Cb)[0] == 6
     comb = imm.imm_commit_matmul(None, None, Cb, 2048, 4096, 14336, out=com)
     bad, _ = ctx.imm_sumcheck_matmul_prove(dev(torch, A), dev(torch, B), comb, ref.FS_INIT)
-    assert imm.imm_verify(comb, ref.FS_INIT, bad)[0] == 0
+    assert imm.imm_verify(comb, ref.FS_INIT, bad)[0] == imm.IMM_REJ_UNOPENED
     assert imm.imm_verify(comb, ref.FS_INIT, bad, None, None, Cb)[0] == 5
 
 
@@ -302,6 +302,32 @@ def test_config4_moe_expert_batch(torch, ctx, oracle_fast):
         assert got[e].mu == ref.ceil_log2(len(routes[e]))
     assert final == want_states[-1]
     assert {int(p.mu) for p in got} <= {10, 11}
+    # the same eight proofs in the other execution modes: narrow-read reductions, the transcript hashed
+    # by the round kernel, weights widened beforehand
+    for mode, got_m, states_m, final_m in other_modes(ctx, items, False, ref.FS_INIT):
+        assert [p.words() for p in got_m] == [ref.proof_words(p) for p in want], mode
+        assert states_m == want_states and final_m == want_states[-1], mode
+
+
+def other_modes(ctx, items, chained, state):
+    """Runs a batch in the execution modes beside the default one (widened tables, host transcript);
+    yields (mode, proofs, states, final state) for each."""
+    try:
+        ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 0)
+        yield ("narrow-read",) + tuple(ctx.imm_sumcheck_matmul_prove_batch(items, chained, state))
+        ctx.imm_ctx_set_option(imm.IMM_OPT_TRANSCRIPT, imm.IMM_TRANSCRIPT_DEVICE)
+        yield ("narrow-read, device transcript",) + tuple(ctx.imm_sumcheck_matmul_prove_batch(items, chained, state))
+        ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
+        yield ("widened, device transcript",) + tuple(ctx.imm_sumcheck_matmul_prove_batch(items, chained, state))
+        ctx.imm_ctx_set_option(imm.IMM_OPT_TRANSCRIPT, imm.IMM_TRANSCRIPT_HOST)
+        pre = [(A, ctx.imm_encode(B), com) for (A, B, com) in items]
+        yield ("weights pre-encoded",) + tuple(ctx.imm_sumcheck_matmul_prove_batch(pre, chained, state))
+        ctx.imm_ctx_set_option(imm.IMM_OPT_TRANSCRIPT, imm.IMM_TRANSCRIPT_DEVICE)
+        yield ("weights pre-encoded, device transcript",) + tuple(ctx.imm_sumcheck_matmul_prove_batch(pre, chained, state))
+        del pre
+    finally:
+        ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
+        ctx.imm_ctx_set_option(imm.IMM_OPT_TRANSCRIPT, imm.IMM_TRANSCRIPT_HOST)
 
 
 @pytest.mark.timeout(1200)
@@ -320,6 +346,12 @@ def test_config5_dense_layers_chained(torch, ctx, oracle_fast):
             oracle_items.append((A, B, C, com.digests()))
             items.append((dev(torch, A), dev(torch, B), com))
         want, want_states = oracle_fast.prove_chain(oracle_items, chained=True, state_in=s_cpu)
+        if layer in (0, layers - 1):
+            # first and last layer also in the other execution modes (W_down has d = 14336: its tables
+            # of 2^14 entries enter the round loop through the hand-over from global memory to LDS)
+            for mode, got_m, states_m, final_m in other_modes(ctx, items, True, s_gpu):
+                assert [p.words() for p in got_m] == [ref.proof_words(p) for p in want], (layer, mode)
+                assert states_m == want_states and final_m == want_states[-1], (layer, mode)
         got, states, s_gpu = ctx.imm_sumcheck_matmul_prove_batch(items, True, s_gpu)
         s_cpu = want_states[-1]
         for t in range(7):
@@ -385,7 +417,7 @@ def test_proofs_are_deterministic_and_survive_other_streams(torch, ctx, oracle_f
     Ad, Bd = dev(torch, A), dev(torch, B)
     first, s_first = ctx.imm_sumcheck_matmul_prove(Ad, Bd, com, ref.FS_INIT)
     side = torch.cuda.Stream()
-    for _ in range(20):
+    for _ in range(100):
         p, s = ctx.imm_sumcheck_matmul_prove(Ad, Bd, com, ref.FS_INIT)
         assert p.words() == first.words() and s == s_first
     side.wait_stream(torch.cuda.current_stream())
@@ -495,6 +527,15 @@ def test_argument_errors(torch, ctx):
              ctypes.byref(pr)) == -2
     assert f(h, None, A.data_ptr(), 1, B.data_ptr(), 1, 2, 2, 2, ctypes.byref(com), st, ctypes.byref(pr)) == -3
     assert f(h, None, A.data_ptr(), 2, B.data_ptr(), 2, 2, 2, 2, ctypes.byref(com), st, ctypes.byref(pr)) == -3
+    # commitments that are not those of the statement: other shapes, or not int16 x int8 -> int64
+    zero = np.zeros((2, 2))
+    good = imm.imm_commit_matmul(zero.astype(np.int16), zero.astype(np.int8), zero.astype(np.int64), 2, 2, 2)
+    assert f(h, None, A.data_ptr(), 2, B.data_ptr(), 1, 2, 2, 2, ctypes.byref(com), st, ctypes.byref(pr)) == -2
+    assert f(h, None, A.data_ptr(), 2, B.data_ptr(), 1, 2, 2, 1, ctypes.byref(good), st, ctypes.byref(pr)) == -2
+    good.C.dtype = imm.IMM_I16
+    assert f(h, None, A.data_ptr(), 2, B.data_ptr(), 1, 2, 2, 2, ctypes.byref(good), st, ctypes.byref(pr)) == -3
+    good.C.dtype = imm.IMM_I64
+    assert f(h, None, A.data_ptr(), 2, B.data_ptr(), 1, 2, 2, 2, ctypes.byref(good), st, ctypes.byref(pr)) == 0
     out = ctypes.c_uint64(0)
     assert L.imm_mle_eval(h, None, A.data_ptr(), 2, 2, 2, 1, None, None, ctypes.byref(out)) == -2   # ld < cols
     assert L.imm_mle_eval(h, None, A.data_ptr(), 9, 2, 2, 2, None, None, ctypes.byref(out)) == -3

@@ -107,10 +107,57 @@ def make_case(oracle_fast, m, d, n, seed):
 def test_verify_accepts_oracle_proofs(lib, oracle_fast, shape):
     m, d, n = shape
     A, B, C, com, proof, s_out = make_case(oracle_fast, m, d, n, 77 + m + d + n)
+    # without the matrices nothing ties c0, vA, vB to the commitments: consistent, but not an accept
     code, st, fr = imm.imm_verify(com, ref.FS_INIT, to_proof(proof))
-    assert (code, st, fr) == (0, s_out, 0)
+    assert (code, st, fr) == (imm.IMM_REJ_UNOPENED, s_out, 0)
+    assert oracle_fast.verify(proof, m, d, n, com.digests())[0] == 0      # the oracle's transcript-only replay
+    for part in ((A, None, None), (None, B, None), (None, None, C), (A, B, None), (A, None, C), (None, B, C)):
+        assert imm.imm_verify(com, ref.FS_INIT, to_proof(proof), *part)[0] == imm.IMM_REJ_UNOPENED
     code, st, fr = imm.imm_verify(com, ref.FS_INIT, to_proof(proof), A, B, C)
     assert (code, st, fr) == (0, s_out, 0)
+    assert oracle_fast.verify(proof, m, d, n, com.digests(), A=A, B=B, C=C)[0] == 0
+
+
+def test_a_proof_with_a_freely_chosen_claim_is_never_accepted_without_openings(lib, oracle_fast):
+    """A prover that picks c0 at will and answers every round consistently passes all transcript checks;
+    only the openings catch it.  The verifier must not report ACCEPT for it in any call form."""
+    m, d, n = 4, 4, 4
+    A, B, C, com, proof, _ = make_case(oracle_fast, m, d, n, 31)
+    tr = ref.Transcript(ref.FS_INIT)
+    tr.absorb(b"shap", ref.u64le(m) + ref.u64le(d) + ref.u64le(n))
+    for tag, dg in zip((b"comA", b"comB", b"comC"), com.digests()):
+        tr.absorb(tag, dg)
+    for _ in range(2 + 2):
+        tr.challenge()
+    c0 = 123456789
+    forged = dict(proof, c0=c0, g=[])
+    tr.absorb_field(b"clmC", [c0])
+    claim = c0
+    for k in range(2):
+        g = [claim, 0, (P - claim) % P]          # g(0) + g(1) = claim; a line through the two points
+        forged["g"] += g
+        tr.absorb_field(b"rnd ", g)
+        r = tr.challenge()
+        claim = ref.interpolate3(g[0], g[1], g[2], r)
+    forged["vA"], forged["vB"] = claim, 1
+    assert imm.imm_verify(com, ref.FS_INIT, to_proof(forged))[0] == imm.IMM_REJ_UNOPENED
+    assert imm.imm_verify(com, ref.FS_INIT, to_proof(forged), A, B, C)[0] in (3, 4, 5)
+    assert imm.imm_verify(com, ref.FS_INIT, to_proof(forged), None, None, C)[0] == 5
+
+
+def test_verify_points_match_the_oracle_trace(lib, oracle_fast):
+    rng = np.random.default_rng(8)
+    A = rng.integers(-2**15, 2**15, size=(5, 9), dtype=np.int16)
+    B = rng.integers(-128, 128, size=(9, 3), dtype=np.int8)
+    C = oracle_fast.matmul(A, B)
+    com = imm.imm_commit_matmul(A, B, C, 5, 9, 3)
+    trace = {}
+    proof, _ = oracle_fast.prove(A, B, C, com.digests(), trace=trace)
+    rx, ry, r = imm.imm_verify_points(com, ref.FS_INIT, to_proof(proof))
+    assert (rx, ry, r) == (trace["rx"], trace["ry"], trace["r"])
+    # the three proof values are the openings at those points
+    assert proof["c0"] == oracle_fast.mle_matrix(C, rx, ry)
+    assert proof["vA"] == oracle_fast.mle_matrix(A, rx, r) and proof["vB"] == oracle_fast.mle_matrix(B, r, ry)
 
 
 def test_verify_reject_codes_match_oracle_on_every_mutation(lib, oracle_fast):
@@ -156,7 +203,7 @@ def test_verify_format_commit_and_opening_rejections(lib, oracle_fast):
             # committed wrong C, sumcheck of the true product: opening of C fails
             comb = imm.imm_commit_matmul(A, B, Cb, m, d, n)
             pb, _ = oracle_fast.prove(A, B, None, comb.digests())
-            assert imm.imm_verify(comb, ref.FS_INIT, to_proof(pb))[0] == 0
+            assert imm.imm_verify(comb, ref.FS_INIT, to_proof(pb))[0] == imm.IMM_REJ_UNOPENED
             assert imm.imm_verify(comb, ref.FS_INIT, to_proof(pb), None, None, Cb)[0] == 5
     Ab = A.copy(); Ab[0, 0] ^= 1
     assert imm.imm_verify(com, ref.FS_INIT, pr, Ab, None, None)[0] == 6
@@ -179,6 +226,9 @@ def test_verify_argument_errors(lib, oracle_fast):
     ctypes.memmove(ctypes.byref(bad), ctypes.byref(com), ctypes.sizeof(com))
     bad.B.rows = 3
     assert lib.imm_verify(ctypes.byref(bad), st, ctypes.byref(pr), None, None, None, None, None) == -2
+    bad.B.rows = 2
+    bad.C.dtype = imm.IMM_I16
+    assert lib.imm_verify(ctypes.byref(bad), st, ctypes.byref(pr), None, None, None, None, None) == -3
 
 
 def test_verify_chained_states(lib, oracle_fast):
@@ -195,5 +245,7 @@ def test_verify_chained_states(lib, oracle_fast):
     s = ref.FS_INIT
     for com, pr, st in zip(coms, proofs, states):
         code, s_next, _ = imm.imm_verify(com, s, to_proof(pr))
-        assert code == 0 and s_next == st
+        assert code == imm.IMM_REJ_UNOPENED and s_next == st
+        A, B, C, _ = items[coms.index(com)]
+        assert imm.imm_verify(com, s, to_proof(pr), A, B, C) == (0, st, 0)
         s = s_next
