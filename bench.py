@@ -145,6 +145,11 @@ def main():
                     help="log2 of the table length of the stand-alone fold-kernel measurement (0 = skip)")
     ap.add_argument("--ldd-steps", type=int, default=2048,
                     help="decision steps of the logit-distance measurement (vocabulary 128256, K = 20); 0 skips it")
+    ap.add_argument("--timeline", action="store_true",
+                    help="after the timed region, prove the first statement 20 more times in each execution mode with the "
+                         "library's host-side time marks switched on and report them (field host_timeline): medians in "
+                         "microseconds from the call's entry, and the absolute CLOCK_MONOTONIC marks of the last proof "
+                         "for lining up with a rocprofv3 kernel trace of the same run")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy three times (reference dispatches for scaling "
                          "hardware byte counters collected with rocprofv3 --pmc)")
@@ -292,6 +297,28 @@ def main():
                                        "run of this command, not measured in this run; null once the kernel sources differ)",
                      "avg_launch_us": round(avg_ms * 1e3, 2), "algorithmic_bytes_per_launch": dom_bytes / max(launches_per_step, 1)},
     }
+
+    if args.timeline:
+        import statistics
+        Ad0, Bd0, com0 = items[0]
+        Bpre0 = ctx.imm_encode(Bd0)
+        ctx.imm_ctx_set_option(imm.IMM_OPT_TIMELINE, 1)
+        tl = {}
+        for mode, Bx, widen in (("widened", Bd0, 1), ("weights_preencoded", Bpre0, 1), ("narrow_read", Bd0, 0)):
+            ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, widen)
+            runs = []
+            for _ in range(23):
+                ctx.imm_sumcheck_matmul_prove(Ad0, Bx, com0, s0)
+                runs.append(ctx.imm_debug_timeline())
+            runs = runs[3:]
+            names = [nm for nm, _ in runs[-1]]
+            tl[mode] = {"us_from_entry_median": {nm: round(statistics.median((r[i][1] - r[0][1]) / 1e3 for r in runs), 2)
+                                                 for i, nm in enumerate(names)},
+                        "last_proof_monotonic_ns": {nm: t for nm, t in runs[-1]}}
+        ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
+        ctx.imm_ctx_set_option(imm.IMM_OPT_TIMELINE, 0)
+        result["host_timeline"] = tl
+        del Bpre0
 
     # Opening of C at (rx || ry): the bilinear MLE of the int64 product matrix, streamed once by the
     # same row-wise reduction (8 B per entry), as a verifier-side check would need it.

@@ -328,9 +328,10 @@ int imm_debug_device_challenge(imm_ctx* ctx, void* stream, uint8_t state[32], ui
                                      into the host's address space; otherwise, and with 0, r_k goes through the
                                      mailbox in pinned host memory) */
 #define IMM_OPT_FUSE_REDUCTIONS 7 /* 1 (default): in narrow-read mode the partial evaluations of A and of B run in
-                                     one launch where the operand forms allow it, and with widened tables the sum
-                                     of A's partial vectors rides in the launch of B's reduction and the widening
-                                     of two raw operands shares a launch with the eq vectors; 0: one launch each */
+                                     one launch where the operand forms allow it (the workgroup of A's part that
+                                     finishes last sums its partial vectors); with widened tables the sum of A's
+                                     partial vectors rides in the launch of B's reduction and the widening of two
+                                     raw operands shares a launch with the eq vectors; 0: one launch each */
 #define IMM_OPT_ENCODE_AHEAD 8    /* 1 (default): in a batch proved one proof after the other, the raw operands of
                                      up to three proofs beyond the current one are widened (IMM_OPT_WIDEN) on a
                                      second stream of the library's own while the current one runs, into a ring
@@ -338,7 +339,26 @@ int imm_debug_device_challenge(imm_ctx* ctx, void* stream, uint8_t state[32], ui
                                      on the caller's stream up to that point, so operands only have to be ready
                                      in the caller's stream order, as without it, and no table outlives the call.
                                      0: every proof widens its own operands */
+#define IMM_OPT_TIMELINE 9        /* value != 0: the host notes the time (CLOCK_MONOTONIC, ns) at which a proof
+                                     passes the points IMM_T_* below; imm_debug_timeline returns the notes of
+                                     the most recent proof (default 0) */
 int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value);
+
+/* Points of a proof on the host's side (IMM_OPT_TIMELINE). */
+#define IMM_T_ENTRY 0                /* the call has validated its arguments */
+#define IMM_T_HEAD_HASHED 1          /* shapes and commitments absorbed, rx and ry squeezed */
+#define IMM_T_FRONT_LAUNCHED 2       /* eq vectors (and the widening, where it shares their launch) queued */
+#define IMM_T_REDUCTIONS_LAUNCHED 3  /* both partial evaluations queued */
+#define IMM_T_ROUNDS_LAUNCHED 4      /* round kernel queued */
+#define IMM_T_FIRST_MESSAGE 5        /* g_1 has arrived in the mailbox */
+#define IMM_T_FIRST_CHALLENGE 6      /* r_1 posted */
+#define IMM_T_LAST_CHALLENGE 7       /* r_delta posted */
+#define IMM_T_FINAL_VALUES 8         /* vA, vB have arrived */
+#define IMM_T_EXIT 9                 /* the call is about to return */
+#define IMM_T_COUNT 10
+/* Copies at most `capacity` notes (ids[i], ns[i]; either may be NULL) of the most recent proof of this
+ * context and stores their number in *count.  IMM_E_STATE unless IMM_OPT_TIMELINE is set. */
+int imm_debug_timeline(imm_ctx* ctx, uint32_t* ids, uint64_t* ns, uint32_t capacity, uint32_t* count);
 
 /* Per-kernel timing with HIP events on the launch stream.  Kernel ids: */
 #define IMM_K_ENCODE_A 0

@@ -22,6 +22,9 @@ IMM_OPT_DEBUG_SNAPSHOTS, IMM_OPT_WIDEN, IMM_OPT_TRANSCRIPT, IMM_OPT_SPIN_LIMIT, 
 IMM_OPT_REPLY_IN_DEVICE_MEMORY = 6
 IMM_OPT_FUSE_REDUCTIONS = 7
 IMM_OPT_ENCODE_AHEAD = 8
+IMM_OPT_TIMELINE = 9
+TIMELINE_NAMES = ["entry", "head_hashed", "front_launched", "reductions_launched", "rounds_launched", "first_message",
+                  "first_challenge", "last_challenge", "final_values", "exit"]
 IMM_TRANSCRIPT_DEVICE, IMM_TRANSCRIPT_HOST = 0, 1
 (IMM_K_ENCODE_A, IMM_K_ENCODE_B, IMM_K_EQ, IMM_K_REDUCE_A, IMM_K_REDUCE_B, IMM_K_ROUND,
  IMM_K_COMBINE, IMM_K_LDD, IMM_K_TOPK, IMM_K_COMMIT, IMM_K_COUNT) = range(11)
@@ -37,7 +40,7 @@ EXPORTS = [
     "imm_verify", "imm_debug_fetch", "imm_ctx_set_option", "imm_ctx_set_profiling", "imm_ctx_kernel_time",
     "imm_ctx_reset_profiling", "imm_ldd_tv_kl", "imm_topk_distance", "imm_tail_density",
     "imm_commit_tables_device", "imm_mle_eval_static", "imm_verify_points", "imm_transcript_challenge",
-    "imm_debug_device_challenge",
+    "imm_debug_device_challenge", "imm_debug_timeline",
 ]
 
 
@@ -126,6 +129,7 @@ def load() -> ctypes.CDLL:
     L.imm_verify_points.argtypes = [ctypes.POINTER(Commit), vp, ctypes.POINTER(Proof), vp, vp, vp]
     L.imm_transcript_challenge.argtypes = [vp, ctypes.POINTER(u64)]
     L.imm_debug_device_challenge.argtypes = [vp, vp, vp, ctypes.POINTER(u64)]
+    L.imm_debug_timeline.argtypes = [vp, vp, vp, u32, ctypes.POINTER(u32)]
     for name in EXPORTS:
         if name != "imm_last_error":
             getattr(L, name).restype = i32
@@ -403,6 +407,12 @@ class Context:
                                         ctypes.byref(r) if r is not None else None, g)
         _check(rc, "imm_round_fold_eval")
         return [int(v) for v in g]
+
+    def imm_debug_timeline(self) -> List[Tuple[str, int]]:
+        """[(point name, CLOCK_MONOTONIC ns)] of the most recent proof (needs IMM_OPT_TIMELINE)."""
+        ids, ns, cnt = (ctypes.c_uint32 * 32)(), (ctypes.c_uint64 * 32)(), ctypes.c_uint32(0)
+        _check(load().imm_debug_timeline(self._h, ids, ns, 32, ctypes.byref(cnt)), "imm_debug_timeline")
+        return [(TIMELINE_NAMES[ids[i]], int(ns[i])) for i in range(min(cnt.value, 32))]
 
     def imm_debug_device_challenge(self, state: bytes, stream=None) -> Tuple[int, bytes]:
         st = (ctypes.c_uint8 * 32).from_buffer_copy(state)

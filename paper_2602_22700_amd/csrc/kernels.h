@@ -23,8 +23,11 @@ hipError_t encode(hipStream_t stream, const void* src, int dtype, uint64_t count
 hipError_t front(hipStream_t stream, const int16_t* A, uint64_t countA, uint64_t* dstA, const int8_t* B, uint64_t countB,
                  uint64_t* dstB, const Point& ptA, int tA, uint64_t* eqA, const Point& ptB, int tB, uint64_t* eqB);
 
+// planesB (nullable, 2^tB x 8 bytes): the second vector once more, cut into bytes -- for every four
+// neighbouring entries eight words, word k holding byte k of each of the four -- which is the form the
+// reduction of an int8 table along its rows takes it in.
 hipError_t eq_build2(hipStream_t stream, const Point& ptA, int tA, uint64_t* outA, const Point& ptB, int tB,
-                     uint64_t* outB);
+                     uint64_t* outB, uint32_t* planesB);
 
 // Geometry of a split reduction: how many partial vectors a launch writes.
 struct Split {
@@ -41,16 +44,27 @@ hipError_t reduce_over_rows(hipStream_t stream, const void* T, int dtype, uint64
                             const uint64_t* eq_rows, uint64_t* partial, Split sp);
 
 // partial[s][i] = sum over the columns j of split s of eq[j] * T[i][j]   (i < rows)
+// eq_planes (nullable): the byte planes of eq_cols as eq_build2 writes them; with them an aligned int8
+// table takes the kernel that reads it as stored.
 hipError_t reduce_over_cols(hipStream_t stream, const void* T, int dtype, uint64_t rows, uint64_t cols, uint64_t ld,
-                            const uint64_t* eq_cols, uint64_t* partial, Split sp);
+                            const uint64_t* eq_cols, const uint32_t* eq_planes, uint64_t* partial, Split sp);
 
-// Both reductions of one statement in a single launch, A's workgroups first: same arguments and results
-// as reduce_over_rows(A ...) followed by reduce_over_cols(B ...).  Covers the aligned forms of widened A
-// with widened B, int16 A with widened B and int16 A with int8 B; for anything else nothing is launched
-// and *done is false.
+// Both reductions of one statement in a single launch, A's workgroups first.  B's part is
+// reduce_over_cols(B ...) as above.  A's part writes its partial vectors into partA and the workgroup
+// that finishes a block of columns last sums them into outA[0 .. colsA) (outA[colsA .. paddedA) is
+// zeroed), so no launch has to follow for A.  For that hand-over partA must hold kNoValue in every word
+// and countersA (kHandoverBlocks words) zeros when the launch starts; it leaves both that way.  Covers
+// the aligned forms of widened A with widened B, int16 A with widened B and int16 A with int8 B; for
+// anything else nothing is launched and *done is false.
+constexpr uint32_t kHandoverBlocks = 1024;  // column blocks of A at most
+constexpr uint64_t kNoValue = 0xFFFFFFFFFFFFFFFFull;  // an empty word of a partial vector: not a canonical element
 hipError_t reduce_both(hipStream_t stream, const void* A, int dtA, uint64_t rowsA, uint64_t colsA, uint64_t ldA,
-                       const uint64_t* eq_rows, uint64_t* partA, Split spA, const void* B, int dtB, uint64_t rowsB,
-                       uint64_t colsB, uint64_t ldB, const uint64_t* eq_cols, uint64_t* partB, Split spB, bool* done);
+                       const uint64_t* eq_rows, uint64_t* partA, Split spA, uint32_t* countersA, uint64_t paddedA,
+                       uint64_t* outA, const void* B, int dtB, uint64_t rowsB, uint64_t colsB, uint64_t ldB,
+                       const uint64_t* eq_cols, const uint32_t* eq_planes, uint64_t* partB, Split spB, bool* done);
+
+// words[0 .. count) = value
+hipError_t fill_words(hipStream_t stream, uint64_t* words, uint64_t count, uint64_t value);
 
 // out[j] = sum_s partial[s][j] for j < len, 0 for len <= j < padded
 // reduce_over_cols of a table of field elements with a single column split (out_rows[i] for i < rows),
@@ -97,6 +111,7 @@ hipError_t challenge_once(hipStream_t stream, const uint32_t state_in[8], uint64
 // hashes the transcript.  Every slot holds kMailEmpty until its owner writes it.
 constexpr uint64_t kMailEmpty = 0xFFFFFFFFFFFFFFFFull;  // not a canonical field element
 constexpr uint64_t kMailAbort = 0xFFFFFFFFFFFFFFFEull;  // host -> device: stop waiting
+constexpr uint64_t kMailFail = 0xFFFFFFFFFFFFFFFDull;   // device -> host, in place of g_1: the tables are not canonical
 struct Mailbox {
     uint64_t g[IMM_MAX_ROUNDS][4];  // device -> host: g_k(0), g_k(1), g_k(2), unused
     uint64_t r[IMM_MAX_ROUNDS];     // host -> device: r_k

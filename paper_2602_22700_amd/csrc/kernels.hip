@@ -55,6 +55,15 @@ template <> __device__ __forceinline__ void unpack<uint64_t>(v2u64 raw, uint64_t
     f1 = raw.y;
 }
 
+// Keeps the loads written above this point above it: the empty statement may touch memory as far as
+// the optimiser knows (so it does not sink a load past it, next to its first use), and the scheduling
+// barrier holds the instruction scheduler to the same order.  What is written above are the requests
+// for data that is only needed later; what follows works on data requested earlier.
+__device__ __forceinline__ void loads_stay_above() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 __device__ __forceinline__ uint64_t wave_sum(uint64_t v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v = gl::add(v, __shfl_down(v, off, 64));
@@ -75,6 +84,94 @@ __device__ __forceinline__ uint64_t block_sum(uint64_t v, uint64_t* lds) {
     }
     __syncthreads();
     return total;
+}
+
+// ------------------------------------------------------------------ partial vectors summed by the last workgroup
+// Where a reduction is split over several workgroups per output, each writes a partial vector and
+// the sum is usually a launch of its own.  Inside a launch that goes on for much longer (the
+// reduction of the other, larger operand) the sum can be had for nothing: a workgroup that has
+// written its partial vector counts itself in on its block of outputs, and the one that finds it
+// is the last sums the block.  Partial values and counters are written with agent-scope atomic
+// stores (they go through to the level all XCDs share) and read with agent-scope atomic loads;
+// nothing relies on the order in which such stores become visible: an empty word is kNoValue, which
+// no canonical field element can be, so every word says for itself whether it is there, and the
+// summing workgroup looks again until it is (the count only tells it that the words are on their
+// way).  It puts kNoValue back as it goes and zeroes the counter, so the next launch finds the
+// memory as this one did.  The looking again is bounded; if the bound were ever reached the word
+// taken is kNoValue, which the round kernels recognise as not canonical and report.
+constexpr uint32_t kHandoverPolls = 1u << 22;
+
+__device__ __forceinline__ void put_word(uint64_t* p, uint64_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t peek_word(const uint64_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct Handover {
+    uint32_t* counters;  // one per block of outputs (grid x index), zero between launches
+    uint64_t* out;       // the summed vector
+    uint64_t padded;     // out[len .. padded) is zeroed by the workgroup (0, 0)
+};
+
+// Called by every thread of workgroup (bx, by) of a split reduction after it has put_word() its W
+// partial values partial[by * len + first + c * stride], c < W (those below len).  `last` is a word
+// of LDS.  The summing workgroup asks for the words of many splits at once: one after the other,
+// each a round trip to memory, they would take longer than the reduction itself.
+constexpr int kHandoverBatch = 16;  // splits whose words a thread has in flight together
+#ifndef IMM_HANDOVER_MAX_SPLITS
+#define IMM_HANDOVER_MAX_SPLITS 16
+#endif
+constexpr uint64_t kHandoverMaxSplits = IMM_HANDOVER_MAX_SPLITS;  // partial vectors per launch where they are summed this way
+
+template <int W>
+__device__ __forceinline__ void sum_by_last_arriver(const Handover& h, uint64_t* __restrict__ partial, uint32_t nsplit,
+                                                    uint64_t len, uint32_t bx, uint32_t by, uint64_t first, uint64_t stride,
+                                                    uint32_t* last) {
+    if (bx == 0 && by == 0)
+        for (uint64_t j = len + threadIdx.x; j < h.padded; j += kBlock) h.out[j] = 0;
+    __syncthreads();  // every wave of the workgroup has issued its stores
+    if (threadIdx.x == 0) {
+        const uint32_t before = __hip_atomic_fetch_add(h.counters + bx, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *last = before + 1 == nsplit;
+    }
+    __syncthreads();
+    if (!*last) return;
+    uint64_t v[W];
+#pragma unroll
+    for (int c = 0; c < W; ++c) v[c] = 0;
+    for (uint32_t s0 = 0; s0 < nsplit; s0 += kHandoverBatch) {
+        uint64_t t[W][kHandoverBatch];
+#pragma unroll
+        for (int c = 0; c < W; ++c)
+#pragma unroll
+            for (int j = 0; j < kHandoverBatch; ++j) {
+                const uint64_t col = first + c * stride;
+                t[c][j] = (col < len && s0 + j < nsplit) ? peek_word(partial + (uint64_t)(s0 + j) * len + col) : 0;
+            }
+#pragma unroll
+        for (int c = 0; c < W; ++c)
+#pragma unroll
+            for (int j = 0; j < kHandoverBatch; ++j) {
+                const uint64_t col = first + c * stride;
+                if (col < len && s0 + j < nsplit) {
+                    const uint64_t* word = partial + (uint64_t)(s0 + j) * len + col;
+                    uint64_t x = t[c][j];
+                    for (uint32_t spin = 0; x == kNoValue && spin < kHandoverPolls; ++spin) x = peek_word(word);
+                    v[c] = (x == kNoValue || v[c] == kNoValue) ? kNoValue : gl::add(v[c], x);
+                }
+            }
+    }
+    // The words go back to empty in a pass of their own: a store among the loads above would have each
+    // wait for a word also wait for the store before it to come back from memory.
+    for (uint32_t sidx = 0; sidx < nsplit; ++sidx)
+#pragma unroll
+        for (int c = 0; c < W; ++c)
+            if (first + c * stride < len) put_word(partial + (uint64_t)sidx * len + first + c * stride, kNoValue);
+#pragma unroll
+    for (int c = 0; c < W; ++c)
+        if (first + c * stride < len) h.out[first + c * stride] = v[c];
+    if (threadIdx.x == 0) __hip_atomic_store(h.counters + bx, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ------------------------------------------------------------------ encode
@@ -140,7 +237,7 @@ hipError_t launch_encode(hipStream_t stream, const void* src, uint64_t count, ui
 // long as a kernel reads its own struct arguments with constant indices they come straight from
 // the argument segment, while handing them to a function, even an inlined one, makes every thread
 // of the launch keep a private 512-byte copy.
-#define IMM_EQ_BUILD2_BODY(ptA, tA, outA, ptB, tB, outB, block)                                   \
+#define IMM_EQ_BUILD2_BODY(ptA, tA, outA, ptB, tB, outB, planesB, block)                          \
     do {                                                                                          \
         uint64_t idx_ = (uint64_t)(block) * kBlock + threadIdx.x;                                 \
         const uint64_t nA_ = 1ull << (tA), nB_ = 1ull << (tB);                                    \
@@ -156,11 +253,22 @@ hipError_t launch_encode(hipStream_t stream, const void* src, uint64_t count, ui
             }                                                                                     \
         }                                                                                         \
         if (!second_ || idx_ < nB_) (second_ ? (outB) : (outA))[idx_] = w_;                       \
+        if (second_ && idx_ < nB_ && (planesB) != nullptr) eq_planes_store((planesB), idx_, w_);  \
     } while (0)
 
+// The second vector once more, cut into bytes for the int8 reduction: for every four neighbouring
+// entries 4g .. 4g+3 eight words, word k holding byte k of each of the four (entry 4g in the low
+// byte).  A dot product of such a word with four table bytes is the sum of four byte products.
+__device__ __forceinline__ void eq_planes_store(uint32_t* planes, uint64_t idx, uint64_t w) {
+    uint8_t* pb = reinterpret_cast<uint8_t*>(planes) + (idx >> 2) * 32 + (idx & 3);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) pb[4 * k] = (uint8_t)(w >> (8 * k));
+}
+
 __global__ __launch_bounds__(kBlock) void eq_build2_kernel(Point ptA, int tA, uint64_t* __restrict__ outA, Point ptB,
-                                                           int tB, uint64_t* __restrict__ outB) {
-    IMM_EQ_BUILD2_BODY(ptA, tA, outA, ptB, tB, outB, blockIdx.x);
+                                                           int tB, uint64_t* __restrict__ outB,
+                                                           uint32_t* __restrict__ planesB) {
+    IMM_EQ_BUILD2_BODY(ptA, tA, outA, ptB, tB, outB, planesB, blockIdx.x);
 }
 
 // Everything a proof launches before its reductions, in one grid: the eq vectors of both points
@@ -182,7 +290,7 @@ template <bool VA, bool VB>
 __global__ __launch_bounds__(kBlock) void front_kernel(FrontArgs f, Point ptA, Point ptB) {
     uint32_t b = blockIdx.x;
     if (b < f.blocks_eq) {
-        IMM_EQ_BUILD2_BODY(ptA, f.tA, f.eqA, ptB, f.tB, f.eqB, b);
+        IMM_EQ_BUILD2_BODY(ptA, f.tA, f.eqA, ptB, f.tB, f.eqB, static_cast<uint32_t*>(nullptr), b);
         return;
     }
     b -= f.blocks_eq;
@@ -348,20 +456,33 @@ hipError_t launch_over_cols(hipStream_t stream, const void* T, uint64_t rows, ui
 // Reads the weights as they are stored (1 byte per entry instead of 8).  With x' = x + 128 in
 // [0, 255] (a sign-bit flip of the byte) the sum over a row is
 //     sum_y eq[y] x[y] = sum_y eq[y] x'[y]  -  128 * sum_y eq[y],
-// and every product eq_limb * x' is below 2^40, so a lane adds thousands of them into a plain
-// 64-bit register: two v_mad_u64_u32 per entry, no carries, one modular reduction per row per
-// block.  A lane owns 16 adjacent columns (one 16-byte load per row) and keeps their 32 eq limbs
-// in registers while it walks the R rows of the block, so the eq vector costs 128/(16 R) bytes of
-// L2 traffic per byte of table.  The correction term is accumulated from the same registers.
+// and with eq[y] cut into its eight bytes e_k[y],
+//     sum_y eq[y] x'[y] = sum_k 2^(8k) sum_y e_k[y] x'[y].
+// The inner sums are sums of byte products, which v_dot4_u32_u8 forms four at a time: one operand is
+// a word of the table (four neighbouring columns of a row), the other the word of the eq vector's
+// byte planes that holds byte k of the same four columns (see eq_planes_store).  Eight such
+// instructions take in four entries: two per entry with nothing to unpack, where 32-bit multiplies
+// need a byte extraction and two multiply-adds each.  A lane owns 16 adjacent columns (one 16-byte
+// load per row) and keeps their 32 plane words in registers while it walks the R rows of the block,
+// so the eq vector costs 128/(16 R) bytes of L2 traffic per byte of table.  The correction term comes
+// from the same registers (dot products with a word of ones).  Sums stay in 32-bit registers: a dot
+// product adds less than 2^18, and a split is short enough (kI8MaxSplit) for the sum over a whole
+// wave to stay below 2^32.  The loads of the next pass are issued before the current one is worked on, so a wave has
+// memory requests in flight while it computes.
 #ifndef IMM_I8_ROWS
 #define IMM_I8_ROWS 8
 #endif
 #ifndef IMM_I8_MIN_BLOCKS
 #define IMM_I8_MIN_BLOCKS 512
 #endif
+#ifndef IMM_I8_GROUPS
+#define IMM_I8_GROUPS 1
+#endif
 constexpr int kI8Rows = IMM_I8_ROWS;              // rows per block
-constexpr uint64_t kI8ColsPerPass = 16 * kBlock;  // columns one block pass covers
-constexpr uint64_t kI8MaxSplit = 1ull << 20;      // columns per split: keeps the 64-bit sums below 2^61
+constexpr int kI8Groups = IMM_I8_GROUPS;          // groups of four columns per lane and pass (4: 16-byte table loads)
+constexpr int kI8LaneCols = 4 * kI8Groups;
+constexpr uint64_t kI8ColsPerPass = (uint64_t)kI8LaneCols * kBlock;  // columns one block pass covers
+constexpr uint64_t kI8MaxSplit = 1ull << 17;      // columns per split: a wave's sum of a plane stays below 2^32
 
 typedef unsigned int v4u32 __attribute__((ext_vector_type(4)));
 
@@ -371,73 +492,213 @@ __device__ __forceinline__ uint64_t wave_sum_plain(uint64_t v) {
     return v;
 }
 
-// value = lo + hi * 2^32 with lo, hi < 2^62, as a canonical residue
+// value = lo + hi * 2^32 as a canonical residue (any lo, hi)
 __device__ __forceinline__ uint64_t combine_limb_sums(uint64_t lo, uint64_t hi) {
     uint64_t low = lo + (hi << 32);
     uint64_t high = (hi >> 32) + (low < lo ? 1 : 0);
     return gl::reduce128(low, high);
 }
 
+// sum_k p[k] 2^(8k) for four 32-bit plane sums: below 2^57
+__device__ __forceinline__ uint64_t gather_planes(const uint32_t* p) {
+    return (uint64_t)p[0] + ((uint64_t)p[1] << 8) + ((uint64_t)p[2] << 16) + ((uint64_t)p[3] << 24);
+}
+
+// Sum of a 32-bit value over the 64 lanes of a wave, valid in lane 63 (no overflow check).  Six
+// additions whose second operand comes from another lane through the data-parallel-primitive path
+// of the vector ALU (shifts by 1, 2, 4, 8 lanes within each row of 16, then the last lane of a row
+// into the following row, then lane 31 into the upper half): no trip through the LDS crossbar, whose
+// latency a chain of shuffles pays at every step.
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);   // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+typedef unsigned int i8_words __attribute__((ext_vector_type(kI8Groups)));  // a lane's table bytes of one row
+struct I8Pass {
+    i8_words x[kI8Rows];
+    v4u32 e[2 * kI8Groups];  // plane words of the lane's columns: e[2g] planes 0..3, e[2g+1] planes 4..7 of group g
+};
+
+// Zeros to read in place of eq weights where there is nothing left to fetch.  (Not const: a constant
+// would live in another address space than the eq vectors, and a load from "one or the other" would
+// then be a generic one, which the hardware does not keep in order with the loads from the table.)
+__device__ uint64_t zero_words[16];
+
+// `real` false: nothing is left for this lane to fetch; it then reads zeros in place of the plane
+// words (and the first bytes of the split, whatever they are), which add nothing to any sum.  So
+// the loads of a pass are issued by every lane in every pass, the loop below has one path, and the
+// number of requests a wave has in flight at any point is known when the kernel is compiled: the
+// wait for the current pass's data then leaves the next pass's requests in flight.  (With a branch
+// around the loads the compiler moves them into the branch that uses their data, behind the work on
+// the current pass, or has to wait for everything where the paths meet.)
+// rowp[r]: start of the split in row r (the same for every lane); off: the lane's column in the split.
+__device__ __forceinline__ void i8_load(I8Pass& f, const int8_t* const (&rowp)[kI8Rows], const uint32_t* __restrict__ planes,
+                                        uint32_t off, bool real) {
+    const uint32_t x_off = real ? off : 0;
+#pragma unroll
+    for (int r = 0; r < kI8Rows; ++r)
+        f.x[r] = __builtin_nontemporal_load(reinterpret_cast<const i8_words*>(rowp[r] + x_off));
+    const v4u32* pe = real ? reinterpret_cast<const v4u32*>(planes + 2 * (uint64_t)off)  // 8 words per 4 columns
+                           : reinterpret_cast<const v4u32*>(zero_words);
+#pragma unroll
+    for (int j = 0; j < 2 * kI8Groups; ++j) f.e[j] = pe[j];
+}
+
+__device__ __forceinline__ void i8_accumulate(const I8Pass& f, uint32_t (&acc)[kI8Rows][8], uint32_t (&ks)[8]) {
+#pragma unroll
+    for (int g = 0; g < kI8Groups; ++g) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            ks[k] = __builtin_amdgcn_udot4(0x01010101u, f.e[2 * g][k], ks[k], false);
+            ks[4 + k] = __builtin_amdgcn_udot4(0x01010101u, f.e[2 * g + 1][k], ks[4 + k], false);
+        }
+#pragma unroll
+        for (int r = 0; r < kI8Rows; ++r) {
+            const uint32_t w = f.x[r][g] ^ 0x80808080u;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                acc[r][k] = __builtin_amdgcn_udot4(w, f.e[2 * g][k], acc[r][k], false);
+                acc[r][4 + k] = __builtin_amdgcn_udot4(w, f.e[2 * g + 1][k], acc[r][4 + k], false);
+            }
+        }
+    }
+}
+
+// Sums of a wave's plane accumulators, left in out[]: out[2t], out[2t + 1] the sums of the two 32-bit
+// limbs of table row t (planes 0..3 and 4..7 gathered), out[2R + k] the wave's sum of plane k of the
+// eq weights themselves.  All sums are below 2^32 (kI8MaxSplit).
+// With eight rows there are 72 values to add up over 64 lanes.  A butterfly per value is six steps
+// each; here the values are first folded onto fewer lanes two at a time -- a swap of the upper half
+// of one register with the lower half of another and one addition leave one register holding one
+// value's sum over pairs of lanes in its lower half and the other's in its upper half; the same with
+// the 16-lane rows -- so that 18 registers are left, each holding four different values, one per row
+// of 16 lanes, and only those take the four steps within a row.  Lane 15 of row rho of the wave then
+// holds, for t0 = 0, 1, all planes of table row t = 4 (rho >> 1) + 2 (rho & 1) + t0.
+__device__ __forceinline__ uint32_t fold_halves(uint32_t lower, uint32_t upper) {
+    const auto s = __builtin_amdgcn_permlane32_swap(lower, upper, false, false);
+    return s[0] + s[1];  // lanes 0..31: `lower` over lane pairs (l, l + 32); lanes 32..63: `upper` likewise
+}
+__device__ __forceinline__ uint32_t fold_rows(uint32_t even, uint32_t odd) {
+    const auto s = __builtin_amdgcn_permlane16_swap(even, odd, false, false);
+    return s[0] + s[1];  // rows 0 and 2: `even` over row pairs (0, 1) and (2, 3); rows 1 and 3: `odd` likewise
+}
+__device__ __forceinline__ uint32_t row_sum_u32(uint32_t v) {  // valid in the last lane of each row of 16
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);  // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);  // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);  // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);  // row_shr:8
+    return v;
+}
+
+__device__ __forceinline__ void i8_wave_totals(uint32_t (&acc)[kI8Rows][8], uint32_t (&ks)[8],
+                                               uint64_t (&out)[2 * kI8Rows + 8], uint32_t lane) {
+    if constexpr (kI8Rows == 8) {
+        uint32_t y[2][8], ky[2];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+#pragma unroll
+            for (int t0 = 0; t0 < 2; ++t0) {
+                const uint32_t x0 = fold_halves(acc[t0][k], acc[t0 + 4][k]);      // table rows t0 | t0 + 4
+                const uint32_t x1 = fold_halves(acc[t0 + 2][k], acc[t0 + 6][k]);  // table rows t0 + 2 | t0 + 6
+                y[t0][k] = row_sum_u32(fold_rows(x0, x1));  // rows of 16: t0, t0 + 2, t0 + 4, t0 + 6
+            }
+        }
+#pragma unroll
+        for (int k0 = 0; k0 < 2; ++k0) {
+            const uint32_t x0 = fold_halves(ks[k0], ks[k0 + 4]);
+            const uint32_t x1 = fold_halves(ks[k0 + 2], ks[k0 + 6]);
+            ky[k0] = row_sum_u32(fold_rows(x0, x1));  // rows of 16: planes k0, k0 + 2, k0 + 4, k0 + 6
+        }
+        if ((lane & 15) == 15) {
+            const uint32_t rho = lane >> 4, base = 4 * (rho >> 1) + 2 * (rho & 1);
+#pragma unroll
+            for (int t0 = 0; t0 < 2; ++t0) {
+                out[2 * (base + t0)] = gather_planes(&y[t0][0]);
+                out[2 * (base + t0) + 1] = gather_planes(&y[t0][4]);
+                out[2 * kI8Rows + base + t0] = ky[t0];
+            }
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < kI8Rows; ++r)
+#pragma unroll
+            for (int k = 0; k < 8; ++k) acc[r][k] = wave_sum_u32(acc[r][k]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) ks[k] = wave_sum_u32(ks[k]);
+        if (lane == 63) {
+#pragma unroll
+            for (int r = 0; r < kI8Rows; ++r) {
+                out[2 * r] = gather_planes(&acc[r][0]);
+                out[2 * r + 1] = gather_planes(&acc[r][4]);
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) out[2 * kI8Rows + k] = ks[k];
+        }
+    }
+}
+
 __device__ __forceinline__ void reduce_over_cols_i8_block(const int8_t* __restrict__ T, uint64_t ld, uint64_t rows,
-                                                          uint64_t cols, const uint64_t* __restrict__ eq,
+                                                          uint64_t cols, const uint32_t* __restrict__ planes,
                                                           uint64_t* __restrict__ partial, uint64_t cols_per_split,
-                                                          uint32_t bx, uint32_t by, uint64_t (*lds)[2 * kI8Rows + 2]) {
+                                                          uint32_t bx, uint32_t by, uint64_t (*lds)[2 * kI8Rows + 8]) {
     constexpr int R = kI8Rows;
     const uint64_t row0 = (uint64_t)bx * R;
     const uint64_t c_begin = (uint64_t)by * cols_per_split;
     uint64_t c_end = c_begin + cols_per_split;
     if (c_end > cols) c_end = cols;
 
-    uint64_t lo[R], hi[R], ks_lo = 0, ks_hi = 0;
+    uint32_t acc[R][8], ks[8];
 #pragma unroll
-    for (int r = 0; r < R; ++r) lo[r] = hi[r] = 0;
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[r][k] = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) ks[k] = 0;
     // rows past the end of the table are read from the last valid row and dropped at the end
     const int8_t* rowp[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) rowp[r] = T + (row0 + r < rows ? row0 + r : rows - 1) * ld;
+    for (int r = 0; r < R; ++r) rowp[r] = T + (row0 + r < rows ? row0 + r : rows - 1) * ld + c_begin;
+    const uint32_t* split_planes = planes + 2 * c_begin;
 
-    for (uint64_t c = c_begin + 16 * (uint64_t)threadIdx.x; c < c_end; c += kI8ColsPerPass) {
-        v4u32 x[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) x[r] = __builtin_nontemporal_load(reinterpret_cast<const v4u32*>(rowp[r] + c));
-        uint32_t e0[16], e1[16];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            v2u64 e = *reinterpret_cast<const v2u64*>(eq + c + 2 * j);
-            e0[2 * j] = (uint32_t)e.x; e1[2 * j] = (uint32_t)(e.x >> 32);
-            e0[2 * j + 1] = (uint32_t)e.y; e1[2 * j + 1] = (uint32_t)(e.y >> 32);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            ks_lo += e0[j];
-            ks_hi += e1[j];
-        }
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t w = x[r][q] ^ 0x80808080u;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const uint32_t byte = (w >> (8 * k)) & 0xFFu;
-                    lo[r] += (uint64_t)e0[4 * q + k] * byte;
-                    hi[r] += (uint64_t)e1[4 * q + k] * byte;
-                }
-            }
-        }
+    // Every lane runs the same number of passes (where a lane has nothing left, see i8_load).  The data
+    // of two passes beyond the current one is on its way at any time -- one pass ahead leaves the
+    // 2 x 4 waves that a CU holds of this kernel with too few bytes in flight to keep HBM busy -- so
+    // the loop takes three passes per turn, and the one or two left over follow it: their data was
+    // asked for in the loop's last turn (or before it).
+    const uint32_t span = (uint32_t)(c_end - c_begin);
+    const uint32_t passes = (span + (uint32_t)kI8ColsPerPass - 1) / (uint32_t)kI8ColsPerPass;
+    constexpr uint32_t kStep = (uint32_t)kI8ColsPerPass;
+    uint32_t off = kI8LaneCols * threadIdx.x;
+    I8Pass fa, fb, fc;
+    i8_load(fa, rowp, split_planes, off, off < span);
+    off += kStep;
+    i8_load(fb, rowp, split_planes, off, off < span);
+    uint32_t pass = 0;
+    for (; pass + 2 < passes; pass += 3) {
+        off += kStep;
+        i8_load(fc, rowp, split_planes, off, off < span);
+        loads_stay_above();
+        i8_accumulate(fa, acc, ks);
+        off += kStep;
+        i8_load(fa, rowp, split_planes, off, off < span);
+        loads_stay_above();
+        i8_accumulate(fb, acc, ks);
+        off += kStep;
+        i8_load(fb, rowp, split_planes, off, off < span);
+        loads_stay_above();
+        i8_accumulate(fc, acc, ks);
     }
-    // block sums of the raw 64-bit accumulators (no wrap: see kI8MaxSplit), then one reduction
+    if (pass < passes) i8_accumulate(fa, acc, ks);
+    if (pass + 1 < passes) i8_accumulate(fb, acc, ks);
+
     const uint32_t lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        uint64_t a = wave_sum_plain(lo[r]), b = wave_sum_plain(hi[r]);
-        if (lane == 0) { lds[w][2 * r] = a; lds[w][2 * r + 1] = b; }
-    }
-    {
-        uint64_t a = wave_sum_plain(ks_lo), b = wave_sum_plain(ks_hi);
-        if (lane == 0) { lds[w][2 * R] = a; lds[w][2 * R + 1] = b; }
-    }
+    i8_wave_totals(acc, ks, lds[w], lane);
     __syncthreads();
     if (threadIdx.x < R && row0 + threadIdx.x < rows) {
         const int r = threadIdx.x;
@@ -445,7 +706,11 @@ __device__ __forceinline__ void reduce_over_cols_i8_block(const int8_t* __restri
 #pragma unroll
         for (int k = 0; k < kWaves; ++k) {
             a += lds[k][2 * r]; b += lds[k][2 * r + 1];
-            ka += lds[k][2 * R]; kb += lds[k][2 * R + 1];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                ka += lds[k][2 * R + q] << (8 * q);
+                kb += lds[k][2 * R + 4 + q] << (8 * q);
+            }
         }
         const uint64_t sum = combine_limb_sums(a, b);
         const uint64_t corr = gl::mul(128, combine_limb_sums(ka, kb));
@@ -455,14 +720,14 @@ __device__ __forceinline__ void reduce_over_cols_i8_block(const int8_t* __restri
 
 __global__ __launch_bounds__(kBlock) void reduce_over_cols_i8_kernel(const int8_t* __restrict__ T, uint64_t ld,
                                                                      uint64_t rows, uint64_t cols,
-                                                                     const uint64_t* __restrict__ eq,
+                                                                     const uint32_t* __restrict__ planes,
                                                                      uint64_t* __restrict__ partial,
                                                                      uint64_t cols_per_split) {
-    __shared__ uint64_t lds[kWaves][2 * kI8Rows + 2];
-    reduce_over_cols_i8_block(T, ld, rows, cols, eq, partial, cols_per_split, blockIdx.x, blockIdx.y, lds);
+    __shared__ uint64_t lds[kWaves][2 * kI8Rows + 8];
+    reduce_over_cols_i8_block(T, ld, rows, cols, planes, partial, cols_per_split, blockIdx.x, blockIdx.y, lds);
 }
 
-// The fast int8 kernel needs 16-byte rows and whole 16-column groups.
+// The fast int8 kernel needs 16-byte aligned rows and whole groups of a lane's columns.
 bool i8_fast_shape(uint64_t cols) { return cols % 16 == 0; }
 
 // ------------------------------------------------------------------ reduction over the rows (column-wise)
@@ -471,19 +736,25 @@ bool i8_fast_shape(uint64_t cols) { return cols % 16 == 0; }
 // (a scalar load).
 constexpr int kRowsUnroll = 8;
 
-// The work of workgroup (bx, by) of the grid (column blocks, row splits).  No barriers.
-template <typename S, bool VEC>
+// The work of workgroup (bx, by) of the grid (column blocks, row splits).  FINISH: the partial
+// vectors are handed over as described above and the last workgroup of a column block sums them;
+// otherwise they are left for a later launch, and the block has no barriers.
+template <typename S, bool VEC, bool FINISH>
 __device__ __forceinline__ void reduce_over_rows_block(const S* __restrict__ T, uint64_t ld, uint64_t rows, uint64_t cols,
                                                        const uint64_t* __restrict__ eq, uint64_t* __restrict__ partial,
-                                                       uint64_t rows_per_split, uint32_t bx, uint32_t by) {
+                                                       uint64_t rows_per_split, uint32_t bx, uint32_t by,
+                                                       const Handover& h, uint32_t nsplit, uint32_t* last) {
     const uint64_t r_begin = (uint64_t)by * rows_per_split;
     uint64_t r_end = r_begin + rows_per_split;
     if (r_end > rows) r_end = rows;
     uint64_t* out = partial + (uint64_t)by * cols;
+    auto emit = [&](uint64_t j, uint64_t v) {
+        if (FINISH) put_word(out + j, v);
+        else out[j] = v;
+    };
     if (VEC) {
         using Raw = typename RawPair<S>::type;
         const uint64_t col = ((uint64_t)bx * kBlock + threadIdx.x) * 2;
-        if (col >= cols) return;
         gl::Acc a0, a1;
         gl::acc_clear(a0);
         gl::acc_clear(a1);
@@ -514,19 +785,22 @@ __device__ __forceinline__ void reduce_over_rows_block(const S* __restrict__ T, 
                 gl::acc_mac(a0, f0, e);
                 gl::acc_mac(a1, f1, e);
             }
-            out[col] = gl::acc_reduce(a0);
-            out[col + 1] = gl::acc_reduce(a1);
-        } else {  // last column of an odd-width table
+            emit(col, gl::acc_reduce(a0));
+            emit(col + 1, gl::acc_reduce(a1));
+        } else if (col < cols) {  // last column of an odd-width table
             for (uint64_t i = r_begin; i < r_end; ++i) gl::acc_mac(a0, to_field<S>(T[i * ld + col]), eq[i]);
-            out[col] = gl::acc_reduce(a0);
+            emit(col, gl::acc_reduce(a0));
         }
+        if (FINISH) sum_by_last_arriver<2>(h, partial, nsplit, cols, bx, by, col, 1, last);
     } else {
         const uint64_t col = (uint64_t)bx * kBlock + threadIdx.x;
-        if (col >= cols) return;
-        gl::Acc a0;
-        gl::acc_clear(a0);
-        for (uint64_t i = r_begin; i < r_end; ++i) gl::acc_mac(a0, to_field<S>(T[i * ld + col]), eq[i]);
-        out[col] = gl::acc_reduce(a0);
+        if (col < cols) {
+            gl::Acc a0;
+            gl::acc_clear(a0);
+            for (uint64_t i = r_begin; i < r_end; ++i) gl::acc_mac(a0, to_field<S>(T[i * ld + col]), eq[i]);
+            emit(col, gl::acc_reduce(a0));
+        }
+        if (FINISH) sum_by_last_arriver<1>(h, partial, nsplit, cols, bx, by, col, 1, last);
     }
 }
 
@@ -535,40 +809,189 @@ __global__ __launch_bounds__(kBlock) void reduce_over_rows_kernel(const S* __res
                                                                   uint64_t cols, const uint64_t* __restrict__ eq,
                                                                   uint64_t* __restrict__ partial,
                                                                   uint64_t rows_per_split) {
-    reduce_over_rows_block<S, VEC>(T, ld, rows, cols, eq, partial, rows_per_split, blockIdx.x, blockIdx.y);
+    reduce_over_rows_block<S, VEC, false>(T, ld, rows, cols, eq, partial, rows_per_split, blockIdx.x, blockIdx.y,
+                                          Handover{}, 0, nullptr);
+}
+
+// ------------------------------------------------------------------ column-wise reduction of an int16 table
+// Reads the activations as they are stored (2 bytes per entry instead of 8).  With x' = x + 32768 in
+// [0, 65535] (a sign-bit flip) the sum over the rows of a split is
+//     sum_i eq[i] x[i][j] = sum_i eq[i] x'[i][j]  -  32768 * sum_i eq[i],
+// and the products of a 32-bit limb of eq[i] with x' are below 2^48, so a lane adds up to 2^15 of
+// them into a plain 64-bit register: two v_mad_u64_u32 per entry, no carries, one modular reduction
+// per column at the end.  A lane owns 8 adjacent columns (one 16-byte load per row); the eq weight
+// of a row is the same for every lane and comes from a scalar load.  The loads of the next trip of
+// kRowsUnroll rows are issued before the current trip is worked on.
+constexpr uint64_t kI16MaxSplit = 1ull << 15;  // rows per split: keeps the 64-bit sums below 2^63
+constexpr int kI16Cols = 8;                    // columns per lane
+
+__device__ __forceinline__ void i16_load(v4u32 (&x)[kRowsUnroll], const int16_t* p, uint64_t ld) {
+#pragma unroll
+    for (int u = 0; u < kRowsUnroll; ++u) x[u] = __builtin_nontemporal_load(reinterpret_cast<const v4u32*>(p + u * ld));
+}
+
+__device__ __forceinline__ void i16_row(const v4u32& x, uint64_t e, uint64_t (&lo)[kI16Cols], uint64_t (&hi)[kI16Cols],
+                                        uint64_t& klo, uint64_t& khi) {
+    const uint32_t e0 = (uint32_t)e, e1 = (uint32_t)(e >> 32);
+    klo += e0;
+    khi += e1;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t w = x[q] ^ 0x80008000u;
+        const uint32_t v0 = w & 0xFFFFu, v1 = w >> 16;
+        lo[2 * q] += (uint64_t)e0 * v0;
+        hi[2 * q] += (uint64_t)e1 * v0;
+        lo[2 * q + 1] += (uint64_t)e0 * v1;
+        hi[2 * q + 1] += (uint64_t)e1 * v1;
+    }
+}
+
+// Workgroup (bx, by): 64 lanes x 8 = 512 columns, the rows of split by; its four waves take a quarter
+// of those rows each and meet in LDS (wave_sums), so that a launch leaves a quarter of the partial
+// vectors it would with one row range per workgroup.
+constexpr int kI16BlockCols = 64 * kI16Cols;
+
+template <bool FINISH>
+__device__ __forceinline__ void reduce_over_rows_i16_block(const int16_t* __restrict__ T, uint64_t ld, uint64_t rows,
+                                                           uint64_t cols, const uint64_t* __restrict__ eq,
+                                                           uint64_t* __restrict__ partial, uint64_t rows_per_split,
+                                                           uint32_t bx, uint32_t by, const Handover& h, uint32_t nsplit,
+                                                           uint32_t* last, uint64_t (*wave_sums)[kI16BlockCols]) {
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // known to be the same for the whole wave
+    const uint64_t s_begin = (uint64_t)by * rows_per_split;
+    uint64_t s_end = s_begin + rows_per_split;
+    if (s_end > rows) s_end = rows;
+    uint64_t per_wave = (s_end - s_begin + kWaves - 1) / kWaves;
+    per_wave = (per_wave + kRowsUnroll - 1) / kRowsUnroll * kRowsUnroll;
+    uint64_t r_begin = s_begin + w * per_wave, r_end = r_begin + per_wave;
+    if (r_begin > s_end) r_begin = s_end;
+    if (r_end > s_end) r_end = s_end;
+    const uint64_t col = (uint64_t)bx * kI16BlockCols + lane * kI16Cols;
+    uint64_t lo[kI16Cols], hi[kI16Cols], klo = 0, khi = 0;
+#pragma unroll
+    for (int c = 0; c < kI16Cols; ++c) lo[c] = hi[c] = 0;
+    if (col < cols) {  // cols is a multiple of kI16Cols here
+        const int16_t* p = T + r_begin * ld + col;
+        uint64_t i = r_begin;
+        // Whole trips of kRowsUnroll rows, two per turn of the loop; the loads of the next trip go out
+        // before the current one is worked on.  Where there is no next trip the lane reads its first
+        // bytes of the table again, with zeros for eq weights (one path through the loop: see i8_load).
+        const uint64_t trips = (r_end - r_begin) / kRowsUnroll;
+        const int16_t* first_bytes = T + col;
+        if (trips) {
+            v4u32 xa[kRowsUnroll], xb[kRowsUnroll];
+            i16_load(xa, p, ld);
+            for (uint64_t t = 0; t < trips; t += 2) {
+                const bool next = t + 1 < trips, after = t + 2 < trips;
+                i16_load(xb, next ? p + kRowsUnroll * ld : first_bytes, next ? ld : 0);
+                loads_stay_above();
+#pragma unroll
+                for (int u = 0; u < kRowsUnroll; ++u) i16_row(xa[u], eq[i + u], lo, hi, klo, khi);
+                i16_load(xa, after ? p + 2 * kRowsUnroll * ld : first_bytes, after ? ld : 0);
+                loads_stay_above();
+                const uint64_t* eq_next = next ? eq + i + kRowsUnroll : zero_words;
+#pragma unroll
+                for (int u = 0; u < kRowsUnroll; ++u) i16_row(xb[u], eq_next[u], lo, hi, klo, khi);
+                i += 2 * kRowsUnroll;
+                p += 2 * kRowsUnroll * ld;
+            }
+            i = r_begin + trips * kRowsUnroll;
+            p = T + i * ld + col;
+        }
+        for (; i < r_end; ++i, p += ld)
+            i16_row(__builtin_nontemporal_load(reinterpret_cast<const v4u32*>(p)), eq[i], lo, hi, klo, khi);
+    }
+    const uint64_t corr = gl::mul(32768, combine_limb_sums(klo, khi));
+#pragma unroll
+    for (int c = 0; c < kI16Cols; ++c) wave_sums[w][lane * kI16Cols + c] = gl::sub(combine_limb_sums(lo[c], hi[c]), corr);
+    __syncthreads();
+    uint64_t* out = partial + (uint64_t)by * cols;
+#pragma unroll
+    for (int c = 0; c < kI16BlockCols / kBlock; ++c) {
+        const uint32_t j = threadIdx.x + c * kBlock;
+        const uint64_t jc = (uint64_t)bx * kI16BlockCols + j;
+        if (jc < cols) {
+            uint64_t v = wave_sums[0][j];
+#pragma unroll
+            for (int k = 1; k < kWaves; ++k) v = gl::add(v, wave_sums[k][j]);
+            if (FINISH) put_word(out + jc, v);
+            else out[jc] = v;
+        }
+    }
+    if (FINISH)
+        sum_by_last_arriver<kI16BlockCols / kBlock>(h, partial, nsplit, cols, bx, by,
+                                                    (uint64_t)bx * kI16BlockCols + threadIdx.x, kBlock, last);
+}
+
+__global__ __launch_bounds__(kBlock) void reduce_over_rows_i16_kernel(const int16_t* __restrict__ T, uint64_t ld,
+                                                                      uint64_t rows, uint64_t cols,
+                                                                      const uint64_t* __restrict__ eq,
+                                                                      uint64_t* __restrict__ partial,
+                                                                      uint64_t rows_per_split) {
+    __shared__ uint64_t wave_sums[kWaves][kI16BlockCols];
+    reduce_over_rows_i16_block<false>(T, ld, rows, cols, eq, partial, rows_per_split, blockIdx.x, blockIdx.y, Handover{}, 0,
+                                      nullptr, wave_sums);
+}
+
+// The fast int16 kernel needs 16-byte rows and whole 8-column groups.
+bool i16_fast_shape(const void* T, uint64_t cols, uint64_t ld) {
+    return cols % kI16Cols == 0 && ld % kI16Cols == 0 && reinterpret_cast<uintptr_t>(T) % 16 == 0;
 }
 
 // ------------------------------------------------------------------ both reductions of a statement in one launch
 // The table of A is small next to B's (67 MB against 470 MB at the FFN shape): on its own its kernel
 // spends a third of its time filling and draining the machine.  Here the workgroups of the
 // row-direction reduction of A come first in the grid of the column-direction reduction of B, so
-// they stream alongside it.  Only the aligned forms of the three operand combinations that the
-// prover produces are covered (both widened; int16 activations with widened or with int8 weights).
+// they stream alongside it, and the last of them to finish a block of columns sums that block's
+// partial vectors while B's reduction is still running.  Only the aligned forms of the operand
+// combinations that the prover produces are covered (both widened; int16 activations with widened
+// or with int8 weights).
 struct ReduceArgs {
     const void* T;
     uint64_t ld, rows, cols;
-    const uint64_t* eq;
+    const void* eq;  // the eq vector; for an int8 table its byte planes
     uint64_t* partial;
     uint64_t per_split;
     uint32_t grid_x, grid_y;
 };
 
-template <typename SA, typename SB, bool B_IS_I8>
-__global__ __launch_bounds__(kBlock) void reduce_both_kernel(ReduceArgs a, ReduceArgs b) {
-    __shared__ uint64_t lds[kWaves][2 * kI8Rows + 2];
+// A_I16: the int16 table of A takes the 8-columns-per-lane kernel (else two columns per lane).
+template <typename SA, typename SB, bool A_I16, bool B_IS_I8>
+__global__ __launch_bounds__(kBlock) void reduce_both_kernel(ReduceArgs a, Handover ha, ReduceArgs b) {
+    __shared__ uint64_t lds[kWaves][2 * kI8Rows + 8];
+    __shared__ uint64_t wave_sums[A_I16 ? kWaves : 1][A_I16 ? kI16BlockCols : 1];
+    __shared__ uint32_t last;
     const uint32_t a_blocks = a.grid_x * a.grid_y;
-    if (blockIdx.x < a_blocks) {
-        reduce_over_rows_block<SA, true>(static_cast<const SA*>(a.T), a.ld, a.rows, a.cols, a.eq, a.partial, a.per_split,
-                                         blockIdx.x % a.grid_x, blockIdx.x / a.grid_x);
+#ifdef IMM_A_LAST
+    const uint32_t b_blocks = b.grid_x * b.grid_y;
+    const bool is_a = blockIdx.x >= b_blocks;
+    const uint32_t a_id = blockIdx.x - b_blocks, b_id = blockIdx.x;
+#else
+    const bool is_a = blockIdx.x < a_blocks;
+    const uint32_t a_id = blockIdx.x, b_id = blockIdx.x - a_blocks;
+#endif
+    if (is_a) {
+        const uint32_t bx = a_id % a.grid_x, by = a_id / a.grid_x;
+        if constexpr (A_I16)
+            reduce_over_rows_i16_block<true>(static_cast<const int16_t*>(a.T), a.ld, a.rows, a.cols,
+                                             static_cast<const uint64_t*>(a.eq), a.partial, a.per_split, bx, by, ha,
+                                             a.grid_y, &last, wave_sums);
+        else
+            reduce_over_rows_block<SA, true, true>(static_cast<const SA*>(a.T), a.ld, a.rows, a.cols,
+                                                   static_cast<const uint64_t*>(a.eq), a.partial, a.per_split, bx, by, ha,
+                                                   a.grid_y, &last);
     } else {
-        const uint32_t id = blockIdx.x - a_blocks;
+        const uint32_t id = b_id;
         if (B_IS_I8)
-            reduce_over_cols_i8_block(static_cast<const int8_t*>(b.T), b.ld, b.rows, b.cols, b.eq, b.partial,
-                                      b.per_split, id % b.grid_x, id / b.grid_x, lds);
+            reduce_over_cols_i8_block(static_cast<const int8_t*>(b.T), b.ld, b.rows, b.cols,
+                                      static_cast<const uint32_t*>(b.eq), b.partial, b.per_split, id % b.grid_x,
+                                      id / b.grid_x, lds);
         else
             reduce_over_cols_block<SB, kRowsPerBlock, kColsUnroll, true>(static_cast<const SB*>(b.T), b.ld, b.rows, b.cols,
-                                                                         b.eq, b.partial, b.per_split, id % b.grid_x,
-                                                                         id / b.grid_x, &lds[0][0]);
+                                                                         static_cast<const uint64_t*>(b.eq), b.partial,
+                                                                         b.per_split, id % b.grid_x, id / b.grid_x,
+                                                                         &lds[0][0]);
     }
 }
 
@@ -585,6 +1008,12 @@ hipError_t launch_over_rows(hipStream_t stream, const void* T, uint64_t rows, ui
         hipLaunchKernelGGL((reduce_over_rows_kernel<S, false>), grid, dim3(kBlock), 0, stream,
                            static_cast<const S*>(T), ld, rows, cols, eq, partial, sp.per_split);
     return hipGetLastError();
+}
+
+// words[i] = value, i < count
+__global__ __launch_bounds__(kBlock) void fill_words_kernel(uint64_t* __restrict__ words, uint64_t count, uint64_t value) {
+    for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < count; i += (uint64_t)gridDim.x * kBlock)
+        words[i] = value;
 }
 
 // ------------------------------------------------------------------ combine / dot
@@ -812,7 +1241,16 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_kernel(uint64_t* __restri
     Triple g = {0, 0, 0};
     {
         const uint64_t h = L >> 1;
-        for (uint64_t i = tid; i < h; i += kRoundsBlock) pair_eval(g, a[i], a[i + h], b[i], b[i + h]);
+        int bad = 0;
+        for (uint64_t i = tid; i < h; i += kRoundsBlock) {
+            const uint64_t x0 = a[i], x1 = a[i + h], y0 = b[i], y1 = b[i + h];
+            bad |= (x0 >= gl::P) | (x1 >= gl::P) | (y0 >= gl::P) | (y1 >= gl::P);
+            pair_eval(g, x0, x1, y0, y1);
+        }
+        if (__syncthreads_or(bad)) {  // the reductions did not deliver canonical field elements
+            if (tid == 0) words[kWordVA] = kNoValue;
+            return;
+        }
     }
     g = rounds_block_sum(g, lds);
     if (tid == 0 && absorb_claim) {
@@ -964,8 +1402,10 @@ __device__ __forceinline__ void rounds_in_lds(const uint64_t* ga, const uint64_t
     // have 2 L0 entries and are bound to fold_r = r_first on their way into LDS; the message of round
     // first + 1 has gone out already.
     uint32_t L = (uint32_t)L0;
+    int bad = 0;  // an entry that is no canonical field element: the reductions did not deliver
     for (uint32_t i = tid; i < L; i += kRoundsBlock) {
         uint64_t x = ga[i], y = gb[i];
+        bad |= (x >= gl::P) | (y >= gl::P);
         if (first) {
             x = gl::add(x, gl::mul(fold_r, gl::sub(ga[i + L], x)));
             y = gl::add(y, gl::mul(fold_r, gl::sub(gb[i + L], y)));
@@ -974,7 +1414,13 @@ __device__ __forceinline__ void rounds_in_lds(const uint64_t* ga, const uint64_t
         near[1][i] = y;
     }
     if (tid < 9 * kRoundsWaves) part[tid / kRoundsWaves][tid % kRoundsWaves] = 0;
-    __syncthreads();
+    if (__syncthreads_or(bad) && !first) {
+        if (tid == 0) {
+            for (int t = 0; t < 3; ++t) mail_post(&mb->g[0][t], kMailFail);
+            status[0] = 1;
+        }
+        return;
+    }
 
     if (!first) {  // round 1: plain evaluation of the tables as they are
         Triple g = {0, 0, 0};
@@ -1141,7 +1587,19 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs
     Triple g = {0, 0, 0};
     {
         const uint64_t h = L >> 1;
-        for (uint64_t i = tid; i < h; i += kRoundsBlock) pair_eval(g, a[i], a[i + h], b[i], b[i + h]);
+        int bad = 0;
+        for (uint64_t i = tid; i < h; i += kRoundsBlock) {
+            const uint64_t x0 = a[i], x1 = a[i + h], y0 = b[i], y1 = b[i + h];
+            bad |= (x0 >= gl::P) | (x1 >= gl::P) | (y0 >= gl::P) | (y1 >= gl::P);
+            pair_eval(g, x0, x1, y0, y1);
+        }
+        if (__syncthreads_or(bad)) {  // the reductions did not deliver canonical field elements
+            if (tid == 0) {
+                for (int t = 0; t < 3; ++t) mail_post(&mb->g[0][t], kMailFail);
+                status[0] = 1;
+            }
+            return;
+        }
     }
     g = rounds_block_sum(g, lds3);
     if (tid == 0) {
@@ -1291,10 +1749,10 @@ hipError_t front(hipStream_t stream, const int16_t* A, uint64_t countA, uint64_t
 }
 
 hipError_t eq_build2(hipStream_t stream, const Point& ptA, int tA, uint64_t* outA, const Point& ptB, int tB,
-                     uint64_t* outB) {
+                     uint64_t* outB, uint32_t* planesB) {
     const uint64_t total = (1ull << tA) + (1ull << tB);
     hipLaunchKernelGGL(eq_build2_kernel, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, ptA,
-                       tA, outA, ptB, tB, outB);
+                       tA, outA, ptB, tB, outB, planesB);
     return hipGetLastError();
 }
 
@@ -1312,15 +1770,27 @@ Split plan_over_rows(uint64_t rows, uint64_t cols) {
     return sp;
 }
 
+#ifndef IMM_BESIDE_DIV
+#define IMM_BESIDE_DIV 512
+#endif
+#ifndef IMM_BESIDE_MIN_KB
+#define IMM_BESIDE_MIN_KB 128u
+#endif
 Split plan_over_rows_beside(uint64_t rows, uint64_t cols, size_t elem_bytes, uint64_t other_bytes) {
     // Beside a larger reduction that fills the machine on its own, few long-lived workgroups stream best:
     // each takes about as many bytes as half a CU's share of the other table, at least 128 KiB.
-    uint64_t target = other_bytes / 512;
-    if (target < (128u << 10)) target = 128u << 10;
-    const uint64_t width = cols < 2 * kBlock ? cols : 2 * kBlock;  // columns of a workgroup
+    uint64_t target = other_bytes / IMM_BESIDE_DIV;
+    if (target < (IMM_BESIDE_MIN_KB << 10)) target = IMM_BESIDE_MIN_KB << 10;
+    const uint64_t block_cols = elem_bytes == 2 ? kI16BlockCols : 2 * kBlock;  // columns of a workgroup
+    const uint64_t width = cols < block_cols ? cols : block_cols;
     uint64_t per = target / (width * elem_bytes);
     if (per < 32) per = 32;
     per = (per + kRowsUnroll - 1) / kRowsUnroll * kRowsUnroll;
+    if (elem_bytes == 2 && per > kI16MaxSplit) per = kI16MaxSplit;
+    if ((rows + per - 1) / per > kHandoverMaxSplits) {  // keep the summing workgroup's share small
+        per = (rows + kHandoverMaxSplits - 1) / kHandoverMaxSplits;
+        per = (per + kRowsUnroll - 1) / kRowsUnroll * kRowsUnroll;
+    }
     if (per > rows) per = rows;
     Split sp;
     sp.per_split = per;
@@ -1358,22 +1828,33 @@ hipError_t reduce_over_rows(hipStream_t stream, const void* T, int dtype, uint64
                             const uint64_t* eq_rows, uint64_t* partial, Split sp) {
     switch (dtype) {
     case IMM_I8: return launch_over_rows<int8_t>(stream, T, rows, cols, ld, eq_rows, partial, sp);
-    case IMM_I16: return launch_over_rows<int16_t>(stream, T, rows, cols, ld, eq_rows, partial, sp);
+    case IMM_I16:
+        if (i16_fast_shape(T, cols, ld) && sp.per_split <= kI16MaxSplit) {
+            dim3 grid((unsigned)((cols + kI16BlockCols - 1) / kI16BlockCols), sp.nsplit);
+            hipLaunchKernelGGL(reduce_over_rows_i16_kernel, grid, dim3(kBlock), 0, stream, static_cast<const int16_t*>(T),
+                               ld, rows, cols, eq_rows, partial, sp.per_split);
+            return hipGetLastError();
+        }
+        return launch_over_rows<int16_t>(stream, T, rows, cols, ld, eq_rows, partial, sp);
     case IMM_I64: return launch_over_rows<int64_t>(stream, T, rows, cols, ld, eq_rows, partial, sp);
     case IMM_F64P: return launch_over_rows<uint64_t>(stream, T, rows, cols, ld, eq_rows, partial, sp);
     default: return hipErrorInvalidValue;
     }
 }
 
+static bool i8_fast_launch(const void* T, uint64_t cols, uint64_t ld, const void* planes, Split sp) {
+    return planes != nullptr && i8_fast_shape(cols) && sp.per_split % kI8ColsPerPass == 0 && sp.per_split <= kI8MaxSplit &&
+           reinterpret_cast<uintptr_t>(T) % 16 == 0 && ld % 16 == 0 && reinterpret_cast<uintptr_t>(planes) % 16 == 0;
+}
+
 hipError_t reduce_over_cols(hipStream_t stream, const void* T, int dtype, uint64_t rows, uint64_t cols, uint64_t ld,
-                            const uint64_t* eq_cols, uint64_t* partial, Split sp) {
+                            const uint64_t* eq_cols, const uint32_t* eq_planes, uint64_t* partial, Split sp) {
     switch (dtype) {
     case IMM_I8:
-        if (i8_fast_shape(cols) && sp.per_split % kI8ColsPerPass == 0 && sp.per_split <= kI8MaxSplit &&
-            reinterpret_cast<uintptr_t>(T) % 16 == 0 && ld % 16 == 0 && reinterpret_cast<uintptr_t>(eq_cols) % 16 == 0) {
+        if (i8_fast_launch(T, cols, ld, eq_planes, sp)) {
             dim3 grid((unsigned)((rows + kI8Rows - 1) / kI8Rows), sp.nsplit);
             hipLaunchKernelGGL(reduce_over_cols_i8_kernel, grid, dim3(kBlock), 0, stream,
-                               static_cast<const int8_t*>(T), ld, rows, cols, eq_cols, partial, sp.per_split);
+                               static_cast<const int8_t*>(T), ld, rows, cols, eq_planes, partial, sp.per_split);
             return hipGetLastError();
         }
         return launch_over_cols<int8_t>(stream, T, rows, cols, ld, eq_cols, partial, sp);
@@ -1385,32 +1866,48 @@ hipError_t reduce_over_cols(hipStream_t stream, const void* T, int dtype, uint64
 }
 
 hipError_t reduce_both(hipStream_t stream, const void* A, int dtA, uint64_t rowsA, uint64_t colsA, uint64_t ldA,
-                       const uint64_t* eq_rows, uint64_t* partA, Split spA, const void* B, int dtB, uint64_t rowsB,
-                       uint64_t colsB, uint64_t ldB, const uint64_t* eq_cols, uint64_t* partB, Split spB, bool* done) {
+                       const uint64_t* eq_rows, uint64_t* partA, Split spA, uint32_t* countersA, uint64_t paddedA,
+                       uint64_t* outA, const void* B, int dtB, uint64_t rowsB, uint64_t colsB, uint64_t ldB,
+                       const uint64_t* eq_cols, const uint32_t* eq_planes, uint64_t* partB, Split spB, bool* done) {
     *done = false;
     const size_t sa = dtA == IMM_F64P ? 8 : dtA == IMM_I16 ? 2 : 0;
     if (!sa || reinterpret_cast<uintptr_t>(A) % (2 * sa) != 0 || ldA % 2 != 0) return hipSuccess;
-    const bool eq_ok = reinterpret_cast<uintptr_t>(eq_cols) % 16 == 0;
     const bool b_wide = dtB == IMM_F64P && reinterpret_cast<uintptr_t>(B) % 16 == 0 && ldB % 2 == 0 &&
-                        spB.per_split % 2 == 0 && eq_ok;
-    const bool b_i8 = dtB == IMM_I8 && dtA == IMM_I16 && i8_fast_shape(colsB) && spB.per_split % kI8ColsPerPass == 0 &&
-                      spB.per_split <= kI8MaxSplit && reinterpret_cast<uintptr_t>(B) % 16 == 0 && ldB % 16 == 0 && eq_ok;
+                        spB.per_split % 2 == 0 && reinterpret_cast<uintptr_t>(eq_cols) % 16 == 0;
+    const bool b_i8 = dtB == IMM_I8 && dtA == IMM_I16 && i8_fast_launch(B, colsB, ldB, eq_planes, spB);
     if (!b_wide && !b_i8) return hipSuccess;
+    const bool a_i16 = dtA == IMM_I16 && i16_fast_shape(A, colsA, ldA) && spA.per_split <= kI16MaxSplit;
+    const uint64_t block_colsA = a_i16 ? kI16BlockCols : 2 * kBlock;
     ReduceArgs a{A, ldA, rowsA, colsA, eq_rows, partA, spA.per_split,
-                 (uint32_t)(((colsA + 1) / 2 + kBlock - 1) / kBlock), spA.nsplit};
-    ReduceArgs b{B, ldB, rowsB, colsB, eq_cols, partB, spB.per_split,
+                 (uint32_t)((colsA + block_colsA - 1) / block_colsA), spA.nsplit};
+    if (a.grid_x > kHandoverBlocks) return hipSuccess;
+    ReduceArgs b{B, ldB, rowsB, colsB, b_i8 ? static_cast<const void*>(eq_planes) : static_cast<const void*>(eq_cols), partB,
+                 spB.per_split,
                  (uint32_t)(b_i8 ? (rowsB + kI8Rows - 1) / kI8Rows : (rowsB + kRowsPerBlock - 1) / kRowsPerBlock),
                  spB.nsplit};
+    const Handover ha{countersA, outA, paddedA};
     const uint64_t blocks = (uint64_t)a.grid_x * a.grid_y + (uint64_t)b.grid_x * b.grid_y;
     if (blocks > 0x7FFFFFFFull) return hipSuccess;
     const dim3 grid((unsigned)blocks);
-    if (b_i8)
-        hipLaunchKernelGGL((reduce_both_kernel<int16_t, int8_t, true>), grid, dim3(kBlock), 0, stream, a, b);
+    if (b_i8 && a_i16)
+        hipLaunchKernelGGL((reduce_both_kernel<int16_t, int8_t, true, true>), grid, dim3(kBlock), 0, stream, a, ha, b);
+    else if (b_i8)
+        hipLaunchKernelGGL((reduce_both_kernel<int16_t, int8_t, false, true>), grid, dim3(kBlock), 0, stream, a, ha, b);
     else if (dtA == IMM_F64P)
-        hipLaunchKernelGGL((reduce_both_kernel<uint64_t, uint64_t, false>), grid, dim3(kBlock), 0, stream, a, b);
+        hipLaunchKernelGGL((reduce_both_kernel<uint64_t, uint64_t, false, false>), grid, dim3(kBlock), 0, stream, a, ha, b);
+    else if (a_i16)
+        hipLaunchKernelGGL((reduce_both_kernel<int16_t, uint64_t, true, false>), grid, dim3(kBlock), 0, stream, a, ha, b);
     else
-        hipLaunchKernelGGL((reduce_both_kernel<int16_t, uint64_t, false>), grid, dim3(kBlock), 0, stream, a, b);
+        hipLaunchKernelGGL((reduce_both_kernel<int16_t, uint64_t, false, false>), grid, dim3(kBlock), 0, stream, a, ha, b);
     *done = true;
+    return hipGetLastError();
+}
+
+hipError_t fill_words(hipStream_t stream, uint64_t* words, uint64_t count, uint64_t value) {
+    if (!count) return hipSuccess;
+    uint64_t blocks = (count + kBlock - 1) / kBlock;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, stream, words, count, value);
     return hipGetLastError();
 }
 

@@ -185,8 +185,8 @@ static inline void reply_store(uint64_t* slot, uint64_t v) {
 
 struct imm_ctx {
     int device = 0;
-    imm::DevBuf eqx, eqy, a, b, partA, partB, round_scratch, words, snapA, snapB, group_tables,
-        ldd_partial, ldd_post, ldd_sum, ldd_arrive, commit_leaves, commit_digests;
+    imm::DevBuf eqx, eqy, eqy_planes, a, b, partA, partB, handA, hand_counters, round_scratch, words, snapA, snapB,
+        group_tables, ldd_partial, ldd_post, ldd_sum, ldd_arrive, commit_leaves, commit_digests;
     uint64_t* pinned = nullptr;  // host staging, 4 KiB
     imm::k::Mailbox* mailbox = nullptr;  // pinned + coherent, kRoundsMaxJobs of them: g_k out, r_k in
     uint64_t* replies = nullptr;         // host-writable device memory for r_k, or null (then the mailbox carries them)
@@ -214,6 +214,17 @@ struct imm_ctx {
         int set;
     } ahead[kAheadDepth];                  // in proof order; ahead[0] belongs to the proof after the current one
     int ahead_count = 0;
+    // host-side time marks of the last proof (IMM_OPT_TIMELINE)
+    bool timeline = false;
+    int marks = 0;
+    uint64_t mark_ns[IMM_T_COUNT * 2] = {};
+    uint32_t mark_id[IMM_T_COUNT * 2] = {};
+    void mark(uint32_t id) {
+        if (!timeline || marks >= IMM_T_COUNT * 2) return;
+        mark_ns[marks] = (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+                             std::chrono::steady_clock::now().time_since_epoch()).count();
+        mark_id[marks++] = id;
+    }
     // intermediates of the last single proof (debug)
     int dbg_mu = -1, dbg_delta = -1, dbg_nu = -1;
     uint64_t dbg_rx[IMM_MAX_ROUNDS], dbg_ry[IMM_MAX_ROUNDS], dbg_r[IMM_MAX_ROUNDS];
@@ -233,17 +244,40 @@ static int fetch_words(imm_ctx* ctx, hipStream_t s, const uint64_t* dev, size_t 
     return IMM_OK;
 }
 
-// eq vectors for the row point (tR coordinates) and the column point (tC).
-static int build_eq(imm_ctx* ctx, hipStream_t s, const uint64_t* pr, int tR, const uint64_t* pc, int tC) {
+// eq vectors for the row point (tR coordinates) and the column point (tC); with `planes` the column
+// vector also in the byte-plane form the int8 reduction reads (ctx->eqy_planes).
+static int build_eq(imm_ctx* ctx, hipStream_t s, const uint64_t* pr, int tR, const uint64_t* pc, int tC,
+                    bool planes = false) {
     int rc;
     if ((rc = ctx->eqx.ensure(sizeof(uint64_t) << tR))) return rc;
     if ((rc = ctx->eqy.ensure(sizeof(uint64_t) << tC))) return rc;
+    if (planes && (rc = ctx->eqy_planes.ensure(sizeof(uint64_t) << tC))) return rc;
     k::Point a{}, b{};
     for (int i = 0; i < tR; ++i) a.v[i] = pr[i];
     for (int i = 0; i < tC; ++i) b.v[i] = pc[i];
     if ((rc = ctx->prof.begin(IMM_K_EQ, s))) return rc;
-    IMM_HIP(k::eq_build2(s, a, tR, ctx->eqx.u64(), b, tC, ctx->eqy.u64()));
+    IMM_HIP(k::eq_build2(s, a, tR, ctx->eqx.u64(), b, tC, ctx->eqy.u64(),
+                         planes ? static_cast<uint32_t*>(ctx->eqy_planes.p) : nullptr));
     return ctx->prof.end(IMM_K_EQ, s);
+}
+
+// Whether the reduction of a table along its rows can read it as int8 (then the eq vector's byte planes are needed).
+static bool wants_planes(int dt, uint64_t cols) { return dt == IMM_I8 && cols % 16 == 0; }
+
+// The memory of the hand-over between the workgroups of A's reduction (k::reduce_both): `words` words
+// of partial vectors, all holding k::kNoValue, and zeroed counters.  Launches leave it as they found it,
+// so it is only written here when it is (re)allocated.
+static int ensure_handover(imm_ctx* ctx, hipStream_t s, uint64_t words) {
+    int rc;
+    if (ctx->handA.bytes < words * sizeof(uint64_t)) {
+        if ((rc = ctx->handA.ensure(words * sizeof(uint64_t)))) return rc;
+        IMM_HIP(k::fill_words(s, ctx->handA.u64(), ctx->handA.bytes / sizeof(uint64_t), k::kNoValue));
+    }
+    if (!ctx->hand_counters.p) {
+        if ((rc = ctx->hand_counters.ensure(sizeof(uint64_t) * (k::kHandoverBlocks / 2)))) return rc;
+        IMM_HIP(k::fill_words(s, ctx->hand_counters.u64(), k::kHandoverBlocks / 2, 0));
+    }
+    return IMM_OK;
 }
 
 // Sum the per-split partial vectors into out[0..len) and zero out[len..padded).  When the
@@ -281,7 +315,9 @@ static int partial_over_cols(imm_ctx* ctx, hipStream_t s, int kid, const void* T
     const bool direct = sp.nsplit == 1;
     if (!direct && (rc = part.ensure(sizeof(uint64_t) * sp.nsplit * rows))) return rc;
     if ((rc = ctx->prof.begin(kid, s))) return rc;
-    IMM_HIP(k::reduce_over_cols(s, T, dt, rows, cols, ld, eq, direct ? out : part.u64(), sp));
+    IMM_HIP(k::reduce_over_cols(s, T, dt, rows, cols, ld, eq,
+                                wants_planes(dt, cols) ? static_cast<const uint32_t*>(ctx->eqy_planes.p) : nullptr,
+                                direct ? out : part.u64(), sp));
     if ((rc = ctx->prof.end(kid, s))) return rc;
     return finish_partial(ctx, s, direct, part, sp.nsplit, rows, padded, out);
 }
@@ -459,6 +495,7 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
         // A raw, B raw or widened beforehand: the widening and the eq vectors (a0 + a1 + a2) go out as one launch
         const bool rawB = dtB == IMM_I8;
         job.tr.head(m, d, n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, job.mu, job.nu, job.rx, job.ry);
+        ctx->mark(IMM_T_HEAD_HASHED);
         if ((rc = ctx->eqx.ensure(sizeof(uint64_t) << job.mu))) return rc;
         if ((rc = ctx->eqy.ensure(sizeof(uint64_t) << job.nu))) return rc;
         if ((rc = encA.ensure(sizeof(uint64_t) * m * d))) return rc;
@@ -475,6 +512,7 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
         if (rawB) Bp = encB.p;
         dtA = dtB = IMM_F64P;
         eq_done = true;
+        ctx->mark(IMM_T_FRONT_LAUNCHED);
     }
     if (ctx->widen && dtA != IMM_F64P) {
         if ((rc = encA.ensure(sizeof(uint64_t) * m * d))) return rc;
@@ -495,34 +533,35 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
     // a0 + a2: the points from the transcript, and their eq vectors
     if (!eq_done) {
         job.tr.head(m, d, n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, job.mu, job.nu, job.rx, job.ry);
-        if ((rc = build_eq(ctx, s, job.rx, job.mu, job.ry, job.nu))) return rc;
+        ctx->mark(IMM_T_HEAD_HASHED);
+        if ((rc = build_eq(ctx, s, job.rx, job.mu, job.ry, job.nu, wants_planes(dtB, n)))) return rc;
+        ctx->mark(IMM_T_FRONT_LAUNCHED);
     }
     if (taken_over) IMM_HIP(hipStreamWaitEvent(s, ctx->ahead_done[ctx->set], 0));  // the tables are written
 
-    // a3 + a4: in narrow-read mode both reductions in one launch where the operand forms allow it
-    // (the small table of A streams alongside B's instead of filling and draining the machine on
-    // its own), else one after the other.
-    // (only beside the narrow-read reduction of B: beside the widened table, ten times larger, A's
-    // share is within the noise, and the reduction of B keeps a launch and a bandwidth figure of its own)
+    // a3 + a4: in narrow-read mode both reductions in one launch where the operand forms allow it: the
+    // table of A is read beside B's instead of filling and draining the machine on its own, and the
+    // workgroup of A's reduction that finishes a block of columns last sums its partial vectors, so no
+    // launch stands between the reductions and the round kernel.
     bool both = false;
-    if (ctx->fuse_reductions && dtB == IMM_I8) {
-        const size_t elemA = dtA == IMM_F64P || dtA == IMM_I64 ? 8 : dtA == IMM_I16 ? 2 : 1;
-        const size_t elemB = dtB == IMM_F64P || dtB == IMM_I64 ? 8 : dtB == IMM_I16 ? 2 : 1;
+    // (Beside a widened table of B nothing is gained: both stream from HBM at its rate, so A's bytes take
+    // their time either way, and the hand-over costs more than the launch it saves.)
+    if (ctx->fuse_reductions && dtB == IMM_I8 && (dtA == IMM_I16 || dtA == IMM_F64P)) {
+        const size_t elemA = dtA == IMM_F64P ? 8 : 2, elemB = dtB == IMM_F64P ? 8 : 1;
         const k::Split spA = k::plan_over_rows_beside(m, d, elemA, d * n * elemB), spB = k::plan_over_cols(d, n, dtB);
-        const bool directA = spA.nsplit == 1, directB = spB.nsplit == 1;
-        if (!directA && (rc = ctx->partA.ensure(sizeof(uint64_t) * spA.nsplit * d))) return rc;
+        const bool directB = spB.nsplit == 1;
+        if ((rc = ensure_handover(ctx, s, (uint64_t)spA.nsplit * d))) return rc;
         if (!directB && (rc = ctx->partB.ensure(sizeof(uint64_t) * spB.nsplit * d))) return rc;
         if ((rc = ctx->prof.begin(IMM_K_REDUCE_B, s))) return rc;
-        IMM_HIP(k::reduce_both(s, Ap, dtA, m, d, d, ctx->eqx.u64(), directA ? job.a : ctx->partA.u64(), spA, Bp, dtB, d, n,
-                               n, ctx->eqy.u64(), directB ? job.b : ctx->partB.u64(), spB, &both));
+        IMM_HIP(k::reduce_both(s, Ap, dtA, m, d, d, ctx->eqx.u64(), ctx->handA.u64(), spA,
+                               static_cast<uint32_t*>(ctx->hand_counters.p), D, job.a, Bp, dtB, d, n, n, ctx->eqy.u64(),
+                               wants_planes(dtB, n) ? static_cast<const uint32_t*>(ctx->eqy_planes.p) : nullptr,
+                               directB ? job.b : ctx->partB.u64(), spB, &both));
         if (both) {
             if ((rc = ctx->prof.end(IMM_K_REDUCE_B, s))) return rc;
+            if ((rc = finish_partial(ctx, s, directB, ctx->partB, spB.nsplit, d, D, job.b))) return rc;
         } else {
             ctx->prof.cancel(IMM_K_REDUCE_B);
-        }
-        if (both) {
-            if ((rc = finish_partial(ctx, s, directA, ctx->partA, spA.nsplit, d, D, job.a))) return rc;
-            if ((rc = finish_partial(ctx, s, directB, ctx->partB, spB.nsplit, d, D, job.b))) return rc;
         }
     }
     if (!both) {
@@ -551,6 +590,7 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
                 return rc;
         }
     }
+    ctx->mark(IMM_T_REDUCTIONS_LAUNCHED);
     if (look_count > 0 && ctx->widen && ctx->encode_ahead && (rc = ahead_queue(ctx, s, look, look_count))) return rc;
 
     std::memset(job.out, 0, sizeof(*job.out));
@@ -627,6 +667,7 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
     if ((rc = ctx->prof.begin(IMM_K_ROUND, s))) return rc;
     IMM_HIP(k::rounds_mailbox(s, rj, count, mb, replies, ctx->spin_limit, status_dev));
     if ((rc = ctx->prof.end(IMM_K_ROUND, s))) return rc;
+    ctx->mark(IMM_T_ROUNDS_LAUNCHED);
     bool ok = true;
     for (int slot = 0; slot < max_rounds && ok; ++slot) {
         for (int p = 0; p < count && ok; ++p) {
@@ -636,6 +677,7 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
             uint64_t g[3];
             for (int t = 0; t < 3 && ok; ++t) ok = mail_wait(&mb[p].g[slot][t], ctx->host_wait_ms, &g[t]);
             if (!ok) break;
+            if (slot == 0 && p == 0) ctx->mark(IMM_T_FIRST_MESSAGE);
             if (!job.claim_absorbed) {
                 job.out->c0 = hf::add(g[0], g[1]);
                 job.tr.absorb_words("clmC", &job.out->c0, 1);
@@ -650,6 +692,8 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
                 reply_store(replies + (size_t)p * IMM_MAX_ROUNDS + slot, job.rr[kk]);
             else
                 __atomic_store_n(&mb[p].r[slot], job.rr[kk], __ATOMIC_RELEASE);
+            if (p == 0 && (slot == 0 || slot == rj.job[0].rounds - 1))
+                ctx->mark(slot == 0 ? IMM_T_FIRST_CHALLENGE : IMM_T_LAST_CHALLENGE);
         }
     }
     for (int p = 0; p < count && ok; ++p) {
@@ -659,6 +703,7 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
         jobs[p]->out->vA = fin[0];
         jobs[p]->out->vB = fin[1];
         jobs[p]->tr.absorb_words("fin ", fin, 2);
+        if (p == 0) ctx->mark(IMM_T_FINAL_VALUES);
     }
     if (!ok) {
         // release every workgroup from whatever wait it is in, then let the kernel drain
@@ -730,6 +775,8 @@ static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uin
     if (!state || !out) return IMM_E_NULL;
     int rc;
     if ((rc = check_desc(ds))) return rc;
+    ctx->marks = 0;
+    ctx->mark(IMM_T_ENTRY);
     Job job(state);
     job.ds = &ds;
     job.out = out;
@@ -754,6 +801,7 @@ static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uin
         std::memcpy(ctx->dbg_ry, job.ry, sizeof(job.ry));
         std::memcpy(ctx->dbg_r, job.rr, sizeof(job.rr));
     }
+    ctx->mark(IMM_T_EXIT);
     return ctx->prof.mask ? ctx->prof.flush() : IMM_OK;
 }
 
@@ -881,7 +929,8 @@ extern "C" int imm_ctx_destroy(imm_ctx* ctx) {
     }
     for (DevBuf& bf : ctx->encA) bf.release();
     for (DevBuf& bf : ctx->encB) bf.release();
-    for (DevBuf* bf : {&ctx->eqx, &ctx->eqy, &ctx->a, &ctx->b, &ctx->partA, &ctx->partB,
+    for (DevBuf* bf : {&ctx->eqx, &ctx->eqy, &ctx->eqy_planes, &ctx->a, &ctx->b, &ctx->partA, &ctx->partB, &ctx->handA,
+                       &ctx->hand_counters,
                        &ctx->round_scratch, &ctx->words, &ctx->snapA, &ctx->snapB, &ctx->group_tables,
                        &ctx->ldd_partial, &ctx->ldd_post, &ctx->ldd_sum, &ctx->ldd_arrive, &ctx->commit_leaves,
                        &ctx->commit_digests})
@@ -901,6 +950,7 @@ extern "C" int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value) {
     case IMM_OPT_WIDEN: ctx->widen = value != 0; return IMM_OK;
     case IMM_OPT_FUSE_REDUCTIONS: ctx->fuse_reductions = value != 0; return IMM_OK;
     case IMM_OPT_ENCODE_AHEAD: ctx->encode_ahead = value != 0; return IMM_OK;
+    case IMM_OPT_TIMELINE: ctx->timeline = value != 0; ctx->marks = 0; return IMM_OK;
     case IMM_OPT_REPLY_IN_DEVICE_MEMORY: ctx->reply_in_device_memory = value != 0; return IMM_OK;
     case IMM_OPT_TRANSCRIPT:
         if (value != IMM_TRANSCRIPT_DEVICE && value != IMM_TRANSCRIPT_HOST) return IMM_E_SHAPE;
@@ -984,7 +1034,7 @@ extern "C" int imm_mle_eval(imm_ctx* ctx, void* stream, const void* table_dev, i
         IMM_HIP(hipSetDevice(ctx->device));
         hipStream_t s = static_cast<hipStream_t>(stream);
         int rc;
-        if ((rc = build_eq(ctx, s, pt_rows, tR, pt_cols, tC))) return rc;
+        if ((rc = build_eq(ctx, s, pt_rows, tR, pt_cols, tC, cols >= 256 && wants_planes((int)dt, cols)))) return rc;
         if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
         if (cols >= 256) {
             // wide table: reduce along the rows first, then one dot product with the row weights
@@ -1104,6 +1154,17 @@ extern "C" int imm_debug_fetch(imm_ctx* ctx, int which, uint64_t* out_host, uint
         }
         return IMM_OK;
     });
+}
+
+extern "C" int imm_debug_timeline(imm_ctx* ctx, uint32_t* ids, uint64_t* ns, uint32_t capacity, uint32_t* count) {
+    if (!ctx || !count) return IMM_E_NULL;
+    if (!ctx->timeline) return IMM_E_STATE;
+    *count = (uint32_t)ctx->marks;
+    for (int i = 0; i < ctx->marks && (uint32_t)i < capacity; ++i) {
+        if (ids) ids[i] = ctx->mark_id[i];
+        if (ns) ns[i] = ctx->mark_ns[i];
+    }
+    return IMM_OK;
 }
 
 extern "C" int imm_debug_device_challenge(imm_ctx* ctx, void* stream, uint8_t state[32], uint64_t* out_host) {

@@ -1,5 +1,5 @@
 // imm_mle_eval_static: the multilinear-extension evaluation of imm_mle_eval for callers that cannot
-// allocate.  Same kernels, same arithmetic; the working memory (both eq vectors, the vector of
+// allocate.  Same kernels, same arithmetic; the working memory (both eq vectors, the column one also cut into bytes for int8 tables, the vector of
 // per-row or per-column partial evaluations, the per-split partial vectors) lives in an array that
 // is part of the library's device image instead of in buffers a context allocates.
 #include <hip/hip_runtime.h>
@@ -70,7 +70,10 @@ extern "C" int imm_mle_eval_static(void* stream, const void* table_dev, imm_dtyp
     const bool direct = sp.nsplit == 1;  // a single split writes the vector itself
     const uint64_t w_eqx = round_up(1ull << tR), w_eqy = round_up(1ull << tC), w_vec = round_up(len);
     const uint64_t w_part = direct ? 0 : round_up((uint64_t)sp.nsplit * len);
-    const uint64_t need = w_eqx + w_eqy + w_vec + w_part;
+    // an int8 table read along its rows takes the column eq vector cut into byte planes as well
+    const bool planes = along_rows_first && dt == IMM_I8 && cols % 16 == 0;
+    const uint64_t w_planes = planes ? w_eqy : 0;
+    const uint64_t need = w_eqx + w_eqy + w_vec + w_part + w_planes;
     if (need > kWords) {
         char msg[192];
         std::snprintf(msg, sizeof(msg),
@@ -91,6 +94,7 @@ extern "C" int imm_mle_eval_static(void* stream, const void* table_dev, imm_dtyp
     uint64_t* eqy = eqx + w_eqx;
     uint64_t* vec = eqy + w_eqy;
     uint64_t* part = vec + w_vec;
+    uint32_t* eqy_planes = planes ? reinterpret_cast<uint32_t*>(part + w_part) : nullptr;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     k::Point pr{}, pc{};
@@ -98,9 +102,9 @@ extern "C" int imm_mle_eval_static(void* stream, const void* table_dev, imm_dtyp
     for (int i = 0; i < tC; ++i) pc.v[i] = pt_cols[i];
     // Nothing in the array has to start at zero: the eq vectors, the partial vectors and the vector
     // of partial evaluations are written in full before they are read.
-    if ((e = k::eq_build2(s, pr, tR, eqx, pc, tC, eqy)) != hipSuccess) return fail_hip(e, "eq_build2");
+    if ((e = k::eq_build2(s, pr, tR, eqx, pc, tC, eqy, eqy_planes)) != hipSuccess) return fail_hip(e, "eq_build2");
     if (along_rows_first)
-        e = k::reduce_over_cols(s, table_dev, (int)dt, rows, cols, ld, eqy, direct ? vec : part, sp);
+        e = k::reduce_over_cols(s, table_dev, (int)dt, rows, cols, ld, eqy, eqy_planes, direct ? vec : part, sp);
     else
         e = k::reduce_over_rows(s, table_dev, (int)dt, rows, cols, ld, eqx, direct ? vec : part, sp);
     if (e != hipSuccess) return fail_hip(e, "partial evaluation");

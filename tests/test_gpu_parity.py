@@ -573,9 +573,10 @@ def test_profiling_counts_launches(torch, ctx, oracle_fast):
             assert counts["encode_A"][0] == (3 if widen and not fused else 0)
             assert counts["encode_B"][0] == (3 if widen else 0)
             assert counts["eq_build"][0] == (0 if widen and fused else 3)
-            # in narrow-read mode one launch covers both reductions unless that is switched off
+            # in narrow-read mode one launch covers both reductions and the sum of A's partial vectors,
+            # unless that is switched off
             assert counts["reduce_A"][0] == (0 if (fused and not widen) else 3) and counts["reduce_B"][0] == 3
-            assert counts["combine"][0] <= 6
+            assert counts["combine"][0] == (0 if fused else counts["combine"][0]) and counts["combine"][0] <= 6
             assert counts["round"][0] == 3       # all rounds of a proof run in one launch
             assert all(ms > 0 for (n, ms) in counts.values() if n)
     finally:
@@ -626,3 +627,16 @@ def test_challenges_through_the_mailbox_or_through_device_memory(torch, ctx, ora
             assert got.words() == ref.proof_words(want) and s_got == s_want
     finally:
         ctx.imm_ctx_set_option(imm.IMM_OPT_REPLY_IN_DEVICE_MEMORY, 1)
+
+
+def test_device_challenge_takes_the_rejection_branch_like_the_oracle(torch, ctx):
+    """The challenge derivation that lane 0 of the round kernel runs when the device hashes the
+    transcript, on the stored state whose first candidate is not canonical, and on ordinary states."""
+    from tests.test_library_cpu import rejecting_state
+    state, first, want, after = rejecting_state()
+    assert first >= P
+    assert ctx.imm_debug_device_challenge(state) == (want, after)
+    s_dev, tr = ref.FS_INIT, ref.Transcript(ref.FS_INIT)
+    for _ in range(5):
+        v, s_dev = ctx.imm_debug_device_challenge(s_dev)
+        assert v == tr.challenge() and s_dev == tr.s

@@ -249,3 +249,32 @@ def test_verify_chained_states(lib, oracle_fast):
         A, B, C, _ = items[coms.index(com)]
         assert imm.imm_verify(com, s, to_proof(pr), A, B, C) == (0, st, 0)
         s = s_next
+
+
+def rejecting_state():
+    """tests/golden/rejecting_state.txt: a state whose first challenge candidate is >= p, with the
+    oracle's outcome (written by tests/golden/find_rejecting_state.py from oracle/reference.py)."""
+    kv = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "rejecting_state.txt")):
+        if " = " in line and not line.startswith("#"):
+            k, v = line.strip().split(" = ")
+            kv[k] = v
+    return (bytes.fromhex(kv["state"]), int(kv["first_candidate"], 16), int(kv["challenge"], 16),
+            bytes.fromhex(kv["state_after"]))
+
+
+def test_challenge_takes_the_rejection_branch_like_the_oracle(lib):
+    """The library's host transcript on a state whose first candidate is not canonical (probability
+    2^-32 per challenge): it must move on to the next counter, not reduce or keep the candidate."""
+    state, first, want, after = rejecting_state()
+    # the stored values are the oracle's, and the first candidate is indeed rejected
+    assert first >= P
+    assert int.from_bytes(hashlib.sha256(state + b"chal" + (0).to_bytes(4, "little")).digest()[:8], "little") == first
+    tr = ref.Transcript(state)
+    assert tr.challenge() == want and tr.s == after and want < P
+    assert imm.imm_transcript_challenge(state) == (want, after)
+    # ordinary states: the same as the oracle, challenge after challenge
+    s_lib, tr = ref.FS_INIT, ref.Transcript(ref.FS_INIT)
+    for _ in range(20):
+        v, s_lib = imm.imm_transcript_challenge(s_lib)
+        assert v == tr.challenge() and s_lib == tr.s
