@@ -382,9 +382,68 @@ def main():
         us = msf * 1e3 / nf
         result["fold_kernel_large_tables"] = {"L": Lf, "us_per_launch": round(us, 1), "algorithmic_MB": 24 * Lf / 1e6,
                                               "GBps": round(24 * Lf / (us * 1e-6) / 1e9, 1),
-                                              "frac_of_8TBps": round(24 * Lf / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 3)}
+                                              "frac_of_8TBps": round(24 * Lf / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 3),
+                                              "traffic_mix": "2 bytes read per byte written, in place"}
         ctx.imm_ctx_reset_profiling()
         del ta, tb
+
+    # The reduction of A over its rows (K3a) on a table large enough for its launch to be mostly
+    # streaming: 16384 x 4096 field elements (537 MB), as the A of a statement with a narrow B, both
+    # operands passed pre-encoded and each reduction in a launch of its own.  At the FFN shape the same
+    # kernel reads 67 MB in a launch that is largely filling and draining the machine.
+    if args.workload == "ffn_up":
+        mL, dL, nL = 16384, 4096, 16
+        Al = torch.randint(0, 1 << 62, (mL, dL), dtype=torch.int64, device="cuda").view(torch.uint64)
+        Bl = torch.randint(0, 1 << 62, (dL, nL), dtype=torch.int64, device="cuda").view(torch.uint64)
+        zA, zB, zC = (torch.zeros(sh, dtype=dt).numpy() for sh, dt in (((1, 1), torch.int16), ((1, 1), torch.int8), ((1, 1), torch.int64)))
+        comL = imm.imm_commit_matmul(zA, zB, zC, 1, 1, 1)      # digests of anything: the prover only absorbs them
+        for c1, rows, cols in ((comL.A, mL, dL), (comL.B, dL, nL), (comL.C, mL, nL)):
+            c1.rows, c1.cols = rows, cols
+        ctx.imm_ctx_set_option(imm.IMM_OPT_FUSE_REDUCTIONS, 0)
+        for _ in range(2):
+            ctx.imm_sumcheck_matmul_prove(Al, Bl, comL, s0)
+        ctx.imm_ctx_reset_profiling()
+        ctx.imm_ctx_set_profiling(1 << imm.IMM_K_REDUCE_A)
+        for _ in range(10):
+            ctx.imm_sumcheck_matmul_prove(Al, Bl, comL, s0)
+        ctx.imm_ctx_set_profiling(0)
+        ctx.imm_ctx_set_option(imm.IMM_OPT_FUSE_REDUCTIONS, 1)
+        na, msa = ctx.imm_ctx_kernel_time(imm.IMM_K_REDUCE_A)
+        usa = msa * 1e3 / na
+        abytes = 8 * mL * dL
+        result["reduce_A_large"] = {"rows": mL, "cols": dL, "us_per_launch": round(usa, 1), "algorithmic_MB": abytes / 1e6,
+                                    "GBps": round(abytes / (usa * 1e-6) / 1e9, 1),
+                                    "frac_of_8TBps": round(abytes / (usa * 1e-6) / 1e9 / HBM_PEAK_GBS, 3)}
+        ctx.imm_ctx_reset_profiling()
+        del Al, Bl
+
+    # What the memory system of this machine delivers to plain library kernels with the same traffic mixes
+    # (512 MiB operands, HIP events on torch's stream): the practical ceilings next to the 8 TB/s peak.
+    if args.workload == "ffn_up":
+        nel = 64 << 20
+        u = torch.arange(nel, dtype=torch.int64, device="cuda")
+        v = torch.ones(nel, dtype=torch.int64, device="cuda")
+        o = torch.empty(nel, dtype=torch.int64, device="cuda")
+
+        def torch_rate(fn, nbytes, reps=10):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            e1.synchronize()
+            return round(nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+
+        result["memory_ceilings_GBps"] = {
+            "read_only (torch.sum, 512 MiB)": torch_rate(lambda: u.sum(), 8 * nel),
+            "write_only (fill_, 512 MiB)": torch_rate(lambda: o.fill_(7), 8 * nel),
+            "copy 1 read : 1 write (copy_, 2 x 512 MiB)": torch_rate(lambda: o.copy_(u), 16 * nel),
+            "2 reads : 1 write (torch.add out=, 3 x 512 MiB)": torch_rate(lambda: torch.add(u, v, out=o), 24 * nel),
+            "note": "library kernels of the PyTorch build in this image, not tuned for this part; the hand-written "
+                    "kernels above are to be read against the 8 TB/s peak, these only say what a plain stream gets"}
+        del u, v, o
 
     # The logit-distance step of the audit on the logits of `ldd_steps` decision steps over a
     # 128256-entry vocabulary: TV and KL of the two softmax rows (8 B per vocabulary entry: one fp32
@@ -512,6 +571,17 @@ def main():
         result["other_workloads"] = {
             name: other_workload(name, torch, imm, workloads, ctx, 10, 0.0 if args.no_cpu_baseline else 3.0)
             for name in ("dense_layer", "moe")}
+    # the other kernels the bandwidth target names, next to the dominant one
+    also = {}
+    if "frac_of_8TBps" in kernels.get("reduce_A", {}):
+        also["reduce_A (K3a) at this shape"] = kernels["reduce_A"]["frac_of_8TBps"]
+    if "reduce_A_large" in result:
+        also["reduce_A (K3a) on 16384 x 4096"] = result["reduce_A_large"]["frac_of_8TBps"]
+    if "fold_kernel_large_tables" in result:
+        also["fold + evaluate (K4) on 2^%d entries" % args.fold_log2] = result["fold_kernel_large_tables"]["frac_of_8TBps"]
+    if "frac_of_8TBps" in kernels.get("encode_B", {}):
+        also["encode (K1, with K2 where they share a launch)"] = kernels["encode_B"]["frac_of_8TBps"]
+    result["roofline"]["other_streaming_kernels_frac"] = also
     print(json.dumps(result))
 
 

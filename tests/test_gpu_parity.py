@@ -425,6 +425,26 @@ def test_proofs_are_deterministic_and_survive_other_streams(torch, ctx, oracle_f
         p, s = ctx.imm_sumcheck_matmul_prove(Ad, Bd, com, ref.FS_INIT, stream=side)
     side.synchronize()
     assert p.words() == first.words() and s == s_first
+    # the same bytes from every launch geometry: the grids and the way partial results are summed
+    # change with the execution mode (one launch or several, partial vectors summed by a launch of
+    # their own, in another kernel's launch, or by the last workgroup), the arithmetic must not
+    rng = np.random.default_rng(31)
+    A2 = rng.integers(-2**15, 2**15, size=(300, 2048), dtype=np.int16)
+    B2 = rng.integers(-128, 128, size=(2048, 1040), dtype=np.int8)
+    com2 = imm.imm_commit_matmul(A2, B2, oracle_fast.matmul(A2, B2), 300, 2048, 1040)
+    A2d, B2d = dev(torch, A2), dev(torch, B2)
+    base, s_base = ctx.imm_sumcheck_matmul_prove(A2d, B2d, com2, ref.FS_INIT)
+    try:
+        for widen in (1, 0):
+            for fused in (1, 0):
+                ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, widen)
+                ctx.imm_ctx_set_option(imm.IMM_OPT_FUSE_REDUCTIONS, fused)
+                for _ in range(25):
+                    p, s = ctx.imm_sumcheck_matmul_prove(A2d, B2d, com2, ref.FS_INIT)
+                    assert p.words() == base.words() and s == s_base, (widen, fused)
+    finally:
+        ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
+        ctx.imm_ctx_set_option(imm.IMM_OPT_FUSE_REDUCTIONS, 1)
 
 
 def test_host_transcript_bounded_waits(torch, oracle_fast):

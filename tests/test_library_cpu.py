@@ -278,3 +278,47 @@ def test_challenge_takes_the_rejection_branch_like_the_oracle(lib):
     for _ in range(20):
         v, s_lib = imm.imm_transcript_challenge(s_lib)
         assert v == tr.challenge() and s_lib == tr.s
+
+
+def test_host_sources_under_address_and_undefined_behaviour_sanitizers(oracle_fast, tmp_path):
+    """The library's CPU sources (SHA-256 with its instruction-set dispatch, transcript, commitments,
+    verifier) compiled with -fsanitize=address,undefined into a small driver; its results on a few
+    statements, one of them with a matrix spanning several commitment leaves and a state that takes
+    the rejection branch of the challenge derivation, equal the oracle's, and no sanitizer speaks."""
+    import shutil
+    import subprocess
+    cxx = shutil.which("g++")
+    if cxx is None:
+        pytest.skip("no host compiler")
+    csrc = os.path.join(ROOT, "paper_2602_22700_amd", "csrc")
+    exe = str(tmp_path / "host_san")
+    cmd = [cxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-static-libasan", "-o", exe, os.path.join(ROOT, "tests", "host_sanitize_main.cpp")] + \
+          [os.path.join(csrc, f) for f in ("sha256.cpp", "transcript.cpp", "commit.cpp", "verify.cpp")] + ["-lpthread"]
+    subprocess.check_call(cmd)
+    rej_state = rejecting_state()[0]
+    for (m, d, n), state in (((4, 4, 4), ref.FS_INIT), ((3, 9, 5), rej_state), ((1, 1, 1), ref.FS_INIT),
+                             ((2, (1 << 20) + 5, 3), ref.FS_INIT)):
+        rng = np.random.default_rng(m * 100 + n)
+        A = rng.integers(-2**15, 2**15, size=(m, d), dtype=np.int16)
+        B = rng.integers(-128, 128, size=(d, n), dtype=np.int8)
+        C = oracle_fast.matmul(A, B)
+        dg = oracle_fast.commit_matmul(A, B, C)
+        trace = {}
+        proof, s_out = oracle_fast.prove(A, B, C, dg, state, trace=trace)
+        text = "%d %d %d\n" % (m, d, n) + " ".join(map(str, A.reshape(-1).tolist())) + "\n" + \
+            " ".join(map(str, B.reshape(-1).tolist())) + "\n" + " ".join(map(str, C.reshape(-1).tolist())) + "\n" + \
+            state.hex() + "\n" + "%d %d %d %d %d %d\n" % (proof["mu"], proof["delta"], proof["nu"], proof["c0"],
+                                                           proof["vA"], proof["vB"]) + " ".join(map(str, proof["g"])) + "\n"
+        env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+        run = subprocess.run([exe], input=text, capture_output=True, text=True, env=env, timeout=300)
+        assert run.returncode == 0 and run.stderr == "", run.stderr[-2000:]
+        out = run.stdout.split("\n")
+        tr = ref.Transcript(state)
+        want_ch = tr.challenge()
+        assert out[0] == "commit 0" and out[1:4] == [x.hex() for x in dg]
+        assert out[4] == "verify_full 0 0" and out[5] == s_out.hex()
+        assert out[6] == "verify_transcript %d 0" % imm.IMM_REJ_UNOPENED and out[7] == s_out.hex()
+        assert out[8] == " ".join(["points", "0"] + [str(v) for v in trace["rx"] + trace["ry"] + trace["r"]])
+        assert out[9] == "challenge 0 %d" % want_ch and out[10] == tr.s.hex()
+        assert out[11] == "verify_bad_C %d" % 6
