@@ -23,6 +23,7 @@ IMM_OPT_REPLY_IN_DEVICE_MEMORY = 6
 IMM_OPT_FUSE_REDUCTIONS = 7
 IMM_OPT_ENCODE_AHEAD = 8
 IMM_OPT_TIMELINE = 9
+IMM_OPT_HOST_TAIL = 10
 TIMELINE_NAMES = ["entry", "head_hashed", "front_launched", "reductions_launched", "rounds_launched", "first_message",
                   "first_challenge", "last_challenge", "final_values", "exit"]
 IMM_TRANSCRIPT_DEVICE, IMM_TRANSCRIPT_HOST = 0, 1

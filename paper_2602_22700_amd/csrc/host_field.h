@@ -40,6 +40,23 @@ inline uint64_t interpolate3(uint64_t g0, uint64_t g1, uint64_t g2, uint64_t r) 
     return add(add(mul(g0, l0), mul(g1, l1)), mul(g2, l2));
 }
 
+// g(0), g(1), g(2) of the round polynomial of two tables of length L >= 2 (leading variable = upper half)
+inline void round_evals(const uint64_t* a, const uint64_t* b, uint64_t L, uint64_t g[3]) {
+    const uint64_t h = L >> 1;
+    g[0] = g[1] = g[2] = 0;
+    for (uint64_t i = 0; i < h; ++i) {
+        const uint64_t a2 = sub(add(a[i + h], a[i + h]), a[i]), b2 = sub(add(b[i + h], b[i + h]), b[i]);
+        g[0] = add(g[0], mul(a[i], b[i]));
+        g[1] = add(g[1], mul(a[i + h], b[i + h]));
+        g[2] = add(g[2], mul(a2, b2));
+    }
+}
+// bind the leading variable of a table of length L to r, in place: x[i] <- x[i] + r (x[i + L/2] - x[i])
+inline void fold(uint64_t* x, uint64_t L, uint64_t r) {
+    const uint64_t h = L >> 1;
+    for (uint64_t i = 0; i < h; ++i) x[i] = add(x[i], mul(r, sub(x[i + h], x[i])));
+}
+
 inline int ceil_log2(uint64_t n) {
     int t = 0;
     while (t < 64 && (1ull << t) < n) ++t;

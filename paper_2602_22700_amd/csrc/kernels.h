@@ -112,10 +112,12 @@ hipError_t challenge_once(hipStream_t stream, const uint32_t state_in[8], uint64
 constexpr uint64_t kMailEmpty = 0xFFFFFFFFFFFFFFFFull;  // not a canonical field element
 constexpr uint64_t kMailAbort = 0xFFFFFFFFFFFFFFFEull;  // host -> device: stop waiting
 constexpr uint64_t kMailFail = 0xFFFFFFFFFFFFFFFDull;   // device -> host, in place of g_1: the tables are not canonical
+constexpr int kTailMaxLog2 = 8;  // longest tables (2^8 entries) that the device hands to the host to finish
 struct Mailbox {
     uint64_t g[IMM_MAX_ROUNDS][4];  // device -> host: g_k(0), g_k(1), g_k(2), unused
     uint64_t r[IMM_MAX_ROUNDS];     // host -> device: r_k
     uint64_t fin[4];                // device -> host: a[0], b[0] after the last fold
+    uint64_t tail[2][1 << kTailMaxLog2];  // device -> host: the tables a, b once they are short (see RoundsJob)
 };
 
 // The same rounds as rounds(), for up to kRoundsMaxJobs independent proofs in one launch (one
@@ -132,7 +134,12 @@ struct RoundsJob {
     uint64_t* b;
     uint64_t L;
     int rounds;
-    int _pad;
+    // 0: the kernel runs all rounds and posts fin[].  t > 0 (at most kTailMaxLog2, at most rounds - 2): it
+    // runs the first rounds - t of them; having bound r_(rounds - t) it has already posted the message of
+    // the round after, as always, and now posts the tables, 2^t entries each, into tail[][] and ends: the
+    // last t rounds work on tables so short that the host computes them faster than a message goes there
+    // and back.
+    int tail_rounds;
 };
 struct RoundsJobs {
     RoundsJob job[kRoundsMaxJobs];

@@ -1385,7 +1385,7 @@ __device__ __forceinline__ void quad_block_sum(const Quad3& qd, uint32_t active_
 // 64 products by shuffles, and lane 0 adds the sum to the wave's slot of that kind; nine threads
 // add the slots up.  The tables never leave LDS; a[0], b[0] go out through the mailbox.
 __device__ __forceinline__ void rounds_in_lds(const uint64_t* ga, const uint64_t* gb, uint64_t L0, int first, int rounds,
-                                              uint64_t fold_r,
+                                              int tail_rounds, uint64_t fold_r,
                                               Mailbox* mb, const uint64_t* reply, uint64_t spin_limit, uint64_t* status,
                                               uint64_t (*near)[kRoundsLdsTable], uint64_t (*part)[kRoundsWaves],
                                               uint64_t (*red)[kRoundsBlock], uint64_t* fin9, uint64_t (*lds3)[3],
@@ -1505,7 +1505,8 @@ __device__ __forceinline__ void rounds_in_lds(const uint64_t* ga, const uint64_t
     if (L > kRoundsTaskMax) prepare_by_groups(L, false, 0);
     else if (L >= 4) prepare(L);
 
-    for (int kk = first; kk < rounds; ++kk) {
+    const int dev_rounds = rounds - tail_rounds;  // the rounds whose challenge this kernel binds
+    for (int kk = first; kk < dev_rounds; ++kk) {
         const uint32_t h = L >> 1;
         // Wave 0: lane 0 waits for r_{kk+1}; lanes 0..2 then evaluate one value each of g_{kk+2} and
         // post it to the host before the tables are touched.
@@ -1543,7 +1544,12 @@ __device__ __forceinline__ void rounds_in_lds(const uint64_t* ga, const uint64_t
         }
         __syncthreads();
         L = h;
-        if (L >= 4) prepare(L);
+        if (L >= 4 && kk + 1 < dev_rounds) prepare(L);
+    }
+    if (tail_rounds) {  // the host finishes: it gets the tables as they are now, 2^tail_rounds entries each
+        if (tid < 2 * L) mail_post(&mb->tail[tid >= L ? 1 : 0][tid >= L ? tid - L : tid], near[tid >= L ? 1 : 0][tid >= L ? tid - L : tid]);
+        if (tid == 0) status[0] = 0;
+        return;
     }
     if (tid == 0) {
         mail_post(&mb->fin[0], near[0][0]);
@@ -1561,6 +1567,7 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs
     uint64_t* b = jobs.job[blockIdx.x].b;
     uint64_t L = jobs.job[blockIdx.x].L;
     const int rounds = jobs.job[blockIdx.x].rounds;
+    const int tail_rounds = jobs.job[blockIdx.x].tail_rounds;
     Mailbox* mb = mailboxes + blockIdx.x;
     const uint64_t* reply = replies ? replies + (uint64_t)blockIdx.x * IMM_MAX_ROUNDS : mb->r;
     uint64_t* status = status_all + blockIdx.x;
@@ -1573,7 +1580,7 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs
     const uint32_t tid = threadIdx.x;
 
     if (L <= kRoundsLdsTable) {  // the usual case: tables of at most 4096 entries
-        rounds_in_lds(a, b, L, 0, rounds, 0, mb, reply, spin_limit, status, near, part, red, fin9, lds3, &r_shared);
+        rounds_in_lds(a, b, L, 0, rounds, tail_rounds, 0, mb, reply, spin_limit, status, near, part, red, fin9, lds3, &r_shared);
         return;
     }
 
@@ -1652,8 +1659,8 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs
             return;
         }
         if (h <= kRoundsLdsTable) {  // from here on the tables fit into LDS: the other loop takes over
-            rounds_in_lds(a, b, h, kk + 1, rounds, r, mb, reply, spin_limit, status, near, part, red, fin9, lds3,
-                          &r_shared);
+            rounds_in_lds(a, b, h, kk + 1, rounds, tail_rounds, r, mb, reply, spin_limit, status, near, part, red, fin9,
+                          lds3, &r_shared);
             return;
         }
         // Bind the leading variable, x[j] <- x[j] + r (x[j + h] - x[j]), in place.  If another round with

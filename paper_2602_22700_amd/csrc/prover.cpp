@@ -194,6 +194,7 @@ struct imm_ctx {
     int transcript_mode = IMM_TRANSCRIPT_HOST;
     uint64_t spin_limit = 1ull << 21;    // device polls per round before giving up (about 2 us each)
     int64_t host_wait_ms = 30000;        // host patience per mailbox slot
+    int host_tail = 6;                   // IMM_OPT_HOST_TAIL: the host computes the rounds on tables of at most 2^6 entries
     imm::Profiler prof;
     bool debug = false;
     bool widen = true;
@@ -654,6 +655,9 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
         rj.job[p].b = jobs[p]->b;
         rj.job[p].L = jobs[p]->L;
         rj.job[p].rounds = jobs[p]->delta - jobs[p]->kk;
+        // The last rounds, on tables of at most 2^host_tail entries, are the host's: it computes them in
+        // less time than one message takes to the device and back (the kernel needs two rounds of its own).
+        rj.job[p].tail_rounds = rj.job[p].rounds >= ctx->host_tail + 2 ? ctx->host_tail : 0;
         if (rj.job[p].rounds > max_rounds) max_rounds = rj.job[p].rounds;
     }
     if (replies) {  // ahead of the launch on the same path to the device, so the kernel finds them empty
@@ -668,15 +672,29 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
     IMM_HIP(k::rounds_mailbox(s, rj, count, mb, replies, ctx->spin_limit, status_dev));
     if ((rc = ctx->prof.end(IMM_K_ROUND, s))) return rc;
     ctx->mark(IMM_T_ROUNDS_LAUNCHED);
-    bool ok = true;
+    bool ok = true, bad_tables = false;
+    // tables of the proofs whose last rounds the host computes (filled when the device hands them over)
+    std::vector<uint64_t> tail((size_t)count * 2 << k::kTailMaxLog2);
     for (int slot = 0; slot < max_rounds && ok; ++slot) {
         for (int p = 0; p < count && ok; ++p) {
             Job& job = *jobs[p];
             if (slot >= rj.job[p].rounds) continue;
             const int kk = job.kk + slot;
+            const int dev_rounds = rj.job[p].rounds - rj.job[p].tail_rounds;  // challenges that the kernel binds
+            uint64_t* ta = tail.data() + ((size_t)p * 2 << k::kTailMaxLog2);
+            uint64_t* tb = ta + (size_t(1) << k::kTailMaxLog2);
             uint64_t g[3];
-            for (int t = 0; t < 3 && ok; ++t) ok = mail_wait(&mb[p].g[slot][t], ctx->host_wait_ms, &g[t]);
-            if (!ok) break;
+            if (!rj.job[p].tail_rounds || slot <= dev_rounds) {  // the kernel's messages: one more than it binds challenges
+                for (int t = 0; t < 3 && ok; ++t) ok = mail_wait(&mb[p].g[slot][t], ctx->host_wait_ms, &g[t]);
+                if (!ok) break;
+                if (g[0] >= hf::P || g[1] >= hf::P || g[2] >= hf::P) {  // k::kMailFail: the tables were not canonical
+                    ok = false;
+                    bad_tables = true;
+                    break;
+                }
+            } else {
+                hf::round_evals(ta, tb, 1ull << (rj.job[p].rounds - slot), g);
+            }
             if (slot == 0 && p == 0) ctx->mark(IMM_T_FIRST_MESSAGE);
             if (!job.claim_absorbed) {
                 job.out->c0 = hf::add(g[0], g[1]);
@@ -688,18 +706,34 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
             job.out->g[3 * kk + 2] = g[2];
             job.tr.absorb_words("rnd ", g, 3);
             job.rr[kk] = job.tr.challenge();
-            if (replies)
-                reply_store(replies + (size_t)p * IMM_MAX_ROUNDS + slot, job.rr[kk]);
-            else
-                __atomic_store_n(&mb[p].r[slot], job.rr[kk], __ATOMIC_RELEASE);
+            if (!rj.job[p].tail_rounds || slot < dev_rounds) {
+                if (replies)
+                    reply_store(replies + (size_t)p * IMM_MAX_ROUNDS + slot, job.rr[kk]);
+                else
+                    __atomic_store_n(&mb[p].r[slot], job.rr[kk], __ATOMIC_RELEASE);
+            } else {
+                const uint64_t len = 1ull << (rj.job[p].rounds - slot);  // table length before this round's fold
+                if (slot == dev_rounds)  // the kernel has bound its last challenge: its tables are on their way
+                    for (uint64_t i = 0; i < len && ok; ++i)
+                        ok = mail_wait(&mb[p].tail[0][i], ctx->host_wait_ms, &ta[i]) &&
+                             mail_wait(&mb[p].tail[1][i], ctx->host_wait_ms, &tb[i]);
+                if (!ok) break;
+                hf::fold(ta, len, job.rr[kk]);
+                hf::fold(tb, len, job.rr[kk]);
+            }
             if (p == 0 && (slot == 0 || slot == rj.job[0].rounds - 1))
                 ctx->mark(slot == 0 ? IMM_T_FIRST_CHALLENGE : IMM_T_LAST_CHALLENGE);
         }
     }
     for (int p = 0; p < count && ok; ++p) {
         uint64_t fin[2] = {0, 0};
-        ok = mail_wait(&mb[p].fin[0], ctx->host_wait_ms, &fin[0]) && mail_wait(&mb[p].fin[1], ctx->host_wait_ms, &fin[1]);
-        if (!ok) break;
+        if (rj.job[p].tail_rounds) {
+            fin[0] = tail[(size_t)p * 2 << k::kTailMaxLog2];
+            fin[1] = tail[((size_t)p * 2 + 1) << k::kTailMaxLog2];
+        } else {
+            ok = mail_wait(&mb[p].fin[0], ctx->host_wait_ms, &fin[0]) && mail_wait(&mb[p].fin[1], ctx->host_wait_ms, &fin[1]);
+            if (!ok) break;
+        }
         jobs[p]->out->vA = fin[0];
         jobs[p]->out->vB = fin[1];
         jobs[p]->tr.absorb_words("fin ", fin, 2);
@@ -713,7 +747,8 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
                 if (replies) reply_store(replies + (size_t)p * IMM_MAX_ROUNDS + t, k::kMailAbort);
             }
         IMM_HIP(hipStreamSynchronize(s));
-        g_last_error = "round kernel and host transcript lost contact (mailbox wait ran out)";
+        g_last_error = bad_tables ? "the reductions did not deliver canonical field elements (a hand-over between workgroups ran out)"
+                                  : "round kernel and host transcript lost contact (mailbox wait ran out)";
         return IMM_E_HIP;
     }
     // No stream synchronisation here: posting fin[] is a workgroup's last access to its mailbox
@@ -951,6 +986,10 @@ extern "C" int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value) {
     case IMM_OPT_FUSE_REDUCTIONS: ctx->fuse_reductions = value != 0; return IMM_OK;
     case IMM_OPT_ENCODE_AHEAD: ctx->encode_ahead = value != 0; return IMM_OK;
     case IMM_OPT_TIMELINE: ctx->timeline = value != 0; ctx->marks = 0; return IMM_OK;
+    case IMM_OPT_HOST_TAIL:
+        if (value < 0 || value > k::kTailMaxLog2) return IMM_E_SHAPE;
+        ctx->host_tail = (int)value;
+        return IMM_OK;
     case IMM_OPT_REPLY_IN_DEVICE_MEMORY: ctx->reply_in_device_memory = value != 0; return IMM_OK;
     case IMM_OPT_TRANSCRIPT:
         if (value != IMM_TRANSCRIPT_DEVICE && value != IMM_TRANSCRIPT_HOST) return IMM_E_SHAPE;
