@@ -267,6 +267,12 @@ def main():
         narrow_proofs = batch.proofs
         ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
 
+    # the same step with every round of the sumcheck on the device (by default the host finishes the rounds on
+    # tables of at most 512 entries, which it computes in less time than a message to the device and back takes)
+    ctx.imm_ctx_set_option(imm.IMM_OPT_HOST_TAIL, 0)
+    ms_all_rounds_on_device = timed_runs(torch, batch, args.steps, 2)
+    ctx.imm_ctx_set_option(imm.IMM_OPT_HOST_TAIL, imm.IMM_HOST_TAIL_DEFAULT)
+
     result = {
         "metric": "matmul_sumcheck_prove_time_per_layer", "value": round(ms_per_step, 4), "unit": "ms",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -284,6 +290,7 @@ def main():
                                 else "encode A+B, eq, reduce A+B, rounds, hashing")},
         "prove_ms_weights_preencoded": round(ms_pre, 4),
         "prove_ms_narrow_read": round(ms_narrow, 4) if ms_narrow is not None else None,
+        "prove_ms_every_round_on_the_device": round(ms_all_rounds_on_device, 4),
         "kernels": kernels,
         "roofline": {"bound": "hbm",
                      "kernel": ("reduce_A+B (partial MLEs of A over its rows and of B over its columns, one launch)" if fused

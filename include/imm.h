@@ -342,13 +342,16 @@ int imm_debug_device_challenge(imm_ctx* ctx, void* stream, uint8_t state[32], ui
 #define IMM_OPT_TIMELINE 9        /* value != 0: the host notes the time (CLOCK_MONOTONIC, ns) at which a proof
                                      passes the points IMM_T_* below; imm_debug_timeline returns the notes of
                                      the most recent proof (default 0) */
-#define IMM_OPT_HOST_TAIL 10      /* host-transcript mode: t = value (0..8, default 6).  The round kernel runs the
-                                     rounds on tables longer than 2^t entries; once a fold leaves 2^t entries it
-                                     hands the two tables to the host (2^(t+4) bytes through the mailbox), which
-                                     computes the last t rounds itself between its hashes: on tables that short a
-                                     round is a few dozen multiplications, less than the time one message takes to
-                                     the device and back.  Same proof bytes for every value; 0: the kernel runs
-                                     every round.  Statements with fewer than t + 2 rounds left are not split */
+#define IMM_OPT_HOST_TAIL 10      /* host-transcript mode: t = value (0..IMM_HOST_TAIL_MAX, default
+                                     IMM_HOST_TAIL_DEFAULT).  The round kernel runs the rounds on tables longer than
+                                     2^t entries; once a fold leaves 2^t entries it hands the two tables to the host
+                                     (2^(t+4) bytes through the mailbox) and ends, and the host, which hashes every
+                                     round's message anyway, computes the last t rounds itself: on tables that short
+                                     a round's arithmetic takes less time than one message to the device and back.
+                                     Same proof bytes for every value; 0: the kernel runs every round.  Statements
+                                     with fewer than t + 2 rounds are not split.  IMM_E_SHAPE outside the range */
+#define IMM_HOST_TAIL_DEFAULT 9
+#define IMM_HOST_TAIL_MAX 10
 int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value);
 
 /* Points of a proof on the host's side (IMM_OPT_TIMELINE). */

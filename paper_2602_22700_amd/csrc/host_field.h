@@ -40,16 +40,32 @@ inline uint64_t interpolate3(uint64_t g0, uint64_t g1, uint64_t g2, uint64_t r) 
     return add(add(mul(g0, l0), mul(g1, l1)), mul(g2, l2));
 }
 
+// Sum of products of canonical residues, reduced once at the end: 128 bits plus a count of the
+// carries out of them, each worth 2^128 = -2^32 (mod p).  Up to 2^32 - 1 products.
+struct ProductSum {
+    unsigned __int128 s = 0;
+    uint64_t carries = 0;
+    void add(uint64_t a, uint64_t b) {
+        const unsigned __int128 p = (unsigned __int128)a * b;
+        s += p;
+        carries += s < p;
+    }
+    uint64_t value() const { return sub(reduce128(s), carries << 32); }
+};
+
 // g(0), g(1), g(2) of the round polynomial of two tables of length L >= 2 (leading variable = upper half)
 inline void round_evals(const uint64_t* a, const uint64_t* b, uint64_t L, uint64_t g[3]) {
     const uint64_t h = L >> 1;
-    g[0] = g[1] = g[2] = 0;
+    ProductSum g0, g1, g2;
     for (uint64_t i = 0; i < h; ++i) {
         const uint64_t a2 = sub(add(a[i + h], a[i + h]), a[i]), b2 = sub(add(b[i + h], b[i + h]), b[i]);
-        g[0] = add(g[0], mul(a[i], b[i]));
-        g[1] = add(g[1], mul(a[i + h], b[i + h]));
-        g[2] = add(g[2], mul(a2, b2));
+        g0.add(a[i], b[i]);
+        g1.add(a[i + h], b[i + h]);
+        g2.add(a2, b2);
     }
+    g[0] = g0.value();
+    g[1] = g1.value();
+    g[2] = g2.value();
 }
 // bind the leading variable of a table of length L to r, in place: x[i] <- x[i] + r (x[i + L/2] - x[i])
 inline void fold(uint64_t* x, uint64_t L, uint64_t r) {

@@ -112,7 +112,7 @@ hipError_t challenge_once(hipStream_t stream, const uint32_t state_in[8], uint64
 constexpr uint64_t kMailEmpty = 0xFFFFFFFFFFFFFFFFull;  // not a canonical field element
 constexpr uint64_t kMailAbort = 0xFFFFFFFFFFFFFFFEull;  // host -> device: stop waiting
 constexpr uint64_t kMailFail = 0xFFFFFFFFFFFFFFFDull;   // device -> host, in place of g_1: the tables are not canonical
-constexpr int kTailMaxLog2 = 8;  // longest tables (2^8 entries) that the device hands to the host to finish
+constexpr int kTailMaxLog2 = IMM_HOST_TAIL_MAX;  // longest tables (2^10 entries) that the device hands to the host to finish
 struct Mailbox {
     uint64_t g[IMM_MAX_ROUNDS][4];  // device -> host: g_k(0), g_k(1), g_k(2), unused
     uint64_t r[IMM_MAX_ROUNDS];     // host -> device: r_k

@@ -1547,7 +1547,7 @@ __device__ __forceinline__ void rounds_in_lds(const uint64_t* ga, const uint64_t
         if (L >= 4 && kk + 1 < dev_rounds) prepare(L);
     }
     if (tail_rounds) {  // the host finishes: it gets the tables as they are now, 2^tail_rounds entries each
-        if (tid < 2 * L) mail_post(&mb->tail[tid >= L ? 1 : 0][tid >= L ? tid - L : tid], near[tid >= L ? 1 : 0][tid >= L ? tid - L : tid]);
+        for (uint32_t i = tid; i < 2 * L; i += kRoundsBlock) mail_post(&mb->tail[i >= L ? 1 : 0][i >= L ? i - L : i], near[i >= L ? 1 : 0][i >= L ? i - L : i]);
         if (tid == 0) status[0] = 0;
         return;
     }

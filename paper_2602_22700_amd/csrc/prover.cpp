@@ -11,6 +11,7 @@
 #include <atomic>
 #include <chrono>
 #include <cstdio>
+#include <cstddef>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -194,7 +195,7 @@ struct imm_ctx {
     int transcript_mode = IMM_TRANSCRIPT_HOST;
     uint64_t spin_limit = 1ull << 21;    // device polls per round before giving up (about 2 us each)
     int64_t host_wait_ms = 30000;        // host patience per mailbox slot
-    int host_tail = 6;                   // IMM_OPT_HOST_TAIL: the host computes the rounds on tables of at most 2^6 entries
+    int host_tail = IMM_HOST_TAIL_DEFAULT;  // IMM_OPT_HOST_TAIL: the host computes the rounds on tables of at most 2^9 entries
     imm::Profiler prof;
     bool debug = false;
     bool widen = true;
@@ -336,7 +337,7 @@ static int run_round(imm_ctx* ctx, hipStream_t s, uint64_t* a, uint64_t* b, uint
 // Wait until a mailbox slot written by the device leaves the empty state.
 static bool mail_wait(const uint64_t* slot, int64_t patience_ms, uint64_t* value) {
     const volatile uint64_t* p = slot;
-    auto t0 = std::chrono::steady_clock::now();
+    std::chrono::steady_clock::time_point t0;
     for (uint64_t spin = 0;; ++spin) {
         uint64_t v = *p;
         if (v != k::kMailEmpty) {
@@ -344,6 +345,7 @@ static bool mail_wait(const uint64_t* slot, int64_t patience_ms, uint64_t* value
             *value = v;
             return true;
         }
+        if (spin == 0) t0 = std::chrono::steady_clock::now();  // a word that is there already costs no look at the clock
         if ((spin & 0xFFF) == 0xFFF) {
             auto dt = std::chrono::steady_clock::now() - t0;
             if (std::chrono::duration_cast<std::chrono::milliseconds>(dt).count() > patience_ms) return false;
@@ -645,8 +647,6 @@ static int long_table_prefix(imm_ctx* ctx, hipStream_t s, Job& job) {
 // absorbs it, squeezes r_k and posts it back; independent proofs overlap their waits.
 static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, int count) {
     k::Mailbox* mb = ctx->mailbox;
-    std::memset(mb, 0xFF, sizeof(k::Mailbox) * (size_t)count);
-    std::atomic_thread_fence(std::memory_order_seq_cst);
     uint64_t* replies = ctx->reply_in_device_memory ? ctx->replies : nullptr;
     k::RoundsJobs rj{};
     int max_rounds = 0;
@@ -659,7 +659,11 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
         // less time than one message takes to the device and back (the kernel needs two rounds of its own).
         rj.job[p].tail_rounds = rj.job[p].rounds >= ctx->host_tail + 2 ? ctx->host_tail : 0;
         if (rj.job[p].rounds > max_rounds) max_rounds = rj.job[p].rounds;
+        // every slot that the kernel will write starts out empty
+        std::memset(&mb[p], 0xFF, offsetof(k::Mailbox, tail));
+        for (int t = 0; t < 2 && rj.job[p].tail_rounds; ++t) std::memset(mb[p].tail[t], 0xFF, sizeof(uint64_t) << rj.job[p].tail_rounds);
     }
+    std::atomic_thread_fence(std::memory_order_seq_cst);
     if (replies) {  // ahead of the launch on the same path to the device, so the kernel finds them empty
         for (int p = 0; p < count; ++p)
             for (int t = 0; t < rj.job[p].rounds; ++t)

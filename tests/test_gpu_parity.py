@@ -194,12 +194,12 @@ def check_proof(torch, ctx, oracle_fast, A, B, C=None, state=ref.FS_INIT, interm
     assert got3.words() == got.words() and s3 == s_got
     # wherever the round kernel hands its tables to the host (never, after all but one round, late), the same bytes
     try:
-        for t in (0, 1, 3, 8):
+        for t in (0, 1, 3, 6, imm.IMM_HOST_TAIL_MAX):
             ctx.imm_ctx_set_option(imm.IMM_OPT_HOST_TAIL, t)
             got5, s5 = ctx.imm_sumcheck_matmul_prove(Af, Bf, com, state)
             assert got5.words() == got.words() and s5 == s_got, t
     finally:
-        ctx.imm_ctx_set_option(imm.IMM_OPT_HOST_TAIL, 6)
+        ctx.imm_ctx_set_option(imm.IMM_OPT_HOST_TAIL, imm.IMM_HOST_TAIL_DEFAULT)
     # the library's own verifier accepts it
     if verify_open:
         assert imm.imm_verify(com, state, got, A, B, C) == (0, s_want, 0)
@@ -339,7 +339,7 @@ def other_modes(ctx, items, chained, state):
     finally:
         ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
         ctx.imm_ctx_set_option(imm.IMM_OPT_TRANSCRIPT, imm.IMM_TRANSCRIPT_HOST)
-        ctx.imm_ctx_set_option(imm.IMM_OPT_HOST_TAIL, 6)
+        ctx.imm_ctx_set_option(imm.IMM_OPT_HOST_TAIL, imm.IMM_HOST_TAIL_DEFAULT)
 
 
 @pytest.mark.timeout(1200)
@@ -577,8 +577,9 @@ def test_argument_errors(torch, ctx):
     g = (ctypes.c_uint64 * 3)()
     assert L.imm_round_fold_eval(h, None, A.data_ptr(), B.data_ptr(), 3, None, g) == -2
     assert L.imm_encode(h, None, A.data_ptr(), 4, 4, A.data_ptr()) == -3
-    assert L.imm_ctx_set_option(h, imm.IMM_OPT_HOST_TAIL, 9) == -2 and L.imm_ctx_set_option(h, imm.IMM_OPT_HOST_TAIL, -1) == -2
-    assert L.imm_ctx_set_option(h, imm.IMM_OPT_HOST_TAIL, 6) == 0
+    assert L.imm_ctx_set_option(h, imm.IMM_OPT_HOST_TAIL, imm.IMM_HOST_TAIL_MAX + 1) == -2
+    assert L.imm_ctx_set_option(h, imm.IMM_OPT_HOST_TAIL, -1) == -2
+    assert L.imm_ctx_set_option(h, imm.IMM_OPT_HOST_TAIL, imm.IMM_HOST_TAIL_DEFAULT) == 0
     bad = ctypes.c_void_p()
     assert L.imm_ctx_create(ctypes.byref(bad), 99, 0) == -5
     assert b"device" in L.imm_last_error()

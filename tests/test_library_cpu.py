@@ -322,3 +322,43 @@ def test_host_sources_under_address_and_undefined_behaviour_sanitizers(oracle_fa
         assert out[8] == " ".join(["points", "0"] + [str(v) for v in trace["rx"] + trace["ry"] + trace["r"]])
         assert out[9] == "challenge 0 %d" % want_ch and out[10] == tr.s.hex()
         assert out[11] == "verify_bad_C %d" % 6
+
+
+def test_host_side_rounds_match_the_oracle(oracle_fast, tmp_path):
+    """The rounds that the prover's host thread computes on short tables (sums of 128-bit products
+    reduced once, fold in place), compiled on their own with the sanitizers: g(0), g(1), g(2) and the
+    folded tables equal the oracle's on random tables, on tables of p - 1 throughout (the largest
+    products and the most carries) and on the shortest table."""
+    import shutil
+    import subprocess
+    cxx = shutil.which("g++")
+    if cxx is None:
+        pytest.skip("no host compiler")
+    exe = str(tmp_path / "host_rounds")
+    subprocess.check_call([cxx, "-std=c++17", "-O2", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                           "-static-libasan", "-o", exe, os.path.join(ROOT, "tests", "host_rounds_main.cpp")])
+    rng = np.random.default_rng(77)
+    P = ref.P
+    cases = []
+    for L in (2, 4, 64, 1024):
+        cases.append((rng.integers(0, P, size=L, dtype=np.uint64), rng.integers(0, P, size=L, dtype=np.uint64),
+                      int(rng.integers(0, P, dtype=np.uint64))))
+    cases.append((np.full(1024, P - 1, dtype=np.uint64), np.full(1024, P - 1, dtype=np.uint64), P - 1))
+    cases.append((np.full(8, P - 1, dtype=np.uint64), np.zeros(8, dtype=np.uint64), 0))
+    for a, b, r in cases:
+        L = len(a)
+        text = "%d\n%s\n%s\n%d\n" % (L, " ".join(map(str, a.tolist())), " ".join(map(str, b.tolist())), r)
+        run = subprocess.run([exe], input=text, capture_output=True, text=True, timeout=60)
+        assert run.returncode == 0 and run.stderr == "", run.stderr[-2000:]
+        lines = run.stdout.strip().split("\n")
+        h = L // 2
+        # the definition, in Python integers
+        g0 = sum(int(a[i]) * int(b[i]) for i in range(h)) % P
+        g1 = sum(int(a[i + h]) * int(b[i + h]) for i in range(h)) % P
+        g2 = sum((2 * int(a[i + h]) - int(a[i])) * (2 * int(b[i + h]) - int(b[i])) for i in range(h)) % P
+        assert [int(v) for v in lines[0].split()] == [g0, g1, g2] == oracle_fast.round_evals(a.copy(), b.copy(), L)
+        fa, fb = a.copy(), b.copy()
+        oracle_fast.fold(fa, L, r)
+        oracle_fast.fold(fb, L, r)
+        assert [int(v) for v in lines[1].split()] == fa[:h].tolist()
+        assert [int(v) for v in lines[2].split()] == fb[:h].tolist()
