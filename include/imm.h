@@ -349,7 +349,9 @@ int imm_debug_device_challenge(imm_ctx* ctx, void* stream, uint8_t state[32], ui
                                      round's message anyway, computes the last t rounds itself: on tables that short
                                      a round's arithmetic takes less time than one message to the device and back.
                                      Same proof bytes for every value; 0: the kernel runs every round.  Statements
-                                     with fewer than t + 2 rounds are not split.  IMM_E_SHAPE outside the range */
+                                     with fewer than t + 2 rounds are not split, and where k independent proofs share
+                                     a launch (their workgroups side by side, one host thread serving them in turn) t
+                                     is lowered by ceil(log2 k).  IMM_E_SHAPE outside the range */
 #define IMM_HOST_TAIL_DEFAULT 9
 #define IMM_HOST_TAIL_MAX 10
 int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value);

@@ -657,7 +657,10 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
         rj.job[p].rounds = jobs[p]->delta - jobs[p]->kk;
         // The last rounds, on tables of at most 2^host_tail entries, are the host's: it computes them in
         // less time than one message takes to the device and back (the kernel needs two rounds of its own).
-        rj.job[p].tail_rounds = rj.job[p].rounds >= ctx->host_tail + 2 ? ctx->host_tail : 0;
+        // One host thread serves the proofs of a launch in turn while their workgroups work side by side,
+        // so with `count` proofs the host's rounds must be that much shorter to beat the device's.
+        const int tail = std::max(0, ctx->host_tail - hf::ceil_log2((uint64_t)count));
+        rj.job[p].tail_rounds = rj.job[p].rounds >= tail + 2 ? tail : 0;
         if (rj.job[p].rounds > max_rounds) max_rounds = rj.job[p].rounds;
         // every slot that the kernel will write starts out empty
         std::memset(&mb[p], 0xFF, offsetof(k::Mailbox, tail));
