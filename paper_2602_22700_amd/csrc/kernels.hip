@@ -324,32 +324,72 @@ __device__ __forceinline__ void combine_block(const uint64_t* __restrict__ parti
 // ------------------------------------------------------------------ reduction over the columns (row-wise)
 // Block = R consecutive rows x one column split.  A lane owns the column pairs
 // (2*tid, 2*tid+1) + 512*u of the split, so one wave load covers 1 KiB of a row and the
-// eq pair is loaded once and reused for the R rows.  In the full-tile path all R*U
-// 16-byte loads of a trip are issued before the first multiply, which is what keeps
-// enough bytes in flight per CU to stream at HBM rate.
+// eq pair is loaded once and reused for the R rows (one row per block costs a tenth of the
+// rate: the eq pairs come from L2 but take the same path into the CU as the table).  In the
+// full-tile path all R*U 16-byte loads of a trip are issued before the first multiply of the
+// trip before it, which is what keeps enough bytes in flight per CU to stream at HBM rate.
+// One trip's requests of a lane: U eq pairs and R x U pairs of table entries.
+template <typename S, int R, int U>
+struct ColsTrip {
+    ulonglong2 e[U];
+    typename RawPair<S>::type x[U][R];
+};
+template <typename S, int R, int U>
+__device__ __forceinline__ void cols_trip_load(ColsTrip<S, R, U>& t, const S* __restrict__ base, uint64_t ld,
+                                               const uint64_t* __restrict__ eqb, uint64_t p) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) t.e[u] = *reinterpret_cast<const ulonglong2*>(eqb + 2 * (p + u * kBlock));
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int r = 0; r < R; ++r) t.x[u][r] = load_pair<S>(base + r * ld + 2 * (p + u * kBlock));
+}
+template <typename S, int R, int U>
+__device__ __forceinline__ void cols_trip_accumulate(const ColsTrip<S, R, U>& t, gl::Acc (&acc)[R]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            uint64_t f0, f1;
+            unpack<S>(t.x[u][r], f0, f1);
+            gl::acc_mac(acc[r], f0, t.e[u].x);
+            gl::acc_mac(acc[r], f1, t.e[u].y);
+        }
+}
 template <typename S, int R, int U>
 __device__ __forceinline__ void cols_full_tile(const S* __restrict__ base, uint64_t ld, const uint64_t* __restrict__ eqb,
                                                uint64_t npairs, gl::Acc (&acc)[R]) {
     using Raw = typename RawPair<S>::type;
     uint64_t p = threadIdx.x;
-    for (; p + (U - 1) * kBlock < npairs; p += U * kBlock) {
-        ulonglong2 e[U];
-        Raw x[U][R];
-#pragma unroll
-        for (int u = 0; u < U; ++u) e[u] = *reinterpret_cast<const ulonglong2*>(eqb + 2 * (p + u * kBlock));
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int r = 0; r < R; ++r) x[u][r] = load_pair<S>(base + r * ld + 2 * (p + u * kBlock));
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                uint64_t f0, f1;
-                unpack<S>(x[u][r], f0, f1);
-                gl::acc_mac(acc[r], f0, e[u].x);
-                gl::acc_mac(acc[r], f1, e[u].y);
-            }
+    // Whole trips (the same number for every lane), two sets of registers: the requests of the next
+    // trip go out before the current one is worked on, so a wave always has a trip's worth of loads
+    // in flight.  The loop has one path (no request behind a branch).
+    const uint64_t trips = npairs / (U * kBlock);
+    if (trips) {
+        constexpr uint64_t kStep = (uint64_t)U * kBlock;
+        uint64_t at = 0;  // the trip to ask for next
+        auto next_trip = [&]() { return p + (at++) * kStep; };
+        ColsTrip<S, R, U> ta, tb;
+        cols_trip_load(ta, base, ld, eqb, next_trip());
+        uint64_t t = 0;  // trips asked for so far, less one: ta holds the t-th
+        while (t + 2 < trips) {
+            cols_trip_load(tb, base, ld, eqb, next_trip());
+            loads_stay_above();
+            cols_trip_accumulate(ta, acc);
+            cols_trip_load(ta, base, ld, eqb, next_trip());
+            loads_stay_above();
+            cols_trip_accumulate(tb, acc);
+            t += 2;
+        }
+        if (t + 1 < trips) {
+            cols_trip_load(tb, base, ld, eqb, next_trip());
+            loads_stay_above();
+            cols_trip_accumulate(ta, acc);
+            cols_trip_accumulate(tb, acc);
+        } else {
+            cols_trip_accumulate(ta, acc);
+        }
+        p += trips * kStep;
     }
     for (; p < npairs; p += kBlock) {
         ulonglong2 e = *reinterpret_cast<const ulonglong2*>(eqb + 2 * p);
