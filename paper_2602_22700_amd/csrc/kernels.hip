@@ -526,12 +526,6 @@ constexpr uint64_t kI8MaxSplit = 1ull << 17;      // columns per split: a wave's
 
 typedef unsigned int v4u32 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ uint64_t wave_sum_plain(uint64_t v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-    return v;
-}
-
 // value = lo + hi * 2^32 as a canonical residue (any lo, hi)
 __device__ __forceinline__ uint64_t combine_limb_sums(uint64_t lo, uint64_t hi) {
     uint64_t low = lo + (hi << 32);
@@ -549,7 +543,7 @@ __device__ __forceinline__ uint64_t gather_planes(const uint32_t* p) {
 // of the vector ALU (shifts by 1, 2, 4, 8 lanes within each row of 16, then the last lane of a row
 // into the following row, then lane 31 into the upper half): no trip through the LDS crossbar, whose
 // latency a chain of shuffles pays at every step.
-__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+[[maybe_unused]] __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
     v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);   // row_shr:1
     v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);   // row_shr:2
     v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);   // row_shr:4
