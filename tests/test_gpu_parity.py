@@ -422,6 +422,31 @@ def test_independent_batch_larger_than_one_group(torch, ctx, oracle_fast):
     ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
 
 
+def test_batches_where_the_host_finishes_some_round_loops_and_not_others(torch, ctx, oracle_fast):
+    """Independent and chained proofs with 12, 10, 5 and 0 rounds in one batch: for each setting of the
+    table length from which the host finishes the rounds, some proofs are split and some are not (the
+    length is lowered for proofs that share a launch, and a proof needs two rounds beyond it)."""
+    rng = np.random.default_rng(321)
+    items, oracle_items = [], []
+    for (m, d, n) in ((3, 4096, 5), (2, 600, 9), (4, 20, 3), (2, 1, 2), (5, 2048, 4)):
+        A = rng.integers(-2**15, 2**15, size=(m, d), dtype=np.int16)
+        B = rng.integers(-128, 128, size=(d, n), dtype=np.int8)
+        C = oracle_fast.matmul(A, B)
+        com = imm.imm_commit_matmul(A, B, C, m, d, n)
+        oracle_items.append((A, B, C, com.digests()))
+        items.append((dev(torch, A), dev(torch, B), com))
+    try:
+        for chained in (False, True):
+            want, want_states = oracle_fast.prove_chain(oracle_items, chained=chained)
+            for t in (0, 2, 5, imm.IMM_HOST_TAIL_DEFAULT, imm.IMM_HOST_TAIL_MAX):
+                ctx.imm_ctx_set_option(imm.IMM_OPT_HOST_TAIL, t)
+                got, states, final = ctx.imm_sumcheck_matmul_prove_batch(items, chained, ref.FS_INIT)
+                assert [p.words() for p in got] == [ref.proof_words(p) for p in want], (chained, t)
+                assert states == want_states and final == want_states[-1], (chained, t)
+    finally:
+        ctx.imm_ctx_set_option(imm.IMM_OPT_HOST_TAIL, imm.IMM_HOST_TAIL_DEFAULT)
+
+
 def test_proofs_are_deterministic_and_survive_other_streams(torch, ctx, oracle_fast):
     A, B = workloads.tiny()
     C = oracle_fast.matmul(A, B)
