@@ -352,6 +352,12 @@ int imm_debug_device_challenge(imm_ctx* ctx, void* stream, uint8_t state[32], ui
                                      with fewer than t + 2 rounds are not split, and where k independent proofs share
                                      a launch (their workgroups side by side, one host thread serving them in turn) t
                                      is lowered by ceil(log2 k).  IMM_E_SHAPE outside the range */
+#define IMM_OPT_QUEUE_AHEAD 11    /* chained batches in host-transcript mode: 1 (default) = the kernels of proof p + 1
+                                     are queued while the host still serves the round loop of proof p; its eq kernel
+                                     waits on the device (bounded by IMM_OPT_SPIN_LIMIT) for the points, which the
+                                     host writes to it the moment proof p is finished.  0 = every proof is launched
+                                     after the one before it has returned.  Same proof bytes either way.  Not used
+                                     while debug snapshots, time marks or kernel profiling are on */
 #define IMM_HOST_TAIL_DEFAULT 9
 #define IMM_HOST_TAIL_MAX 10
 int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value);

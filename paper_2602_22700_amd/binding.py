@@ -24,6 +24,7 @@ IMM_OPT_FUSE_REDUCTIONS = 7
 IMM_OPT_ENCODE_AHEAD = 8
 IMM_OPT_TIMELINE = 9
 IMM_OPT_HOST_TAIL = 10
+IMM_OPT_QUEUE_AHEAD = 11
 IMM_HOST_TAIL_DEFAULT = 9
 IMM_HOST_TAIL_MAX = 10
 TIMELINE_NAMES = ["entry", "head_hashed", "front_launched", "reductions_launched", "rounds_launched", "first_message",

@@ -29,6 +29,17 @@ hipError_t front(hipStream_t stream, const int16_t* A, uint64_t countA, uint64_t
 hipError_t eq_build2(hipStream_t stream, const Point& ptA, int tA, uint64_t* outA, const Point& ptB, int tB,
                      uint64_t* outB, uint32_t* planesB);
 
+// The same vectors from points that the host hands over after the launch: the kernel waits, at most
+// `spin_limit` polls per word, until the words rx[0..tA), ry[0..tB) of `gate` (device-visible memory,
+// preset to kMailEmpty by the host) hold canonical elements.  kMailAbort in a needed word, or a wait that
+// runs out, makes the kernel end without writing.
+struct Gate {
+    uint64_t rx[IMM_MAX_ROUNDS];
+    uint64_t ry[IMM_MAX_ROUNDS];
+};
+hipError_t eq_build2_gated(hipStream_t stream, const Gate* gate, uint64_t spin_limit, int tA, uint64_t* outA, int tB,
+                           uint64_t* outB, uint32_t* planesB);
+
 // Geometry of a split reduction: how many partial vectors a launch writes.
 struct Split {
     uint32_t nsplit;      // number of partial vectors

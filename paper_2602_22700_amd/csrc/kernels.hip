@@ -1363,6 +1363,43 @@ __device__ __forceinline__ uint64_t mail_peek(const uint64_t* slot) {
     return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
+// The eq vectors of a proof whose points are not known yet when its kernels are queued: in a chain of
+// proofs the points come out of the transcript of the proof before, whose round loop the host is
+// still serving.  The kernel is queued behind that loop's kernel and waits (bounded) for the host to
+// write the points into `gate`: words rx[0..tA) and ry[0..tB), kMailEmpty until then.  Every word says
+// for itself whether it is there, so their order of arrival does not matter.  A word that is not a
+// canonical element when the wait ends (never written, or kMailAbort) makes every workgroup leave
+// without writing anything; the host, which then knows why, discards what the kernels behind compute.
+__global__ __launch_bounds__(kBlock) void eq_build2_gated_kernel(const Gate* __restrict__ gate, uint64_t spin_limit, int tA,
+                                                                 uint64_t* __restrict__ outA, int tB,
+                                                                 uint64_t* __restrict__ outB,
+                                                                 uint32_t* __restrict__ planesB) {
+    __shared__ Point ptA, ptB;
+    __shared__ int dead;
+    const uint32_t tid = threadIdx.x;
+    if (tid < 64) {  // lane i < 32 fetches rx[i], lane 32 + i fetches ry[i]
+        const uint32_t i = tid & 31;
+        const bool second = tid >= 32;
+        const bool need = (int)i < (second ? tB : tA);
+        const uint64_t* word = second ? &gate->ry[i] : &gate->rx[i];
+        uint64_t v = 0;
+        if (need) {
+            v = kMailEmpty;
+            for (uint64_t spin = 0; spin < spin_limit; ++spin) {
+                v = mail_peek(word);
+                if (v != kMailEmpty) break;
+                __builtin_amdgcn_s_sleep(4);
+            }
+        }
+        (second ? ptB : ptA).v[i] = v;
+        const int bad = __any(need && v >= gl::P);
+        if (tid == 0) dead = bad;
+    }
+    __syncthreads();
+    if (dead) return;
+    IMM_EQ_BUILD2_BODY(ptA, tA, outA, ptB, tB, outB, planesB, blockIdx.x);
+}
+
 // While the host hashes g_k, the device already prepares round k+1: after the fold with r_k the
 // entries are x + r_k dx, so each value g_{k+1}(t) is a quadratic c0 + c1 r_k + c2 r_k^2 whose
 // coefficients depend only on the tables as they are now.  The block computes the nine
@@ -1788,6 +1825,14 @@ hipError_t eq_build2(hipStream_t stream, const Point& ptA, int tA, uint64_t* out
     const uint64_t total = (1ull << tA) + (1ull << tB);
     hipLaunchKernelGGL(eq_build2_kernel, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, ptA,
                        tA, outA, ptB, tB, outB, planesB);
+    return hipGetLastError();
+}
+
+hipError_t eq_build2_gated(hipStream_t stream, const Gate* gate, uint64_t spin_limit, int tA, uint64_t* outA, int tB,
+                           uint64_t* outB, uint32_t* planesB) {
+    const uint64_t total = (1ull << tA) + (1ull << tB);
+    hipLaunchKernelGGL(eq_build2_gated_kernel, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, gate,
+                       spin_limit, tA, outA, tB, outB, planesB);
     return hipGetLastError();
 }
 

@@ -42,12 +42,23 @@ int fail_hip(hipError_t e, const char* what) {
         if (e_ != hipSuccess) return fail_hip(e_, #call);   \
     } while (0)
 
+// While kernels are queued that wait for this thread (the round loop of one proof with the kernels of
+// the next proof behind it), a buffer that has to grow must not be freed on the spot: the kernels in
+// flight may still use it, and hipFree waits for the device, which waits for this thread.  Buffers
+// that are outgrown meanwhile are parked here and freed once the stream has drained.
+static thread_local std::vector<void*>* g_parked = nullptr;
+
 // A device buffer that only grows.
 struct DevBuf {
     void* p = nullptr;
     size_t bytes = 0;
     int ensure(size_t need) {
         if (need <= bytes) return IMM_OK;
+        if (p && g_parked) {
+            g_parked->push_back(p);
+            p = nullptr;
+            bytes = 0;
+        }
         if (p) {
             hipError_t e = hipFree(p);
             p = nullptr;
@@ -145,7 +156,8 @@ struct Profiler {
 // Reply slots that the host writes and the round kernel polls: fine-grained device memory, reachable
 // from the host through the PCIe aperture when the whole device memory is mapped there.  Blocks are
 // handed from context to context and never given back to the runtime while the process lives.
-constexpr size_t kReplyWords = (size_t)k::kRoundsMaxJobs * IMM_MAX_ROUNDS;
+constexpr size_t kGateCount = 2;  // proofs whose points may be outstanding: the one after the current
+constexpr size_t kReplyWords = (size_t)k::kRoundsMaxJobs * IMM_MAX_ROUNDS + kGateCount * sizeof(k::Gate) / sizeof(uint64_t);
 static std::mutex g_reply_mutex;
 static std::vector<std::pair<int, uint64_t*>> g_reply_pool;  // (device, block)
 
@@ -191,6 +203,8 @@ struct imm_ctx {
     uint64_t* pinned = nullptr;  // host staging, 4 KiB
     imm::k::Mailbox* mailbox = nullptr;  // pinned + coherent, kRoundsMaxJobs of them: g_k out, r_k in
     uint64_t* replies = nullptr;         // host-writable device memory for r_k, or null (then the mailbox carries them)
+    imm::k::Gate* gates_pinned = nullptr; // behind the mailboxes: where the points of a proof queued ahead arrive
+    bool queue_ahead = true;             // IMM_OPT_QUEUE_AHEAD
     bool reply_in_device_memory = true;
     int transcript_mode = IMM_TRANSCRIPT_HOST;
     uint64_t spin_limit = 1ull << 21;    // device polls per round before giving up (about 2 us each)
@@ -248,19 +262,44 @@ static int fetch_words(imm_ctx* ctx, hipStream_t s, const uint64_t* dev, size_t 
 
 // eq vectors for the row point (tR coordinates) and the column point (tC); with `planes` the column
 // vector also in the byte-plane form the int8 reduction reads (ctx->eqy_planes).
+// With `gate` the points are not known yet: the kernel waits for them to arrive there (gate_open).
 static int build_eq(imm_ctx* ctx, hipStream_t s, const uint64_t* pr, int tR, const uint64_t* pc, int tC,
-                    bool planes = false) {
+                    bool planes = false, const k::Gate* gate = nullptr) {
     int rc;
     if ((rc = ctx->eqx.ensure(sizeof(uint64_t) << tR))) return rc;
     if ((rc = ctx->eqy.ensure(sizeof(uint64_t) << tC))) return rc;
     if (planes && (rc = ctx->eqy_planes.ensure(sizeof(uint64_t) << tC))) return rc;
-    k::Point a{}, b{};
-    for (int i = 0; i < tR; ++i) a.v[i] = pr[i];
-    for (int i = 0; i < tC; ++i) b.v[i] = pc[i];
+    uint32_t* planes_dev = planes ? static_cast<uint32_t*>(ctx->eqy_planes.p) : nullptr;
     if ((rc = ctx->prof.begin(IMM_K_EQ, s))) return rc;
-    IMM_HIP(k::eq_build2(s, a, tR, ctx->eqx.u64(), b, tC, ctx->eqy.u64(),
-                         planes ? static_cast<uint32_t*>(ctx->eqy_planes.p) : nullptr));
+    if (gate) {
+        IMM_HIP(k::eq_build2_gated(s, gate, ctx->spin_limit, tR, ctx->eqx.u64(), tC, ctx->eqy.u64(), planes_dev));
+    } else {
+        k::Point a{}, b{};
+        for (int i = 0; i < tR; ++i) a.v[i] = pr[i];
+        for (int i = 0; i < tC; ++i) b.v[i] = pc[i];
+        IMM_HIP(k::eq_build2(s, a, tR, ctx->eqx.u64(), b, tC, ctx->eqy.u64(), planes_dev));
+    }
     return ctx->prof.end(IMM_K_EQ, s);
+}
+
+// The gate of pipeline slot `slot`: in device memory that the host writes into where there is such
+// memory, else in pinned host memory.  Closed = every word kMailEmpty.
+static k::Gate* gate_of(imm_ctx* ctx, int slot) {
+    if (ctx->reply_in_device_memory && ctx->replies)
+        return reinterpret_cast<k::Gate*>(ctx->replies + (size_t)k::kRoundsMaxJobs * IMM_MAX_ROUNDS) + slot;
+    return ctx->gates_pinned + slot;
+}
+static void gate_fill(k::Gate* g, uint64_t value) {
+    volatile uint64_t* w = reinterpret_cast<volatile uint64_t*>(g);
+    for (size_t i = 0; i < sizeof(k::Gate) / sizeof(uint64_t); ++i) w[i] = value;
+    _mm_sfence();
+}
+static void gate_open(k::Gate* g, const uint64_t* rx, int mu, const uint64_t* ry, int nu) {
+    volatile uint64_t* wx = g->rx;
+    volatile uint64_t* wy = g->ry;
+    for (int i = 0; i < mu; ++i) wx[i] = rx[i];
+    for (int i = 0; i < nu; ++i) wy[i] = ry[i];
+    _mm_sfence();
 }
 
 // Whether the reduction of a table along its rows can read it as int8 (then the eq vector's byte planes are needed).
@@ -452,8 +491,10 @@ static int ahead_queue(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc* look,
 
 // look[0..look_count) are the proofs that follow this one on the same context in the same call:
 // their raw operands are widened while this proof and the ones between run.
+// With `gate` the proof before this one in a chain is not finished yet: the head of the transcript is
+// left out here, and the eq kernel waits at the gate for the points.
 static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_desc* look = nullptr,
-                        int look_count = 0) {
+                        int look_count = 0, const k::Gate* gate = nullptr) {
     const imm_matmul_desc& ds = *job.ds;
     const uint64_t m = ds.m, d = ds.d, n = ds.n;
     job.mu = hf::ceil_log2(m);
@@ -494,7 +535,7 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
     imm::DevBuf& encA = ctx->encA[ctx->set];
     imm::DevBuf& encB = ctx->encB[ctx->set];
     bool eq_done = false;
-    if (ctx->widen && ctx->fuse_reductions && !taken_over && dtA == IMM_I16 && (dtB == IMM_I8 || dtB == IMM_F64P)) {
+    if (!gate && ctx->widen && ctx->fuse_reductions && !taken_over && dtA == IMM_I16 && (dtB == IMM_I8 || dtB == IMM_F64P)) {
         // A raw, B raw or widened beforehand: the widening and the eq vectors (a0 + a1 + a2) go out as one launch
         const bool rawB = dtB == IMM_I8;
         job.tr.head(m, d, n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, job.mu, job.nu, job.rx, job.ry);
@@ -534,7 +575,9 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
         dtB = IMM_F64P;
     }
     // a0 + a2: the points from the transcript, and their eq vectors
-    if (!eq_done) {
+    if (gate) {
+        if ((rc = build_eq(ctx, s, nullptr, job.mu, nullptr, job.nu, wants_planes(dtB, n), gate))) return rc;
+    } else if (!eq_done) {
         job.tr.head(m, d, n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, job.mu, job.nu, job.rx, job.ry);
         ctx->mark(IMM_T_HEAD_HASHED);
         if ((rc = build_eq(ctx, s, job.rx, job.mu, job.ry, job.nu, wants_planes(dtB, n)))) return rc;
@@ -645,11 +688,17 @@ static int long_table_prefix(imm_ctx* ctx, hipStream_t s, Job& job) {
 // a5..a8 for up to kRoundsMaxJobs proofs at once: the round kernel (one workgroup per proof) runs
 // on the device while this thread hashes.  For every proof in turn the kernel posts g_k, the host
 // absorbs it, squeezes r_k and posts it back; independent proofs overlap their waits.
-static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, int count) {
-    k::Mailbox* mb = ctx->mailbox;
-    uint64_t* replies = ctx->reply_in_device_memory ? ctx->replies : nullptr;
+struct RoundsLaunch {
     k::RoundsJobs rj{};
     int max_rounds = 0;
+    int slot = 0;  // first of the `count` mailboxes (and reply rows, status words) that the launch uses
+};
+static int rounds_launch(imm_ctx* ctx, hipStream_t s, Job** jobs, int count, int slot, RoundsLaunch& rl) {
+    k::Mailbox* mb = ctx->mailbox + slot;
+    rl.slot = slot;
+    uint64_t* replies = ctx->reply_in_device_memory && ctx->replies ? ctx->replies + (size_t)slot * IMM_MAX_ROUNDS : nullptr;
+    k::RoundsJobs& rj = rl.rj;
+    int& max_rounds = rl.max_rounds;
     for (int p = 0; p < count; ++p) {
         rj.job[p].a = jobs[p]->a;
         rj.job[p].b = jobs[p]->b;
@@ -674,11 +723,21 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
         _mm_sfence();
     }
     int rc;
-    uint64_t* status_dev = ctx->words.u64() + k::kWordCount + 4;
+    uint64_t* status_dev = ctx->words.u64() + k::kWordCount + 4 + slot;
     if ((rc = ctx->prof.begin(IMM_K_ROUND, s))) return rc;
     IMM_HIP(k::rounds_mailbox(s, rj, count, mb, replies, ctx->spin_limit, status_dev));
     if ((rc = ctx->prof.end(IMM_K_ROUND, s))) return rc;
     ctx->mark(IMM_T_ROUNDS_LAUNCHED);
+    return IMM_OK;
+}
+
+// The host's side of the loop that rounds_launch started.  On failure the kernel's waits have been
+// released (abort values in every reply slot); the caller lets the stream drain.
+static int rounds_serve(imm_ctx* ctx, Job** jobs, int count, const RoundsLaunch& rl) {
+    k::Mailbox* mb = ctx->mailbox + rl.slot;
+    uint64_t* replies = ctx->reply_in_device_memory && ctx->replies ? ctx->replies + (size_t)rl.slot * IMM_MAX_ROUNDS : nullptr;
+    const k::RoundsJobs& rj = rl.rj;
+    const int max_rounds = rl.max_rounds;
     bool ok = true, bad_tables = false;
     // tables of the proofs whose last rounds the host computes (filled when the device hands them over)
     std::vector<uint64_t> tail((size_t)count * 2 << k::kTailMaxLog2);
@@ -753,7 +812,6 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
                 __atomic_store_n(&mb[p].r[t], k::kMailAbort, __ATOMIC_RELEASE);
                 if (replies) reply_store(replies + (size_t)p * IMM_MAX_ROUNDS + t, k::kMailAbort);
             }
-        IMM_HIP(hipStreamSynchronize(s));
         g_last_error = bad_tables ? "the reductions did not deliver canonical field elements (a hand-over between workgroups ran out)"
                                   : "round kernel and host transcript lost contact (mailbox wait ran out)";
         return IMM_E_HIP;
@@ -762,6 +820,15 @@ static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, 
     // and tables, every result is already on the host, and whatever is launched next on this
     // stream is ordered behind the kernel's last instructions anyway.
     return IMM_OK;
+}
+
+static int rounds_with_host_transcript(imm_ctx* ctx, hipStream_t s, Job** jobs, int count) {
+    RoundsLaunch rl;
+    int rc = rounds_launch(ctx, s, jobs, count, 0, rl);
+    if (rc) return rc;
+    rc = rounds_serve(ctx, jobs, count, rl);
+    if (rc) (void)hipStreamSynchronize(s);
+    return rc;
 }
 
 // a5..a8 in one launch that also hashes the transcript on the device; one copy at the end brings
@@ -847,6 +914,113 @@ static int prove_one(imm_ctx* ctx, hipStream_t s, const imm_matmul_desc& ds, uin
     return ctx->prof.mask ? ctx->prof.flush() : IMM_OK;
 }
 
+// A chain of proofs (each starts from the state the one before it leaves) with the kernels of proof
+// p + 1 queued while the host still serves the round loop of proof p.  The state that proof p + 1
+// starts from is not known then, so its eq kernel is launched without the points and waits for them at
+// a gate; everything behind it in the stream (reductions, round kernel) needs no value from the host
+// to be launched.  When proof p is finished the host hashes the head of proof p + 1 and writes the
+// points through the gate: the device goes on within a microsecond or two, where a launch after the
+// fact costs the hashing, the launch calls and the start of a kernel on an idle queue (about 10 us per
+// proof).  Proofs that the round kernel does not take (no rounds, very long tables) are proven the
+// plain way, with nothing queued across them.
+static bool queueable(const imm_matmul_desc& ds) {
+    const int delta = hf::ceil_log2(ds.d);
+    return delta >= 1 && (1ull << delta) <= k::kRoundsMaxL;
+}
+
+static int prove_chain(imm_ctx* ctx, hipStream_t s, int count, const imm_matmul_desc* descs, uint8_t state[32],
+                       imm_proof* outs, uint8_t* states_out) {
+    int rc;
+    uint64_t Dmax = 1;
+    for (int p = 0; p < count; ++p) Dmax = std::max<uint64_t>(Dmax, uint64_t(1) << hf::ceil_log2(descs[p].d));
+    if ((rc = ctx->a.ensure(sizeof(uint64_t) * Dmax))) return rc;
+    if ((rc = ctx->b.ensure(sizeof(uint64_t) * Dmax))) return rc;
+    if ((rc = ctx->words.ensure(sizeof(uint64_t) * kWordsDev))) return rc;
+
+    std::vector<void*> parked;
+    struct Parking {  // buffers outgrown while kernels are queued are freed when the stream has drained
+        std::vector<void*>& list;
+        hipStream_t s;
+        explicit Parking(std::vector<void*>& l, hipStream_t st) : list(l), s(st) { g_parked = &list; }
+        ~Parking() {
+            g_parked = nullptr;
+            if (list.empty()) return;
+            (void)hipStreamSynchronize(s);
+            for (void* q : list) (void)hipFree(q);
+        }
+    } parking(parked, s);
+
+    Job job[2] = {Job(state), Job(state)};
+    RoundsLaunch rl[2];
+    bool in_loop[2] = {false, false};  // its round kernel is launched and waits to be served
+    auto set_up = [&](int p, int sl) {
+        job[sl] = Job(state);
+        job[sl].ds = &descs[p];
+        job[sl].out = &outs[p];
+        job[sl].a = ctx->a.u64();
+        job[sl].b = ctx->b.u64();
+    };
+    // proof p from the known state: plain launch; its round loop is left to be served if the kernel takes it
+    auto start_plain = [&](int p, int sl) -> int {
+        set_up(p, sl);
+        int r;
+        if ((r = stream_phase(ctx, s, job[sl], descs + p + 1, count - p - 1))) return r;
+        in_loop[sl] = queueable(descs[p]);
+        if (in_loop[sl]) {
+            Job* one = &job[sl];
+            return rounds_launch(ctx, s, &one, 1, sl, rl[sl]);
+        }
+        return finish_one(ctx, s, job[sl]);
+    };
+    auto give_up = [&](int r) -> int {
+        // release whatever waits for this thread, in both slots, then let everything drain
+        for (int sl = 0; sl < 2; ++sl) {
+            gate_fill(gate_of(ctx, sl), k::kMailAbort);
+            uint64_t* replies = ctx->reply_in_device_memory && ctx->replies ? ctx->replies + (size_t)sl * IMM_MAX_ROUNDS : nullptr;
+            for (int t = 0; t < IMM_MAX_ROUNDS; ++t) {
+                __atomic_store_n(&ctx->mailbox[sl].r[t], k::kMailAbort, __ATOMIC_RELEASE);
+                if (replies) reply_store(replies + t, k::kMailAbort);
+            }
+        }
+        (void)hipStreamSynchronize(s);
+        (void)ahead_drop(ctx);
+        return r;
+    };
+
+    if ((rc = start_plain(0, 0))) return give_up(rc);
+    for (int p = 0; p < count; ++p) {
+        const int sl = p & 1, nsl = sl ^ 1;
+        bool queued = false;
+        k::Gate* gate = gate_of(ctx, nsl);
+        if (in_loop[sl] && p + 1 < count && queueable(descs[p + 1])) {
+            set_up(p + 1, nsl);
+            gate_fill(gate, k::kMailEmpty);
+            if ((rc = stream_phase(ctx, s, job[nsl], descs + p + 2, count - p - 2, gate))) return give_up(rc);
+            Job* one = &job[nsl];
+            if ((rc = rounds_launch(ctx, s, &one, 1, nsl, rl[nsl]))) return give_up(rc);
+            in_loop[nsl] = true;
+            queued = true;
+        }
+        if (in_loop[sl]) {
+            Job* one = &job[sl];
+            if ((rc = rounds_serve(ctx, &one, 1, rl[sl]))) return give_up(rc);
+            in_loop[sl] = false;
+        }
+        std::memcpy(state, job[sl].tr.s, 32);
+        if (states_out) std::memcpy(states_out + 32 * (size_t)p, state, 32);
+        if (queued) {
+            Job& jn = job[nsl];
+            const imm_matmul_desc& ds = descs[p + 1];
+            jn.tr = Transcript(state);
+            jn.tr.head(ds.m, ds.d, ds.n, ds.com->A.digest, ds.com->B.digest, ds.com->C.digest, jn.mu, jn.nu, jn.rx, jn.ry);
+            gate_open(gate, jn.rx, jn.mu, jn.ry, jn.nu);
+        } else if (p + 1 < count) {
+            if ((rc = start_plain(p + 1, nsl))) return give_up(rc);
+        }
+    }
+    return IMM_OK;
+}
+
 // Independent proofs (every one starts from `start`): the streaming phases are queued back to
 // back, each into its own pair of tables, and the round loops of a whole group then run in one
 // launch.  A statement that needs a different path (no rounds, very long tables) is proven on its
@@ -930,13 +1104,15 @@ extern "C" int imm_ctx_create(imm_ctx** out, int device, size_t scratch_bytes) {
             delete ctx;
             return fail_hip(e, "hipHostMalloc");
         }
-        e = hipHostMalloc(reinterpret_cast<void**>(&ctx->mailbox), sizeof(k::Mailbox) * k::kRoundsMaxJobs,
+        e = hipHostMalloc(reinterpret_cast<void**>(&ctx->mailbox),
+                          sizeof(k::Mailbox) * k::kRoundsMaxJobs + sizeof(k::Gate) * kGateCount,
                           hipHostMallocMapped | hipHostMallocCoherent);
         if (e != hipSuccess) {
             (void)hipHostFree(ctx->pinned);
             delete ctx;
             return fail_hip(e, "hipHostMalloc(mailbox)");
         }
+        ctx->gates_pinned = reinterpret_cast<k::Gate*>(ctx->mailbox + k::kRoundsMaxJobs);
         ctx->replies = reply_block_take(device);  // may be null: then the mailbox carries the challenges
         if (int rc = static_scratch_prepare(device)) {
             (void)hipHostFree(ctx->pinned);
@@ -993,6 +1169,7 @@ extern "C" int imm_ctx_set_option(imm_ctx* ctx, int option, int64_t value) {
     case IMM_OPT_FUSE_REDUCTIONS: ctx->fuse_reductions = value != 0; return IMM_OK;
     case IMM_OPT_ENCODE_AHEAD: ctx->encode_ahead = value != 0; return IMM_OK;
     case IMM_OPT_TIMELINE: ctx->timeline = value != 0; ctx->marks = 0; return IMM_OK;
+    case IMM_OPT_QUEUE_AHEAD: ctx->queue_ahead = value != 0; return IMM_OK;
     case IMM_OPT_HOST_TAIL:
         if (value < 0 || value > k::kTailMaxLog2) return IMM_E_SHAPE;
         ctx->host_tail = (int)value;
@@ -1138,6 +1315,13 @@ extern "C" int imm_sumcheck_matmul_prove_batch(imm_ctx* ctx, void* stream, int c
             if (rc) return rc;
             if (states_out) std::memcpy(states_out, states.data(), states.size());
             std::memcpy(transcript_state, states.data() + 32 * (size_t)(count - 1), 32);
+            return IMM_OK;
+        }
+        if (chained && count > 1 && ctx->queue_ahead && ctx->transcript_mode == IMM_TRANSCRIPT_HOST && !ctx->debug &&
+            !ctx->timeline && !ctx->prof.mask) {
+            int rc = prove_chain(ctx, s, count, descs, cur, outs_host, states_out);
+            if (rc) return rc;
+            std::memcpy(transcript_state, cur, 32);
             return IMM_OK;
         }
         for (int t = 0; t < count; ++t) {

@@ -508,6 +508,55 @@ def test_host_transcript_bounded_waits(torch, oracle_fast):
     c.close()
 
 
+def test_chain_with_the_next_proof_queued_ahead_or_not(torch, oracle_fast):
+    """In a chained batch the kernels of proof p + 1 are queued while the host still serves proof p's
+    round loop, its eq kernel waiting on the device for the points.  Same proofs and states with that
+    switched off, in every execution mode, for a chain that mixes statements the round kernel takes
+    with ones it does not (a single shared index; tables longer than one workgroup's limit), buffers
+    that have to grow while kernels are queued, and after a failure with kernels queued behind it."""
+    rng = np.random.default_rng(515)
+    shapes = [(4, 64, 8), (3, 700, 5), (2, 1, 3), (5, 4096, 16), (2, 65539, 3), (6, 33, 40), (3, 2048, 64), (4, 8, 4)]
+    items, oracle_items = [], []
+    for (m, d, n) in shapes:
+        A = rng.integers(-2**15, 2**15, size=(m, d), dtype=np.int16)
+        B = rng.integers(-128, 128, size=(d, n), dtype=np.int8)
+        C = oracle_fast.matmul(A, B)
+        com = imm.imm_commit_matmul(A, B, C, m, d, n)
+        oracle_items.append((A, B, C, com.digests()))
+        items.append((dev(torch, A), dev(torch, B), com))
+    want, want_states = oracle_fast.prove_chain(oracle_items, chained=True)
+    want_words = [ref.proof_words(p) for p in want]
+    c = imm.Context(0)   # a fresh context: its buffers grow as the chain goes
+    for ahead in (1, 0):
+        c.imm_ctx_set_option(imm.IMM_OPT_QUEUE_AHEAD, ahead)
+        for widen in (1, 0):
+            c.imm_ctx_set_option(imm.IMM_OPT_WIDEN, widen)
+            for tail in (imm.IMM_HOST_TAIL_DEFAULT, 0):
+                c.imm_ctx_set_option(imm.IMM_OPT_HOST_TAIL, tail)
+                for _ in range(2):
+                    got, states, final = c.imm_sumcheck_matmul_prove_batch(items, True, ref.FS_INIT)
+                    assert [p.words() for p in got] == want_words, (ahead, widen, tail)
+                    assert states == want_states and final == want_states[-1], (ahead, widen, tail)
+    c.imm_ctx_set_option(imm.IMM_OPT_QUEUE_AHEAD, 1)
+    c.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
+    c.imm_ctx_set_option(imm.IMM_OPT_HOST_TAIL, imm.IMM_HOST_TAIL_DEFAULT)
+    pre = [(A, c.imm_encode(B), com) for (A, B, com) in items]
+    got, states, final = c.imm_sumcheck_matmul_prove_batch(pre, True, ref.FS_INIT)
+    assert [p.words() for p in got] == want_words and final == want_states[-1]
+    # a wait that runs out with the next proof's kernels queued: error, everything drains, and the context works on
+    c.imm_ctx_set_option(imm.IMM_OPT_SPIN_LIMIT, 0)
+    c.imm_ctx_set_option(imm.IMM_OPT_HOST_WAIT_MS, 50)
+    with pytest.raises(imm.ImmError) as e:
+        c.imm_sumcheck_matmul_prove_batch(items, True, ref.FS_INIT)
+    assert e.value.code == -5
+    torch.cuda.synchronize()
+    c.imm_ctx_set_option(imm.IMM_OPT_SPIN_LIMIT, 1 << 21)
+    c.imm_ctx_set_option(imm.IMM_OPT_HOST_WAIT_MS, 30000)
+    got, states, final = c.imm_sumcheck_matmul_prove_batch(items, True, ref.FS_INIT)
+    assert [p.words() for p in got] == want_words and states == want_states
+    c.close()
+
+
 def test_operands_of_the_next_proof_widened_ahead_or_not(torch, oracle_fast):
     """In a sequence of proofs the next proof's raw operands are widened on a second stream while the
     current proof's rounds run.  Same proofs and states with that switched off; with operands that
