@@ -543,6 +543,14 @@ def test_chain_with_the_next_proof_queued_ahead_or_not(torch, oracle_fast):
     pre = [(A, c.imm_encode(B), com) for (A, B, com) in items]
     got, states, final = c.imm_sumcheck_matmul_prove_batch(pre, True, ref.FS_INIT)
     assert [p.words() for p in got] == want_words and final == want_states[-1]
+    # challenges and points through pinned host memory instead of host-written device memory
+    c.imm_ctx_set_option(imm.IMM_OPT_REPLY_IN_DEVICE_MEMORY, 0)
+    for widen in (1, 0):
+        c.imm_ctx_set_option(imm.IMM_OPT_WIDEN, widen)
+        got, states, final = c.imm_sumcheck_matmul_prove_batch(items, True, ref.FS_INIT)
+        assert [p.words() for p in got] == want_words and states == want_states, widen
+    c.imm_ctx_set_option(imm.IMM_OPT_REPLY_IN_DEVICE_MEMORY, 1)
+    c.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
     # a wait that runs out with the next proof's kernels queued: error, everything drains, and the context works on
     c.imm_ctx_set_option(imm.IMM_OPT_SPIN_LIMIT, 0)
     c.imm_ctx_set_option(imm.IMM_OPT_HOST_WAIT_MS, 50)
