@@ -1655,32 +1655,11 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs
         return;
     }
 
-    // round 1: plain evaluation of the tables as they are
-    Triple g = {0, 0, 0};
-    {
-        const uint64_t h = L >> 1;
-        int bad = 0;
-        for (uint64_t i = tid; i < h; i += kRoundsBlock) {
-            const uint64_t x0 = a[i], x1 = a[i + h], y0 = b[i], y1 = b[i + h];
-            bad |= (x0 >= gl::P) | (x1 >= gl::P) | (y0 >= gl::P) | (y1 >= gl::P);
-            pair_eval(g, x0, x1, y0, y1);
-        }
-        if (__syncthreads_or(bad)) {  // the reductions did not deliver canonical field elements
-            if (tid == 0) {
-                for (int t = 0; t < 3; ++t) mail_post(&mb->g[0][t], kMailFail);
-                status[0] = 1;
-            }
-            return;
-        }
-    }
-    g = rounds_block_sum(g, lds3);
-    if (tid == 0) {
-        mail_post(&mb->g[0][0], g.g0);
-        mail_post(&mb->g[0][1], g.g1);
-        mail_post(&mb->g[0][2], g.g2);
-    }
-
-    // coefficients of g_2(t) as polynomials in r_1, from the tables as they are
+    // Longer tables (up to kRoundsMaxL entries, 16-byte aligned) start out in global memory, which for one
+    // workgroup means: every trip to memory costs a microsecond or two whatever it fetches.  So a thread
+    // asks for everything a trip needs at once, as 16-byte accesses (two neighbouring groups of four
+    // entries per table), before it computes or stores anything, and round 1 and the coefficients of
+    // round 2 come out of one pass over the tables.
     auto clear = [](Quad3& qd) {
 #pragma unroll
         for (int t = 0; t < 3; ++t) qd.c[t][0] = qd.c[t][1] = qd.c[t][2] = 0;
@@ -1696,20 +1675,52 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs
     auto waves_for = [](uint64_t items) {
         return (uint32_t)((items + 63) / 64 < kRoundsWaves ? (items + 63) / 64 : kRoundsWaves);
     };
-    if (L >= 4) {
-        const uint64_t h = L >> 1, q = L >> 2;
+    auto pair_at = [](const uint64_t* p) { return *reinterpret_cast<const v2u64*>(p); };
+    auto pair_to = [](uint64_t* p, uint64_t x, uint64_t y) {
+        v2u64 v;
+        v.x = x;
+        v.y = y;
+        *reinterpret_cast<v2u64*>(p) = v;
+    };
+
+    // The coefficients of g_2(t) as polynomials in r_1: a thread takes the groups i, i + 1 (entries i,
+    // i + q, i + h, i + h + q of each table).  Round 1 needs no pass of its own: g_1(r) = g_2(0) + g_2(1)
+    // as polynomials in r, so its three values are those two quadratics at r = 0, 1, 2.
+    {
+        const uint64_t h = L >> 1, q = L >> 2;  // L > 4096: q is a multiple of 1024
+        int bad = 0;
         Quad3 qd;
         clear(qd);
-        for (uint64_t i = tid; i < q; i += kRoundsBlock)
-            accumulate(qd, a[i], a[i + q], a[i + h], a[i + h + q], b[i], b[i + q], b[i + h], b[i + h + q]);
-        quad_block_sum(qd, waves_for(q), red, fin9);
+        for (uint64_t i = 2 * (uint64_t)tid; i < q; i += 2 * kRoundsBlock) {
+            const v2u64 x0 = pair_at(a + i), x1 = pair_at(a + i + q), x2 = pair_at(a + i + h), x3 = pair_at(a + i + h + q);
+            const v2u64 y0 = pair_at(b + i), y1 = pair_at(b + i + q), y2 = pair_at(b + i + h), y3 = pair_at(b + i + h + q);
+            __builtin_amdgcn_sched_barrier(0);
+            bad |= (x0.x >= gl::P) | (x1.x >= gl::P) | (x2.x >= gl::P) | (x3.x >= gl::P) | (y0.x >= gl::P) | (y1.x >= gl::P) |
+                   (y2.x >= gl::P) | (y3.x >= gl::P) | (x0.y >= gl::P) | (x1.y >= gl::P) | (x2.y >= gl::P) | (x3.y >= gl::P) |
+                   (y0.y >= gl::P) | (y1.y >= gl::P) | (y2.y >= gl::P) | (y3.y >= gl::P);
+            accumulate(qd, x0.x, x1.x, x2.x, x3.x, y0.x, y1.x, y2.x, y3.x);
+            accumulate(qd, x0.y, x1.y, x2.y, x3.y, y0.y, y1.y, y2.y, y3.y);
+        }
+        if (__syncthreads_or(bad)) {  // the reductions did not deliver canonical field elements
+            if (tid == 0) {
+                for (int t = 0; t < 3; ++t) mail_post(&mb->g[0][t], kMailFail);
+                status[0] = 1;
+            }
+            return;
+        }
+        quad_block_sum(qd, waves_for(q / 2), red, fin9);
+        if (tid < 3) {  // g_1(tid) = sum over t = 0, 1 of c0 + tid c1 + tid^2 c2
+            const uint64_t c0 = gl::add(fin9[0], fin9[3]), c1 = gl::add(fin9[1], fin9[4]), c2 = gl::add(fin9[2], fin9[5]);
+            const uint64_t r = tid;
+            mail_post(&mb->g[0][tid], gl::add(c0, gl::mul(r, gl::add(c1, gl::mul(r, c2)))));
+        }
     }
 
     for (int kk = 0; kk < rounds; ++kk) {
         const uint64_t h = L >> 1;
-        // fin9 holds the coefficients of g_{kk+2} (if there is such a round).  Wave 0: lane 0 waits for
-        // r_{kk+1}; lanes 0..2 then evaluate one value each, g_{kk+2}(t) = c0 + r (c1 + r c2), and post
-        // it to the host before the tables are touched.
+        // fin9 holds the coefficients of g_{kk+2}.  Wave 0: lane 0 waits for r_{kk+1}; lanes 0..2 then
+        // evaluate one value each, g_{kk+2}(t) = c0 + r (c1 + r c2), and post it to the host before the
+        // tables are touched.
         if (tid < 64) {
             uint64_t r = kMailEmpty;
             if (tid == 0)
@@ -1718,7 +1729,7 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs
                     if (r != kMailEmpty) break;
                 }
             r = __shfl(r, 0, 64);
-            if (r < gl::P && L >= 4 && tid < 3)
+            if (r < gl::P && tid < 3)
                 mail_post(&mb->g[kk + 1][tid],
                           gl::add(fin9[3 * tid], gl::mul(r, gl::add(fin9[3 * tid + 1], gl::mul(r, fin9[3 * tid + 2])))));
             if (tid == 0) r_shared = r;
@@ -1734,35 +1745,38 @@ __global__ __launch_bounds__(kRoundsBlock) void rounds_mailbox_kernel(RoundsJobs
                           lds3, &r_shared);
             return;
         }
-        // Bind the leading variable, x[j] <- x[j] + r (x[j + h] - x[j]), in place.  If another round with
-        // prepared coefficients follows (h >= 4), a thread folds exactly the four entries of each table
-        // that its share of the next coefficients is made of, and accumulates them right away: one
-        // pass over the tables and one reduction per round, while the host hashes.
-        if (h >= 4) {
+        // Bind the leading variable, x[j] <- x[j] + r (x[j + h] - x[j]), in place: a thread folds exactly
+        // the four entries of each table (of two neighbouring groups) that its share of the next
+        // coefficients is made of, and accumulates them right away: one pass over the tables and one
+        // reduction per round, while the host hashes.  h > 4096 here, so there is always such a round.
+        {
             const uint64_t h2 = h >> 1, q2 = h >> 2;
             Quad3 qd;
             clear(qd);
-            for (uint64_t i = tid; i < q2; i += kRoundsBlock) {
+            for (uint64_t i = 2 * (uint64_t)tid; i < q2; i += 2 * kRoundsBlock) {
                 const uint64_t j[4] = {i, i + q2, i + h2, i + h2 + q2};
-                uint64_t fa[4], fb[4];
+                v2u64 xl[4], xu[4], yl[4], yu[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const uint64_t x = a[j[e]], y = b[j[e]];
-                    fa[e] = gl::add(x, gl::mul(r, gl::sub(a[j[e] + h], x)));
-                    fb[e] = gl::add(y, gl::mul(r, gl::sub(b[j[e] + h], y)));
-                    a[j[e]] = fa[e];
-                    b[j[e]] = fb[e];
+                    xl[e] = pair_at(a + j[e]);
+                    xu[e] = pair_at(a + j[e] + h);
+                    yl[e] = pair_at(b + j[e]);
+                    yu[e] = pair_at(b + j[e] + h);
                 }
-                accumulate(qd, fa[0], fa[1], fa[2], fa[3], fb[0], fb[1], fb[2], fb[3]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    xl[e].x = gl::add(xl[e].x, gl::mul(r, gl::sub(xu[e].x, xl[e].x)));
+                    xl[e].y = gl::add(xl[e].y, gl::mul(r, gl::sub(xu[e].y, xl[e].y)));
+                    yl[e].x = gl::add(yl[e].x, gl::mul(r, gl::sub(yu[e].x, yl[e].x)));
+                    yl[e].y = gl::add(yl[e].y, gl::mul(r, gl::sub(yu[e].y, yl[e].y)));
+                    pair_to(a + j[e], xl[e].x, xl[e].y);
+                    pair_to(b + j[e], yl[e].x, yl[e].y);
+                }
+                accumulate(qd, xl[0].x, xl[1].x, xl[2].x, xl[3].x, yl[0].x, yl[1].x, yl[2].x, yl[3].x);
+                accumulate(qd, xl[0].y, xl[1].y, xl[2].y, xl[3].y, yl[0].y, yl[1].y, yl[2].y, yl[3].y);
             }
-            quad_block_sum(qd, waves_for(q2), red, fin9);  // its barriers also publish the folded entries
-        } else {
-            for (uint64_t i = tid; i < h; i += kRoundsBlock) {
-                const uint64_t x = a[i], y = b[i];
-                a[i] = gl::add(x, gl::mul(r, gl::sub(a[i + h], x)));
-                b[i] = gl::add(y, gl::mul(r, gl::sub(b[i + h], y)));
-            }
-            __syncthreads();
+            quad_block_sum(qd, waves_for(q2 / 2), red, fin9);  // its barriers also publish the folded entries
         }
         L = h;
     }

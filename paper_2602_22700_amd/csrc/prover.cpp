@@ -704,6 +704,11 @@ static int rounds_launch(imm_ctx* ctx, hipStream_t s, Job** jobs, int count, int
         rj.job[p].b = jobs[p]->b;
         rj.job[p].L = jobs[p]->L;
         rj.job[p].rounds = jobs[p]->delta - jobs[p]->kk;
+        // the kernel reads tables that do not fit into LDS with 16-byte accesses; they are buffers of the context
+        if ((reinterpret_cast<uintptr_t>(jobs[p]->a) | reinterpret_cast<uintptr_t>(jobs[p]->b)) % 16 != 0) {
+            g_last_error = "round tables are not 16-byte aligned";
+            return IMM_E_STATE;
+        }
         // The last rounds, on tables of at most 2^host_tail entries, are the host's: it computes them in
         // less time than one message takes to the device and back (the kernel needs two rounds of its own).
         // One host thread serves the proofs of a launch in turn while their workgroups work side by side,
