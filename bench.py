@@ -266,6 +266,12 @@ def main():
     ms_pre = timed_runs(torch, batch_pre, args.steps, 2)
     pre_proofs = batch_pre.proofs
     ms_pre_default = with_default_tail(batch_pre)
+    # ... and the activations read as they are stored (no widening at all inside the call)
+    ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 0)
+    ms_pre_raw = timed_runs(torch, batch_pre, args.steps, 2)
+    pre_raw_proofs = batch_pre.proofs
+    ms_pre_raw_default = with_default_tail(batch_pre)
+    ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 0 if args.narrow else 1)
     del items_pre, batch_pre
 
     ms_narrow, narrow_proofs, ms_narrow_default = None, None, None
@@ -292,12 +298,14 @@ def main():
                    "includes": ("eq, narrow-read reduce A+B, rounds, hashing" if args.narrow
                                 else "encode A+B, eq, reduce A+B, rounds, hashing")},
         "prove_ms_weights_preencoded": round(ms_pre, 4),
+        "prove_ms_weights_preencoded_activations_read_raw": round(ms_pre_raw, 4),
         "prove_ms_narrow_read": round(ms_narrow, 4) if ms_narrow is not None else None,
         "rounds": "every round of the sumcheck on the device (IMM_OPT_HOST_TAIL = 0) in value, in the prove_ms_* beside it, in "
                   "kernels and in other_workloads; library_default holds the same measurements with the library's default, in "
                   "which the calling thread, which hashes every round's message anyway, finishes the rounds on tables of at "
                   "most 512 entries",
         "library_default": {"prove_ms": round(ms_default, 4), "prove_ms_weights_preencoded": round(ms_pre_default, 4),
+                            "prove_ms_weights_preencoded_activations_read_raw": round(ms_pre_raw_default, 4),
                             "prove_ms_narrow_read": round(ms_narrow_default, 4) if ms_narrow_default is not None else None},
         "kernels": kernels,
         "roofline": {"bound": "hbm",
@@ -572,6 +580,7 @@ def main():
         want, _ = oracle_fast.prove_chain(oracle_items, chained, check=False)   # also warms the library
         same = [p.words() for p in proofs] == [ref.proof_words(p) for p in want] and \
                [p.words() for p in pre_proofs] == [ref.proof_words(p) for p in want] and \
+               [p.words() for p in pre_raw_proofs] == [ref.proof_words(p) for p in want] and \
                (narrow_proofs is None or [p.words() for p in narrow_proofs] == [ref.proof_words(p) for p in want])
         n_cpu, t_cpu0 = 0, time.perf_counter()
         while True:

@@ -590,9 +590,12 @@ static int stream_phase(imm_ctx* ctx, hipStream_t s, Job& job, const imm_matmul_
     // workgroup of A's reduction that finishes a block of columns last sums its partial vectors, so no
     // launch stands between the reductions and the round kernel.
     bool both = false;
-    // (Beside a widened table of B nothing is gained: both stream from HBM at its rate, so A's bytes take
-    // their time either way, and the hand-over costs more than the launch it saves.)
-    if (ctx->fuse_reductions && dtB == IMM_I8 && (dtA == IMM_I16 || dtA == IMM_F64P)) {
+    // Raw int16 activations also share the launch of weights that the caller widened beforehand
+    // (narrow-read mode with pre-encoded B): A's 2 bytes per entry are a thirtieth of the launch's traffic.
+    // (A widened table of A beside a widened B gains nothing: both stream from HBM at its rate, so A's
+    // bytes take their time either way, and the hand-over costs more than the launch it saves.)
+    if (ctx->fuse_reductions && ((dtB == IMM_I8 && (dtA == IMM_I16 || dtA == IMM_F64P)) ||
+                                 (dtB == IMM_F64P && dtA == IMM_I16))) {
         const size_t elemA = dtA == IMM_F64P ? 8 : 2, elemB = dtB == IMM_F64P ? 8 : 1;
         const k::Split spA = k::plan_over_rows_beside(m, d, elemA, d * n * elemB), spB = k::plan_over_cols(d, n, dtB);
         const bool directB = spB.nsplit == 1;

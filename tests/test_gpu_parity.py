@@ -192,6 +192,11 @@ def check_proof(torch, ctx, oracle_fast, A, B, C=None, state=ref.FS_INIT, interm
     Af, Bf = ctx.imm_encode(Ad), ctx.imm_encode(Bd)
     got3, s3 = ctx.imm_sumcheck_matmul_prove(Af, Bf, com, state)
     assert got3.words() == got.words() and s3 == s_got
+    # weights widened beforehand, activations read as they are stored
+    ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 0)
+    got6, s6 = ctx.imm_sumcheck_matmul_prove(Ad, Bf, com, state)
+    ctx.imm_ctx_set_option(imm.IMM_OPT_WIDEN, 1)
+    assert got6.words() == got.words() and s6 == s_got
     # wherever the round kernel hands its tables to the host (never, after all but one round, late), the same bytes
     try:
         for t in (0, 1, 3, 6, imm.IMM_HOST_TAIL_MAX):
